@@ -1,0 +1,78 @@
+/*
+ * Single-kernel entry points of libstage, used to check each kernel of the stage step against
+ * the CPU oracle on its own.  Same conventions as stage.h: device pointers, caller-owned
+ * buffers, enqueue-only on the given hipStream_t, int status (STAGE_OK / STAGE_ERR_ARG /
+ * STAGE_ERR_DEVICE).  dtype: 0 float, 1 bf16.  Argument checks happen on the host before any
+ * launch.  The operations are the steps of one decoder layer's forward and backward pass and of
+ * the optimizer update that the paper's training iteration consists of (Section 1: forward pass,
+ * backward pass, optimizer update); the formulas are stated with each function.
+ */
+#ifndef STAGE_OPS_H
+#define STAGE_OPS_H
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] (op)= sum_k A(m,k) B(k,n) (+ bias[n]) (+ R[m,n]).
+ * transA 0: A stored [M,K] row-major, lda its row stride; 1: stored [K,M].
+ * transB 0: B stored [K,N]; 1: stored [N,K].  c_f32_accum 0: C has `dtype`, overwritten;
+ * 1: C is float and the product is added to it.  bias/resid may be NULL.  batch >= 1 with element
+ * strides sA, sB, sC (sC also for resid), sBias.  kseg > 0: K is cut in segments of kseg and segment
+ * s reads B from B + s*segB.  impl: 0 automatic, 1 the plain fp32-FMA kernel, 2 the bf16 MFMA
+ * kernel (STAGE_ERR_ARG if the shape/alignment is not supported by it). */
+int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
+                  const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
+                  const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,
+                  int64_t sBias, int32_t kseg, int64_t segB, int32_t impl);
+
+/* kind 0: LayerNorm n = (x-mean)/sqrt(var+eps)*g + b (biased variance), saves rstd[T], mean[T].
+ * kind 1: RMSNorm n = x/sqrt(mean(x^2)+eps)*g, saves rstd[T].  x, n: [T,H]. */
+int stage_op_norm_fwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* x, const void* g,
+                      const void* b, float eps, void* n, float* rstd, float* mean);
+/* dx = (dres ? dres : 0) + J^T dn; dg_part/db_part: float[nblk,H] per-row-block partial sums of
+ * dn*xhat and dn (db_part NULL for RMSNorm); nblk <= T. */
+int stage_op_norm_bwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* dn, const void* x,
+                      const void* g, const float* rstd, const float* mean, const void* dres, void* dx,
+                      float* dg_part, float* db_part, int32_t nblk);
+
+/* In-place rotation of adjacent pairs (2i,2i+1) of every d-wide head in a[T,ncols] (row stride ld)
+ * by sign * (t mod S) * base^(-2i/d).  table: float[S, d/2, 2] scratch that receives (cos, sin). */
+int stage_op_rope(void* stream, int32_t dtype, int32_t T, int32_t S, int32_t ncols, int32_t d, void* a, int64_t ld,
+                  float base, float sign, float* table);
+
+/* GELU(z) = z*Phi(z) (erf form) and its derivative; SwiGLU a = silu(gate)*up with gu = [gate | up] [T,2F]. */
+int stage_op_gelu(void* stream, int32_t dtype, int64_t n, const void* z, const void* da, void* out, int32_t backward);
+int stage_op_swiglu(void* stream, int32_t dtype, int32_t T, int32_t F, const void* gu, const void* da, void* out,
+                    int32_t backward);
+
+/* Causal softmax attention per (sequence, head): o_i = sum_{j<=i} softmax_j(q_i.k_j/sqrt(d)) v_j.
+ * q, k, v: first elements of [mb*S, nh*d] blocks with row stride ld; o row stride ldo;
+ * lse: float[mb,nh,S] = log sum_j exp(s_ij).  impl: 0 auto, 1 wave-per-row kernel, 2 MFMA kernel. */
+int stage_op_attention_fwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                           const void* k, const void* v, int64_t ld, void* o, int64_t ldo, float* lse, int32_t impl);
+/* Gradients dq, dk, dv (row stride ldd) from dout; delta: float[mb,nh,S] scratch. */
+int stage_op_attention_bwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                           const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
+                           const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl);
+
+/* x[t,:] = E[ids[t],:] ; dE[id,:] += sum of dx rows of the tokens carrying id (token order). */
+int stage_op_embed(void* stream, int32_t dtype, int32_t T, int32_t H, int32_t V, const int32_t* ids, const void* E,
+                   void* x, const void* dx, float* dE, int32_t backward);
+/* forward: lse[t], rowloss[t] = lse[t]-z[t,target], *loss = mean_t rowloss.  backward (in place):
+ * z[t,j] = scale*(exp(z[t,j]-lse[t]) - [j==target[t]]). */
+int stage_op_cross_entropy(void* stream, int32_t dtype, int32_t T, int32_t V, void* z, int64_t ldz,
+                           const int32_t* targets, float* lse, float* rowloss, float* loss, float scale,
+                           int32_t backward);
+
+/* AdamW with decoupled weight decay, step t >= 1, on n elements starting at flat index `begin`
+ * (formula in stage.h).  dtype 1: master/m/v are float[n], grad float[>=begin+n], params bf16;
+ * dtype 0: master NULL, params float.  grad[begin..begin+n) is zeroed. */
+int stage_op_adamw(void* stream, int32_t dtype, int64_t n, int64_t begin, void* params, float* master, float* grad,
+                   float* m, float* v, float lr, float beta1, float beta2, float eps, float wd, int64_t t,
+                   float grad_scale);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

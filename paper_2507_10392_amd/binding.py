@@ -1,0 +1,187 @@
+"""ctypes binding of libstage.so: argument marshalling only.
+
+PyTorch is used for device memory (torch.empty on the GPU) and for the stream handle; no
+computation of the stage step happens in Python or in torch.  The library must have been built
+(python -m paper_2507_10392_amd.build, or __graft_entry__.build()); loading fails loudly if
+it is missing - there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libstage.so")
+
+STAGE_OK, STAGE_ERR_ARG, STAGE_ERR_STATE, STAGE_ERR_WORKSPACE, STAGE_ERR_BUDGET, STAGE_ERR_DEVICE = range(6)
+_ERR_NAMES = {1: "STAGE_ERR_ARG", 2: "STAGE_ERR_STATE", 3: "STAGE_ERR_WORKSPACE", 4: "STAGE_ERR_BUDGET",
+              5: "STAGE_ERR_DEVICE"}
+
+
+class StageError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"{_ERR_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+class StageConfigC(C.Structure):
+    _fields_ = [("arch", C.c_int32), ("dtype", C.c_int32), ("layers", C.c_int32), ("hidden", C.c_int32),
+                ("heads", C.c_int32), ("ffn", C.c_int32), ("seq", C.c_int32), ("microbatch", C.c_int32),
+                ("max_microbatches", C.c_int32), ("vocab", C.c_int32), ("has_embed", C.c_int32),
+                ("has_head", C.c_int32), ("recompute", C.c_int32), ("reserved0", C.c_int32),
+                ("act_budget_bytes", C.c_int64), ("shard_begin", C.c_int64), ("shard_end", C.c_int64),
+                ("norm_eps", C.c_float), ("rope_base", C.c_float), ("lr", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("adam_eps", C.c_float), ("weight_decay", C.c_float), ("reserved1", C.c_float)]
+
+
+class StageMemoryC(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("params", "grads", "optim", "activations", "scratch", "workspace")]
+
+
+class StageSegmentC(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("offset", C.c_int64), ("rows", C.c_int64), ("cols", C.c_int64)]
+
+
+class StageKernelStatC(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it was not built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2507_10392_amd.build` "
+                               "(there is no fallback implementation)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        L.stage_query.argtypes = [C.POINTER(StageConfigC), C.POINTER(i64), C.POINTER(StageMemoryC), C.POINTER(i32)]
+        L.stage_layout.argtypes = [C.POINTER(StageConfigC), C.POINTER(StageSegmentC), i32]
+        L.stage_init.argtypes = [C.POINTER(StageConfigC), vp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(vp)]
+        L.stage_forward.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.stage_backward.argtypes = [vp, i32, vp, vp, f32]
+        L.stage_accumulate.argtypes = [vp, i32]
+        L.stage_optimizer_step.argtypes = [vp, i64, f32]
+        L.stage_profile.argtypes = [vp, i32]
+        L.stage_profile_read.argtypes = [vp, C.POINTER(StageKernelStatC), i32]
+        L.stage_last_error.argtypes = [vp]
+        L.stage_last_error.restype = C.c_char_p
+        L.stage_destroy.argtypes = [vp]
+        L.stage_destroy.restype = None
+        L.stage_op_gemm.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, i32,
+                                    i64, i64, i64, i64, i32, i64, i32]
+        L.stage_op_norm_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, f32, vp, vp, vp]
+        L.stage_op_norm_bwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32]
+        L.stage_op_rope.argtypes = [vp, i32, i32, i32, i32, i32, vp, i64, f32, f32, vp]
+        L.stage_op_gelu.argtypes = [vp, i32, i64, vp, vp, vp, i32]
+        L.stage_op_swiglu.argtypes = [vp, i32, i32, i32, vp, vp, vp, i32]
+        L.stage_op_attention_fwd.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, i64, vp, i32]
+        L.stage_op_attention_bwd.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp,
+                                             vp, i64, i32]
+        L.stage_op_embed.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
+        L.stage_op_cross_entropy.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, vp, vp, f32, i32]
+        L.stage_op_adamw.argtypes = [vp, i32, i64, i64, vp, vp, vp, vp, vp, f32, f32, f32, f32, f32, i64, f32]
+        _lib = L
+    return _lib
+
+
+def make_config(cfg, shard=None, max_microbatches=None) -> StageConfigC:
+    """Builds the C struct from any object with the attributes of workloads.StageConfig."""
+    b, e = cfg.shard_range if shard is None else shard
+    return StageConfigC(cfg.arch, cfg.dtype, cfg.layers, cfg.hidden, cfg.heads, cfg.ffn, cfg.seq, cfg.microbatch,
+                        cfg.num_microbatches if max_microbatches is None else max_microbatches, cfg.vocab,
+                        cfg.has_embed, cfg.has_head, cfg.recompute, 0, cfg.act_budget_bytes, b, e, cfg.norm_eps,
+                        cfg.rope_base, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay, 0.0)
+
+
+def _check(code, handle=None):
+    if code != STAGE_OK:
+        raise StageError(code, (lib().stage_last_error(handle) or b"").decode())
+
+
+def query(cc: StageConfigC):
+    """-> (n_params, dict of memory terms in bytes, n_segments); raises StageError on a bad config."""
+    n, mem, ns = C.c_int64(), StageMemoryC(), C.c_int32()
+    _check(lib().stage_query(C.byref(cc), C.byref(n), C.byref(mem), C.byref(ns)))
+    return n.value, {k: getattr(mem, k) for k, _ in StageMemoryC._fields_}, ns.value
+
+
+def layout(cc: StageConfigC):
+    _, _, ns = query(cc)
+    segs = (StageSegmentC * ns)()
+    _check(lib().stage_layout(C.byref(cc), segs, ns))
+    return [(s.name.decode(), s.offset, s.rows, s.cols) for s in segs]
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class Stage:
+    """One stage bound to torch device tensors.  The tensors are kept alive by this object."""
+
+    def __init__(self, cc: StageConfigC, params, master, grad_acc, adam_m, adam_v, workspace, stream=None):
+        import torch
+        self.cc = cc
+        self._keep = (params, master, grad_acc, adam_m, adam_v, workspace)
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = C.c_void_p()
+        _check(lib().stage_init(C.byref(cc), C.c_void_p(self.stream.cuda_stream), _ptr(params), _ptr(master),
+                                _ptr(grad_acc), _ptr(adam_m), _ptr(adam_v), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), C.byref(h)))
+        self.h = h
+
+    def forward(self, mb, x_or_ids, y_out=None, targets=None, loss_out=None):
+        _check(lib().stage_forward(self.h, mb, _ptr(x_or_ids), _ptr(y_out), _ptr(targets), _ptr(loss_out)), self.h)
+
+    def backward(self, mb, dy=None, dx_out=None, loss_scale=1.0):
+        _check(lib().stage_backward(self.h, mb, _ptr(dy), _ptr(dx_out), loss_scale), self.h)
+
+    def accumulate(self, mb):
+        _check(lib().stage_accumulate(self.h, mb), self.h)
+
+    def optimizer_step(self, t, grad_scale=1.0):
+        _check(lib().stage_optimizer_step(self.h, t, grad_scale), self.h)
+
+    def profile(self, enable):
+        _check(lib().stage_profile(self.h, 1 if enable else 0), self.h)
+
+    def profile_read(self):
+        out = (StageKernelStatC * 64)()
+        n = lib().stage_profile_read(self.h, out, 64)
+        if n < 0:
+            raise StageError(-n, "stage_profile_read failed")
+        return {out[i].name.decode(): dict(launches=out[i].launches, ms=out[i].ms, flops=out[i].flops,
+                                           bytes=out[i].bytes) for i in range(n)}
+
+    def close(self):
+        if self.h:
+            lib().stage_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class _Ops:
+    """Single-kernel entry points (stage_op_*), same names as in include/stage_ops.h."""
+
+    def __getattr__(self, name):
+        fn = getattr(lib(), "stage_op_" + name)
+
+        def call(*args):
+            conv = [(_ptr(a) if hasattr(a, "data_ptr") else a) for a in args]
+            code = fn(*conv)
+            if code != STAGE_OK:
+                raise StageError(code, f"stage_op_{name}")
+        return call
+
+
+ops = _Ops()

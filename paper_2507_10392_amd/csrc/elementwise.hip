@@ -1,0 +1,538 @@
+// Bandwidth-bound kernels of the stage step: norms, activations, RoPE, embedding, cross
+// entropy, vector-gradient reductions and the fused AdamW.  Statistics and all arithmetic are
+// fp32; storage is float or bf16.  Every global access is a 16-byte vector per lane where the
+// shape allows it, consecutive lanes touching consecutive vectors.
+#include "kernels.h"
+
+namespace zs {
+
+template <typename T> struct VT { typedef typename Vec<T>::type type; };
+
+template <typename T> __device__ __forceinline__ void load_vec(const T* p, float (&out)[Vec<T>::N]) {
+  typename Vec<T>::type v = *reinterpret_cast<const typename Vec<T>::type*>(p);
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) out[i] = to_f(v[i]);
+}
+template <typename T> __device__ __forceinline__ void store_vec(T* p, const float (&in)[Vec<T>::N]) {
+  typename Vec<T>::type v;
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) v[i] = from_f<T>(in[i]);
+  *reinterpret_cast<typename Vec<T>::type*>(p) = v;
+}
+
+// ------------------------------------------------------------------ norm forward
+// One wave per row; three passes over a row that stays in cache (mean, variance, output).
+template <typename T, int KIND>
+__global__ __launch_bounds__(256) void norm_fwd_kernel(int Trows, int H, const T* __restrict__ x,
+                                                       const T* __restrict__ g, const T* __restrict__ b, float eps,
+                                                       T* __restrict__ n, float* __restrict__ rstd,
+                                                       float* __restrict__ mean) {
+  constexpr int V = Vec<T>::N;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Trows) return;
+  const T* xr = x + (int64_t)row * H;
+  float mu = 0.f;
+  if (KIND == 0) {
+    float s = 0.f;
+    for (int c = lane * V; c < H; c += 64 * V) {
+      float a[V];
+      load_vec(xr + c, a);
+#pragma unroll
+      for (int i = 0; i < V; ++i) s += a[i];
+    }
+    mu = wave_sum(s) / (float)H;
+  }
+  float s2 = 0.f;
+  for (int c = lane * V; c < H; c += 64 * V) {
+    float a[V];
+    load_vec(xr + c, a);
+#pragma unroll
+    for (int i = 0; i < V; ++i) s2 += (a[i] - mu) * (a[i] - mu);
+  }
+  const float r = 1.0f / sqrtf(wave_sum(s2) / (float)H + eps);
+  if (lane == 0) {
+    rstd[row] = r;
+    if (KIND == 0) mean[row] = mu;
+  }
+  T* nr = n + (int64_t)row * H;
+  for (int c = lane * V; c < H; c += 64 * V) {
+    float a[V], gg[V], bb[V], o[V];
+    load_vec(xr + c, a);
+    load_vec(g + c, gg);
+    if (KIND == 0) load_vec(b + c, bb);
+#pragma unroll
+    for (int i = 0; i < V; ++i) o[i] = (a[i] - mu) * r * gg[i] + (KIND == 0 ? bb[i] : 0.f);
+    store_vec(nr + c, o);
+  }
+}
+
+hipError_t norm_fwd(hipStream_t st, DType dt, int kind, int T, int H, const void* x, const void* g, const void* b,
+                    float eps, void* n, float* rstd, float* mean) {
+  dim3 grid((unsigned)cdiv(T, 4)), blk(256);
+#define L(TT, KK) \
+  hipLaunchKernelGGL((norm_fwd_kernel<TT, KK>), grid, blk, 0, st, T, H, (const TT*)x, (const TT*)g, (const TT*)b, eps, (TT*)n, rstd, mean)
+  if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
+  else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+#undef L
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ norm backward (dx only)
+// u = dn*g; dx = r*(u - mean(u) [LN] - xhat*mean(u*xhat)) + dres
+template <typename T, int KIND>
+__global__ __launch_bounds__(256) void norm_bwd_kernel(int Trows, int H, const T* __restrict__ dn,
+                                                       const T* __restrict__ x, const T* __restrict__ g,
+                                                       const float* __restrict__ rstd, const float* __restrict__ mean,
+                                                       const T* dres, T* dx) {
+  constexpr int V = Vec<T>::N;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Trows) return;
+  const float r = rstd[row];
+  const float mu = (KIND == 0) ? mean[row] : 0.f;
+  const T* xr = x + (int64_t)row * H;
+  const T* dr = dn + (int64_t)row * H;
+  float su = 0.f, sux = 0.f;
+  for (int c = lane * V; c < H; c += 64 * V) {
+    float a[V], d[V], gg[V];
+    load_vec(xr + c, a);
+    load_vec(dr + c, d);
+    load_vec(g + c, gg);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const float u = d[i] * gg[i];
+      su += u;
+      sux += u * (a[i] - mu) * r;
+    }
+  }
+  const float mu_u = (KIND == 0) ? wave_sum(su) / (float)H : 0.f;
+  const float mu_ux = wave_sum(sux) / (float)H;
+  for (int c = lane * V; c < H; c += 64 * V) {
+    float a[V], d[V], gg[V], o[V], rs[V];
+    load_vec(xr + c, a);
+    load_vec(dr + c, d);
+    load_vec(g + c, gg);
+    if (dres) load_vec(dres + (int64_t)row * H + c, rs);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const float u = d[i] * gg[i];
+      o[i] = r * (u - mu_u - (a[i] - mu) * r * mu_ux) + (dres ? rs[i] : 0.f);
+    }
+    store_vec(dx + (int64_t)row * H + c, o);
+  }
+}
+
+hipError_t norm_bwd(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x, const void* g,
+                    const float* rstd, const float* mean, const void* dres, void* dx) {
+  dim3 grid((unsigned)cdiv(T, 4)), blk(256);
+#define L(TT, KK) \
+  hipLaunchKernelGGL((norm_bwd_kernel<TT, KK>), grid, blk, 0, st, T, H, (const TT*)dn, (const TT*)x, (const TT*)g, rstd, mean, (const TT*)dres, (TT*)dx)
+  if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
+  else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+#undef L
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ column partial sums
+// grid (column chunks of 256*V, nblk); each thread owns V columns and walks its row block.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(int Trows, int N, const T* __restrict__ a, int64_t lda,
+                                                     const T* __restrict__ x, int64_t ldx,
+                                                     const float* __restrict__ rstd, const float* __restrict__ mean,
+                                                     float* __restrict__ part, int rows_per_blk) {
+  constexpr int V = Vec<T>::N;
+  const int col = (blockIdx.x * 256 + threadIdx.x) * V;
+  if (col >= N) return;
+  const int r0 = blockIdx.y * rows_per_blk;
+  const int r1 = min(Trows, r0 + rows_per_blk);
+  float acc[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) acc[i] = 0.f;
+  for (int t = r0; t < r1; ++t) {
+    float av[V];
+    load_vec(a + (int64_t)t * lda + col, av);
+    if (x) {
+      float xv[V];
+      load_vec(x + (int64_t)t * ldx + col, xv);
+      const float r = rstd[t];
+      const float mu = mean ? mean[t] : 0.f;
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] += av[i] * ((xv[i] - mu) * r);
+    } else {
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] += av[i];
+    }
+  }
+  float* p = part + (int64_t)blockIdx.y * N + col;
+#pragma unroll
+  for (int i = 0; i < V; ++i) p[i] = acc[i];
+}
+
+hipError_t colsum_partial(hipStream_t st, DType dt, int T, int N, const void* a, int64_t lda, const void* x,
+                          int64_t ldx, const float* rstd, const float* mean, float* part, int nblk) {
+  const int rows_per_blk = (int)cdiv(T, nblk);
+  const int V = dt == F32 ? 4 : 8;
+  dim3 grid((unsigned)cdiv(N, 256 * V), (unsigned)nblk), blk(256);
+  if (dt == F32)
+    hipLaunchKernelGGL(colsum_kernel<float>, grid, blk, 0, st, T, N, (const float*)a, lda, (const float*)x, ldx, rstd, mean, part, rows_per_blk);
+  else
+    hipLaunchKernelGGL(colsum_kernel<bf16>, grid, blk, 0, st, T, N, (const bf16*)a, lda, (const bf16*)x, ldx, rstd, mean, part, rows_per_blk);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceJob* __restrict__ jobs) {
+  const ReduceJob j = jobs[blockIdx.x];
+  const int c = blockIdx.y * 256 + threadIdx.x;
+  if (c >= j.width) return;
+  float s = 0.f;
+  for (int b = 0; b < j.nblk; ++b) s += j.part[(int64_t)b * j.width + c];
+  j.dst[c] += s;
+}
+
+hipError_t reduce_partials(hipStream_t st, const ReduceJob* jobs_dev, int njobs, int max_width) {
+  if (njobs == 0) return hipSuccess;
+  dim3 grid((unsigned)njobs, (unsigned)cdiv(max_width, 256)), blk(256);
+  hipLaunchKernelGGL(reduce_partials_kernel, grid, blk, 0, st, jobs_dev);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ RoPE
+__global__ void rope_table_kernel(int S, int d, double base, float2* table) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int half = d / 2;
+  if (idx >= S * half) return;
+  const int s = idx / half, i = idx % half;
+  const double theta = (double)s * pow(base, -2.0 * (double)i / (double)d);
+  table[idx] = make_float2((float)cos(theta), (float)sin(theta));
+}
+hipError_t rope_table(hipStream_t st, int S, int d, float base, float2* table) {
+  const int n = S * (d / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st, S, d, (double)base, table);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(int Trows, int S, int ncols, int d, T* a, int64_t ld,
+                                                   const float2* __restrict__ table, float sign) {
+  constexpr int V = Vec<T>::N;
+  const int vec_per_row = ncols / V;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)Trows * vec_per_row) return;
+  const int t = (int)(idx / vec_per_row);
+  const int c = (int)(idx % vec_per_row) * V;
+  const int pos = t % S;
+  T* p = a + (int64_t)t * ld + c;
+  float u[V], o[V];
+  load_vec(p, u);
+  const int i0 = (c % d) / 2;
+#pragma unroll
+  for (int i = 0; i < V / 2; ++i) {
+    const float2 cs = table[pos * (d / 2) + i0 + i];
+    const float sn = sign * cs.y;
+    o[2 * i] = u[2 * i] * cs.x - u[2 * i + 1] * sn;
+    o[2 * i + 1] = u[2 * i] * sn + u[2 * i + 1] * cs.x;
+  }
+  store_vec(p, o);
+}
+hipError_t rope_apply(hipStream_t st, DType dt, int T, int S, int ncols, int d, void* a, int64_t ld,
+                      const float2* table, float sign) {
+  const int V = dt == F32 ? 4 : 8;
+  const int64_t n = (int64_t)T * (ncols / V);
+  dim3 grid((unsigned)cdiv(n, 256)), blk(256);
+  if (dt == F32) hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, st, T, S, ncols, d, (float*)a, ld, table, sign);
+  else hipLaunchKernelGGL(rope_kernel<bf16>, grid, blk, 0, st, T, S, ncols, d, (bf16*)a, ld, table, sign);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ activations
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float z) {
+  const float Phi = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
+  const float phi = 0.39894228040143268f * expf(-0.5f * z * z);
+  return Phi + z * phi;
+}
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + expf(-z)); }
+
+template <typename T, int MODE>  // 0: a = gelu(z); 1: dz = da * gelu'(z)
+__global__ __launch_bounds__(256) void gelu_kernel(int64_t nvec, const T* __restrict__ z, const T* __restrict__ da,
+                                                   T* __restrict__ out) {
+  constexpr int V = Vec<T>::N;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nvec) return;
+  float zz[V], o[V], d[V];
+  load_vec(z + i * V, zz);
+  if (MODE == 1) load_vec(da + i * V, d);
+#pragma unroll
+  for (int k = 0; k < V; ++k) o[k] = MODE == 0 ? gelu_f(zz[k]) : d[k] * gelu_df(zz[k]);
+  store_vec(out + i * V, o);
+}
+hipError_t gelu_fwd(hipStream_t st, DType dt, int64_t n, const void* z, void* a) {
+  const int V = dt == F32 ? 4 : 8;
+  dim3 grid((unsigned)cdiv(n / V, 256)), blk(256);
+  if (dt == F32) hipLaunchKernelGGL((gelu_kernel<float, 0>), grid, blk, 0, st, n / V, (const float*)z, (const float*)nullptr, (float*)a);
+  else hipLaunchKernelGGL((gelu_kernel<bf16, 0>), grid, blk, 0, st, n / V, (const bf16*)z, (const bf16*)nullptr, (bf16*)a);
+  return hipGetLastError();
+}
+hipError_t gelu_bwd(hipStream_t st, DType dt, int64_t n, const void* z, const void* da, void* dz) {
+  const int V = dt == F32 ? 4 : 8;
+  dim3 grid((unsigned)cdiv(n / V, 256)), blk(256);
+  if (dt == F32) hipLaunchKernelGGL((gelu_kernel<float, 1>), grid, blk, 0, st, n / V, (const float*)z, (const float*)da, (float*)dz);
+  else hipLaunchKernelGGL((gelu_kernel<bf16, 1>), grid, blk, 0, st, n / V, (const bf16*)z, (const bf16*)da, (bf16*)dz);
+  return hipGetLastError();
+}
+
+template <typename T, int MODE>  // 0: a = silu(g)*u ; 1: (dg, du) from da
+__global__ __launch_bounds__(256) void swiglu_kernel(int Trows, int F, const T* gu, const T* __restrict__ da, T* out) {
+  constexpr int V = Vec<T>::N;
+  const int vec_per_row = F / V;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)Trows * vec_per_row) return;
+  const int t = (int)(idx / vec_per_row);
+  const int c = (int)(idx % vec_per_row) * V;
+  float g[V], u[V];
+  load_vec(gu + (int64_t)t * 2 * F + c, g);
+  load_vec(gu + (int64_t)t * 2 * F + F + c, u);
+  if (MODE == 0) {
+    float o[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) o[k] = g[k] * sigmoid_f(g[k]) * u[k];
+    store_vec(out + (int64_t)t * F + c, o);
+  } else {
+    float d[V], dg[V], du[V];
+    load_vec(da + (int64_t)t * F + c, d);
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+      const float s = sigmoid_f(g[k]);
+      du[k] = d[k] * g[k] * s;
+      dg[k] = d[k] * u[k] * s * (1.0f + g[k] * (1.0f - s));
+    }
+    store_vec(out + (int64_t)t * 2 * F + c, dg);
+    store_vec(out + (int64_t)t * 2 * F + F + c, du);
+  }
+}
+hipError_t swiglu_fwd(hipStream_t st, DType dt, int T, int F, const void* gu, void* a) {
+  const int V = dt == F32 ? 4 : 8;
+  dim3 grid((unsigned)cdiv((int64_t)T * (F / V), 256)), blk(256);
+  if (dt == F32) hipLaunchKernelGGL((swiglu_kernel<float, 0>), grid, blk, 0, st, T, F, (const float*)gu, (const float*)nullptr, (float*)a);
+  else hipLaunchKernelGGL((swiglu_kernel<bf16, 0>), grid, blk, 0, st, T, F, (const bf16*)gu, (const bf16*)nullptr, (bf16*)a);
+  return hipGetLastError();
+}
+hipError_t swiglu_bwd(hipStream_t st, DType dt, int T, int F, const void* gu, const void* da, void* dgu) {
+  const int V = dt == F32 ? 4 : 8;
+  dim3 grid((unsigned)cdiv((int64_t)T * (F / V), 256)), blk(256);
+  if (dt == F32) hipLaunchKernelGGL((swiglu_kernel<float, 1>), grid, blk, 0, st, T, F, (const float*)gu, (const float*)da, (float*)dgu);
+  else hipLaunchKernelGGL((swiglu_kernel<bf16, 1>), grid, blk, 0, st, T, F, (const bf16*)gu, (const bf16*)da, (bf16*)dgu);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ embedding
+template <typename T>
+__global__ __launch_bounds__(256) void embed_fwd_kernel(int H, int V, const int32_t* __restrict__ ids,
+                                                        const T* __restrict__ E, T* __restrict__ x) {
+  constexpr int VN = Vec<T>::N;
+  typedef typename Vec<T>::type vec_t;
+  const int t = blockIdx.x;
+  const int id = ids[t];
+  const bool ok = id >= 0 && id < V;
+  for (int c = threadIdx.x * VN; c < H; c += 256 * VN) {
+    vec_t v;
+    if (ok) v = *reinterpret_cast<const vec_t*>(E + (int64_t)id * H + c);   // bit-exact row copy
+    else {
+#pragma unroll
+      for (int i = 0; i < VN; ++i) v[i] = from_f<T>(0.f);
+    }
+    *reinterpret_cast<vec_t*>(x + (int64_t)t * H + c) = v;
+  }
+}
+hipError_t embed_fwd(hipStream_t st, DType dt, int T, int H, int V, const int32_t* ids, const void* E, void* x) {
+  if (dt == F32) hipLaunchKernelGGL(embed_fwd_kernel<float>, dim3(T), dim3(256), 0, st, H, V, ids, (const float*)E, (float*)x);
+  else hipLaunchKernelGGL(embed_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, H, V, ids, (const bf16*)E, (bf16*)x);
+  return hipGetLastError();
+}
+
+// One workgroup per token.  The workgroup of the FIRST token carrying an id adds the rows of
+// every token with that id, in increasing token order, to dE[id]; the others exit.  A row of dE
+// has one owner workgroup and a column one owner thread, so no atomics are needed and the
+// result does not depend on scheduling.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_bwd_kernel(int Trows, int H, int V, const int32_t* __restrict__ ids,
+                                                        const T* __restrict__ dx, float* __restrict__ dE) {
+  __shared__ int flags[256];
+  const int t = blockIdx.x;
+  const int id = ids[t];
+  if (id < 0 || id >= V) return;
+  int earlier = 0;
+  for (int u = threadIdx.x; u < t; u += 256) earlier |= (ids[u] == id);
+  if (__syncthreads_or(earlier)) return;
+  for (int base = t; base < Trows; base += 256) {
+    const int u = base + threadIdx.x;
+    const int match = (u < Trows) && (ids[u] == id);
+    flags[threadIdx.x] = match;
+    if (__syncthreads_or(match)) {
+      for (int j = 0; j < 256; ++j) {
+        if (!flags[j]) continue;
+        for (int c = threadIdx.x; c < H; c += 256) dE[(int64_t)id * H + c] += to_f(dx[(int64_t)(base + j) * H + c]);
+      }
+    }
+    __syncthreads();
+  }
+}
+hipError_t embed_bwd(hipStream_t st, DType dt, int T, int H, int V, const int32_t* ids, const void* dx, float* dE) {
+  if (dt == F32) hipLaunchKernelGGL(embed_bwd_kernel<float>, dim3(T), dim3(256), 0, st, T, H, V, ids, (const float*)dx, dE);
+  else hipLaunchKernelGGL(embed_bwd_kernel<bf16>, dim3(T), dim3(256), 0, st, T, H, V, ids, (const bf16*)dx, dE);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ cross entropy
+template <typename T>
+__global__ __launch_bounds__(256) void ce_fwd_kernel(int V, const T* __restrict__ z, int64_t ldz,
+                                                     const int32_t* __restrict__ targets, float* __restrict__ lse,
+                                                     float* __restrict__ rowloss) {
+  __shared__ float red[4];
+  const int t = blockIdx.x;
+  const T* zr = z + (int64_t)t * ldz;
+  float mx = -INFINITY;
+  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, to_f(zr[c]));
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float s = 0.f;
+  for (int c = threadIdx.x; c < V; c += 256) s += expf(to_f(zr[c]) - mx);
+  s = block_sum<4>(s, red);
+  if (threadIdx.x == 0) {
+    const float l = mx + logf(s);
+    const int tg = targets[t];
+    lse[t] = l;
+    rowloss[t] = (tg >= 0 && tg < V) ? l - to_f(zr[tg]) : 0.f;
+  }
+}
+__global__ __launch_bounds__(256) void mean_kernel(int n, const float* __restrict__ v, float* __restrict__ out) {
+  __shared__ float red[4];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += v[i];
+  s = block_sum<4>(s, red);
+  if (threadIdx.x == 0) *out = s / (float)n;
+}
+hipError_t ce_fwd(hipStream_t st, DType dt, int T, int V, const void* z, int64_t ldz, const int32_t* targets,
+                  float* lse, float* rowloss, float* loss) {
+  if (dt == F32) hipLaunchKernelGGL(ce_fwd_kernel<float>, dim3(T), dim3(256), 0, st, V, (const float*)z, ldz, targets, lse, rowloss);
+  else hipLaunchKernelGGL(ce_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, V, (const bf16*)z, ldz, targets, lse, rowloss);
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st, T, rowloss, loss);
+  return hipGetLastError();
+}
+template <typename T>
+__global__ __launch_bounds__(256) void ce_bwd_kernel(int V, T* z, int64_t ldz, const int32_t* __restrict__ targets,
+                                                     const float* __restrict__ lse, float scale) {
+  const int t = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= V) return;
+  T* p = z + (int64_t)t * ldz + c;
+  const float pr = expf(to_f(*p) - lse[t]);
+  *p = from_f<T>(scale * (pr - (c == targets[t] ? 1.f : 0.f)));
+}
+hipError_t ce_bwd(hipStream_t st, DType dt, int T, int V, void* z, int64_t ldz, const int32_t* targets,
+                  const float* lse, float scale) {
+  dim3 grid((unsigned)cdiv(V, 256), (unsigned)T), blk(256);
+  if (dt == F32) hipLaunchKernelGGL(ce_bwd_kernel<float>, grid, blk, 0, st, V, (float*)z, ldz, targets, lse, scale);
+  else hipLaunchKernelGGL(ce_bwd_kernel<bf16>, grid, blk, 0, st, V, (bf16*)z, ldz, targets, lse, scale);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ AdamW
+__device__ __forceinline__ float adamw_one(float p, float g, float& m, float& v, const AdamW& h) {
+  g *= h.grad_scale;
+  m = h.beta1 * m + (1.0f - h.beta1) * g;
+  v = h.beta2 * v + (1.0f - h.beta2) * g * g;
+  const float mhat = m * h.inv_bc1;
+  const float vhat = v * h.inv_bc2;
+  return p - h.lr * (mhat / (sqrtf(vhat) + h.eps) + h.wd * p);
+}
+
+// One float4 of p, g, m, v per lane; reads 16 B/element, writes 12 B (+2 B bf16 copy, +4 B zeroed grad).
+// VEC=false is the scalar variant for ranges that are not 16-byte aligned and for the tail.
+template <bool BF, bool VEC>
+__global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, void* params, float* master,
+                                                    float* grad, float* m, float* v, AdamW h) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * (VEC ? 4 : 1);
+  if (i >= n) return;
+  float* pm = BF ? master + i : (float*)params + begin + i;
+  if (VEC) {
+    f32x4 p4 = *(f32x4*)pm, g4 = *(f32x4*)(grad + begin + i), m4 = *(f32x4*)(m + i), v4 = *(f32x4*)(v + i);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      float mm = m4[k], vv = v4[k];
+      p4[k] = adamw_one(p4[k], g4[k], mm, vv, h);
+      m4[k] = mm;
+      v4[k] = vv;
+    }
+    *(f32x4*)pm = p4;
+    *(f32x4*)(m + i) = m4;
+    *(f32x4*)(v + i) = v4;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    *(f32x4*)(grad + begin + i) = zero;
+    if (BF) {
+      bf16x4 b;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) b[k] = (bf16)p4[k];
+      *(bf16x4*)((bf16*)params + begin + i) = b;
+    }
+  } else {
+    float mm = m[i], vv = v[i];
+    const float pn = adamw_one(*pm, grad[begin + i], mm, vv, h);
+    *pm = pn;
+    m[i] = mm;
+    v[i] = vv;
+    grad[begin + i] = 0.f;
+    if (BF) ((bf16*)params)[begin + i] = (bf16)pn;
+  }
+}
+
+hipError_t adamw(hipStream_t st, DType dt, int64_t n, int64_t begin, void* params, float* master, float* grad,
+                 float* m, float* v, const AdamW& h) {
+  if (n <= 0) return hipSuccess;
+  const bool aligned = (begin % 4) == 0;   // then grad+begin, params+begin share the alignment of the shard arrays
+  const int64_t nv = aligned ? (n / 4) * 4 : 0;
+  if (nv > 0) {
+    dim3 grid((unsigned)cdiv(nv / 4, 256)), blk(256);
+    if (dt == BF16) hipLaunchKernelGGL((adamw_kernel<true, true>), grid, blk, 0, st, nv, begin, params, master, grad, m, v, h);
+    else hipLaunchKernelGGL((adamw_kernel<false, true>), grid, blk, 0, st, nv, begin, params, master, grad, m, v, h);
+  }
+  if (n > nv) {
+    const int64_t r = n - nv;
+    dim3 grid((unsigned)cdiv(r, 256)), blk(256);
+    if (dt == BF16)
+      hipLaunchKernelGGL((adamw_kernel<true, false>), grid, blk, 0, st, r, begin + nv, params, master + nv, grad, m + nv, v + nv, h);
+    else
+      hipLaunchKernelGGL((adamw_kernel<false, false>), grid, blk, 0, st, r, begin + nv, params, (float*)nullptr, grad, m + nv, v + nv, h);
+  }
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* p, int64_t n) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i + 4 <= n) {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    *(f32x4*)(p + i) = zero;
+  } else {
+    for (int64_t k = i; k < n; ++k) p[k] = 0.f;
+  }
+}
+hipError_t fill_zero(hipStream_t st, float* p, int64_t n) {
+  if (n <= 0) return hipSuccess;
+  // peel so that the vector stores are 16-byte aligned
+  int64_t head = ((16 - ((uintptr_t)p & 15)) & 15) / 4;
+  if (head > n) head = n;
+  if (head) hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, st, p, head < 4 ? head : 3);
+  p += head;
+  n -= head;
+  if (n > 0) hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)cdiv(cdiv(n, 4), 256)), dim3(256), 0, st, p, n);
+  return hipGetLastError();
+}
+
+hipError_t copy_bytes(hipStream_t st, void* dst, const void* src, int64_t bytes) {
+  return hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyDeviceToDevice, st);
+}
+
+}  // namespace zs

@@ -1,0 +1,115 @@
+// Plain LDS-tiled GEMM with fp32 FMA accumulation.  It serves the fp32 configuration (which may
+// not round below fp32 anywhere) and shapes the MFMA kernel does not take (unaligned leading
+// dimensions).  64x64x16 tiles, 256 threads, 4x4 outputs per thread, every access bounds-checked.
+#include "kernels.h"
+
+namespace zs {
+
+template <typename T, int TA, int TB>
+__global__ __launch_bounds__(256) void gemm_simple_kernel(Gemm g) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const int z = blockIdx.z;
+  const T* A = (const T*)g.A + (int64_t)z * g.sA;
+  const T* B = (const T*)g.B + (int64_t)z * g.sB;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int m, k;
+      if (TA == 0) { k = tid & 15; m = (tid >> 4) + 16 * i; }
+      else { m = tid & 63; k = (tid >> 6) + 4 * i; }
+      const int gm = m0 + m, gk = k0 + k;
+      float v = 0.f;
+      if (gm < g.M && gk < g.K) v = to_f(TA == 0 ? A[(int64_t)gm * g.lda + gk] : A[(int64_t)gk * g.lda + gm]);
+      As[k][m] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int n, k;
+      if (TB == 0) { n = tid & 63; k = (tid >> 6) + 4 * i; }
+      else { k = tid & 15; n = (tid >> 4) + 16 * i; }
+      const int gn = n0 + n, gk = k0 + k;
+      float v = 0.f;
+      if (gn < g.N && gk < g.K) {
+        const int seg = g.kseg ? gk / g.kseg : 0;
+        const int kk = g.kseg ? gk - seg * g.kseg : gk;
+        const T* Bp = B + (int64_t)seg * g.segB;
+        v = to_f(TB == 0 ? Bp[(int64_t)kk * g.ldb + gn] : Bp[(int64_t)gn * g.ldb + kk]);
+      }
+      Bs[k][n] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+
+  const T* bias = g.bias ? (const T*)g.bias + (int64_t)z * g.sBias : nullptr;
+  const T* R = g.resid ? (const T*)g.resid + (int64_t)z * g.sC : nullptr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int gm = m0 + ty * 4 + i;
+    if (gm >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int gn = n0 + tx * 4 + j;
+      if (gn >= g.N) continue;
+      float v = acc[i][j];
+      if (bias) v += to_f(bias[gn]);
+      if (R) v += to_f(R[(int64_t)gm * g.ldr + gn]);
+      if (g.c_f32_accum) {
+        float* C = (float*)g.C + (int64_t)z * g.sC;
+        C[(int64_t)gm * g.ldc + gn] += v;
+      } else {
+        T* C = (T*)g.C + (int64_t)z * g.sC;
+        C[(int64_t)gm * g.ldc + gn] = from_f<T>(v);
+      }
+    }
+  }
+}
+
+template <typename T> static hipError_t launch_simple(hipStream_t st, const Gemm& g) {
+  dim3 grid((unsigned)cdiv(g.N, 64), (unsigned)cdiv(g.M, 64), (unsigned)g.batch), blk(256);
+  if (!g.transA && !g.transB) hipLaunchKernelGGL((gemm_simple_kernel<T, 0, 0>), grid, blk, 0, st, g);
+  else if (!g.transA && g.transB) hipLaunchKernelGGL((gemm_simple_kernel<T, 0, 1>), grid, blk, 0, st, g);
+  else if (g.transA && !g.transB) hipLaunchKernelGGL((gemm_simple_kernel<T, 1, 0>), grid, blk, 0, st, g);
+  else hipLaunchKernelGGL((gemm_simple_kernel<T, 1, 1>), grid, blk, 0, st, g);
+  return hipGetLastError();
+}
+
+hipError_t gemm_simple(hipStream_t st, DType dt, const Gemm& g) {
+  if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
+  return dt == F32 ? launch_simple<float>(st, g) : launch_simple<bf16>(st, g);
+}
+
+int gemm_select(DType dt, const Gemm& g, int force) {
+  if (force == GEMM_SIMPLE) return GEMM_SIMPLE;
+  return gemm_mfma_supported(dt, g) ? GEMM_MFMA : GEMM_SIMPLE;
+}
+
+hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
+  if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, g);
+  return gemm_simple(st, dt, g);
+}
+
+}  // namespace zs

@@ -1,0 +1,92 @@
+// Host-side launchers of the stage kernels.  All pointers are device pointers; every
+// launcher only enqueues on the given stream and returns the launch status.
+#pragma once
+#include "common.h"
+
+namespace zs {
+
+// C[M,N] (op)= sum_k A(m,k) * B(k,n)  (+ bias[n]) (+ R[m,n])
+//   transA = 0: A stored row-major [M,K] (lda = row stride);  1: stored [K,M]
+//   transB = 0: B stored row-major [K,N] (ldb = row stride);  1: stored [N,K]
+//   c_f32_accum = 0: C has the compute dtype and is overwritten
+//                 1: C is float and the product is ADDED to it (weight gradients into grad_acc)
+//   batch > 1: operand z uses A + z*sA, B + z*sB, C + z*sC, bias + z*sBias, R + z*sC.
+//   kseg > 0: the K range is cut in segments of kseg; segment s reads B from B + s*segB
+//             (dgrad through several weight matrices stored one after another).
+struct Gemm {
+  int M = 0, N = 0, K = 0, transA = 0, transB = 0;
+  const void* A = nullptr; int64_t lda = 0;
+  const void* B = nullptr; int64_t ldb = 0;
+  void* C = nullptr; int64_t ldc = 0;
+  int c_f32_accum = 0;
+  const void* bias = nullptr;
+  const void* resid = nullptr; int64_t ldr = 0;
+  int batch = 1; int64_t sA = 0, sB = 0, sC = 0, sBias = 0;
+  int kseg = 0; int64_t segB = 0;
+};
+enum GemmImpl { GEMM_AUTO = 0, GEMM_SIMPLE = 1, GEMM_MFMA = 2 };
+// Returns which implementation a call with these arguments runs (GEMM_SIMPLE or GEMM_MFMA).
+int gemm_select(DType dt, const Gemm& g, int force);
+hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force);
+hipError_t gemm_simple(hipStream_t st, DType dt, const Gemm& g);
+bool gemm_mfma_supported(DType dt, const Gemm& g);
+hipError_t gemm_mfma(hipStream_t st, const Gemm& g);
+
+// kind 0 LayerNorm (mean and rstd saved), 1 RMSNorm (rstd saved).  b and mean may be NULL for RMSNorm.
+hipError_t norm_fwd(hipStream_t st, DType dt, int kind, int T, int H, const void* x, const void* g, const void* b,
+                    float eps, void* n, float* rstd, float* mean);
+// dx = (dres ? dres : 0) + norm'(x)^T dn.  dres may alias dx.
+hipError_t norm_bwd(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x, const void* g,
+                    const float* rstd, const float* mean, const void* dres, void* dx);
+// part[blk, n] = sum over the rows t of block blk of a[t,n] * (x ? (x[t,n]-mean[t])*rstd[t] : 1)
+// (mean may be NULL = 0).  Rows are cut in nblk equal blocks.  part is float[nblk, N].
+hipError_t colsum_partial(hipStream_t st, DType dt, int T, int N, const void* a, int64_t lda, const void* x,
+                          int64_t ldx, const float* rstd, const float* mean, float* part, int nblk);
+struct ReduceJob { const float* part; float* dst; int nblk; int width; };
+// dst[c] += sum_blk part[blk, c] for every job, blocks added in increasing order.
+hipError_t reduce_partials(hipStream_t st, const ReduceJob* jobs_dev, int njobs, int max_width);
+
+// table[s, i] = (cos, sin)(s * base^(-2i/d)), computed in double precision.
+hipError_t rope_table(hipStream_t st, int S, int d, float base, float2* table);
+// Rotates adjacent pairs of every head in a[T, ncols] (ld = row stride, heads are d wide) in place;
+// token t has position t % S; sign = -1 applies the inverse rotation.
+hipError_t rope_apply(hipStream_t st, DType dt, int T, int S, int ncols, int d, void* a, int64_t ld,
+                      const float2* table, float sign);
+
+hipError_t gelu_fwd(hipStream_t st, DType dt, int64_t n, const void* z, void* a);
+hipError_t gelu_bwd(hipStream_t st, DType dt, int64_t n, const void* z, const void* da, void* dz);
+// gu is [T, 2F] = [gate | up]; a is [T, F].  dgu may alias gu.
+hipError_t swiglu_fwd(hipStream_t st, DType dt, int T, int F, const void* gu, void* a);
+hipError_t swiglu_bwd(hipStream_t st, DType dt, int T, int F, const void* gu, const void* da, void* dgu);
+
+// Causal softmax attention.  q, k, v point at the first element of their [T, nh*d] blocks inside a
+// buffer with row stride ld (elements); token t = b*S + s.  lse is float[mb, nh, S].
+enum AttnImpl { ATTN_AUTO = 0, ATTN_SIMPLE = 1, ATTN_MFMA = 2 };
+int attn_select(DType dt, int S, int d, int force);
+hipError_t attn_fwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, const void* q, const void* k,
+                    const void* v, int64_t ld, void* o, int64_t ldo, float* lse, int force);
+// delta is float[mb, nh, S] scratch.  dq, dk, dv are laid out like q, k, v with row stride ldd.
+hipError_t attn_bwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, const void* q, const void* k,
+                    const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse,
+                    float* delta, void* dq, void* dk, void* dv, int64_t ldd, int force);
+
+// x[t,:] = E[ids[t],:] (rows of ids outside [0,V) give zeros).
+hipError_t embed_fwd(hipStream_t st, DType dt, int T, int H, int V, const int32_t* ids, const void* E, void* x);
+// dE[id,:] += sum over the tokens with that id, added in increasing token order.
+hipError_t embed_bwd(hipStream_t st, DType dt, int T, int H, int V, const int32_t* ids, const void* dx, float* dE);
+// lse[t] = logsumexp(z[t,:]); rowloss[t] = lse[t] - z[t,target[t]]; then *loss = mean_t rowloss[t].
+hipError_t ce_fwd(hipStream_t st, DType dt, int T, int V, const void* z, int64_t ldz, const int32_t* targets,
+                  float* lse, float* rowloss, float* loss);
+// z[t,j] <- scale * (exp(z[t,j]-lse[t]) - [j == target[t]])   (scale = loss_scale / T)
+hipError_t ce_bwd(hipStream_t st, DType dt, int T, int V, void* z, int64_t ldz, const int32_t* targets,
+                  const float* lse, float scale);
+
+struct AdamW { float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2, grad_scale; };
+// Elements i in [0,n): flat parameter index begin+i.  dtype BF16: master/m/v indexed by i, grad and
+// params_bf16 by begin+i.  dtype F32: params (float) indexed by begin+i is the master.  grad is zeroed.
+hipError_t adamw(hipStream_t st, DType dt, int64_t n, int64_t begin, void* params, float* master, float* grad,
+                 float* m, float* v, const AdamW& h);
+hipError_t fill_zero(hipStream_t st, float* p, int64_t n);
+hipError_t copy_bytes(hipStream_t st, void* dst, const void* src, int64_t bytes);
+
+}  // namespace zs

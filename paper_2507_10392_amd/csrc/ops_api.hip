@@ -1,0 +1,131 @@
+// C-ABI wrappers around single kernels (declared in include/stage_ops.h).
+#include "../../include/stage.h"
+#include "../../include/stage_ops.h"
+#include "kernels.h"
+
+#include <cmath>
+
+using namespace zs;
+
+namespace {
+int rc(hipError_t e) { return e == hipSuccess ? STAGE_OK : STAGE_ERR_DEVICE; }
+bool dt_ok(int d) { return d == 0 || d == 1; }
+int vec_of(int d) { return d == 0 ? 4 : 8; }
+}  // namespace
+
+extern "C" {
+
+int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
+                  const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
+                  const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,
+                  int64_t sBias, int32_t kseg, int64_t segB, int32_t impl) {
+  if (!dt_ok(dtype) || M < 0 || N < 0 || K < 0 || batch < 1 || !A || !B || !C || kseg < 0) return STAGE_ERR_ARG;
+  if (kseg > 0 && K % kseg) return STAGE_ERR_ARG;
+  Gemm g;
+  g.M = M; g.N = N; g.K = K; g.transA = transA != 0; g.transB = transB != 0;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.c_f32_accum = c_f32_accum != 0;
+  g.bias = bias; g.resid = resid; g.ldr = ldr; g.batch = batch; g.sA = sA; g.sB = sB; g.sC = sC; g.sBias = sBias;
+  g.kseg = kseg; g.segB = segB;
+  if (impl == GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
+  return rc(gemm((hipStream_t)stream, (DType)dtype, g, impl));
+}
+
+int stage_op_norm_fwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* x, const void* g,
+                      const void* b, float eps, void* n, float* rstd, float* mean) {
+  if (!dt_ok(dtype) || (kind != 0 && kind != 1) || T < 0 || H < 1 || H % vec_of(dtype) || !x || !g || !n || !rstd)
+    return STAGE_ERR_ARG;
+  if (kind == 0 && (!b || !mean)) return STAGE_ERR_ARG;
+  if (T == 0) return STAGE_OK;
+  return rc(norm_fwd((hipStream_t)stream, (DType)dtype, kind, T, H, x, g, b, eps, n, rstd, mean));
+}
+
+int stage_op_norm_bwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* dn, const void* x,
+                      const void* g, const float* rstd, const float* mean, const void* dres, void* dx,
+                      float* dg_part, float* db_part, int32_t nblk) {
+  if (!dt_ok(dtype) || (kind != 0 && kind != 1) || T < 1 || H < 1 || H % vec_of(dtype) || !dn || !x || !g || !rstd ||
+      !dx || !dg_part || nblk < 1 || nblk > T)
+    return STAGE_ERR_ARG;
+  if (kind == 0 && (!mean || !db_part)) return STAGE_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = colsum_partial(st, (DType)dtype, T, H, dn, H, x, H, rstd, kind == 0 ? mean : nullptr, dg_part, nblk);
+  if (e == hipSuccess && kind == 0) e = colsum_partial(st, (DType)dtype, T, H, dn, H, nullptr, H, nullptr, nullptr, db_part, nblk);
+  if (e == hipSuccess) e = norm_bwd(st, (DType)dtype, kind, T, H, dn, x, g, rstd, mean, dres, dx);
+  return rc(e);
+}
+
+int stage_op_rope(void* stream, int32_t dtype, int32_t T, int32_t S, int32_t ncols, int32_t d, void* a, int64_t ld,
+                  float base, float sign, float* table) {
+  if (!dt_ok(dtype) || T < 0 || S < 1 || d < 2 || d % 8 || ncols % d || !a || !table || !(base > 0.f)) return STAGE_ERR_ARG;
+  if (T == 0) return STAGE_OK;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = rope_table(st, S, d, base, (float2*)table);
+  if (e == hipSuccess) e = rope_apply(st, (DType)dtype, T, S, ncols, d, a, ld, (const float2*)table, sign);
+  return rc(e);
+}
+
+int stage_op_gelu(void* stream, int32_t dtype, int64_t n, const void* z, const void* da, void* out, int32_t backward) {
+  if (!dt_ok(dtype) || n < 0 || n % vec_of(dtype) || !z || !out || (backward && !da)) return STAGE_ERR_ARG;
+  if (n == 0) return STAGE_OK;
+  return rc(backward ? gelu_bwd((hipStream_t)stream, (DType)dtype, n, z, da, out)
+                     : gelu_fwd((hipStream_t)stream, (DType)dtype, n, z, out));
+}
+
+int stage_op_swiglu(void* stream, int32_t dtype, int32_t T, int32_t F, const void* gu, const void* da, void* out,
+                    int32_t backward) {
+  if (!dt_ok(dtype) || T < 0 || F < 1 || F % vec_of(dtype) || !gu || !out || (backward && !da)) return STAGE_ERR_ARG;
+  if (T == 0) return STAGE_OK;
+  return rc(backward ? swiglu_bwd((hipStream_t)stream, (DType)dtype, T, F, gu, da, out)
+                     : swiglu_fwd((hipStream_t)stream, (DType)dtype, T, F, gu, out));
+}
+
+int stage_op_attention_fwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                           const void* k, const void* v, int64_t ld, void* o, int64_t ldo, float* lse, int32_t impl) {
+  if (!dt_ok(dtype) || mb < 1 || S < 1 || nh < 1 || d < 8 || d % 8 || d > 256 || !q || !k || !v || !o || !lse)
+    return STAGE_ERR_ARG;
+  if (impl == ATTN_MFMA && attn_select((DType)dtype, S, d, 0) != ATTN_MFMA) return STAGE_ERR_ARG;
+  return rc(attn_fwd((hipStream_t)stream, (DType)dtype, mb, S, nh, d, q, k, v, ld, o, ldo, lse, impl));
+}
+
+int stage_op_attention_bwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                           const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
+                           const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl) {
+  if (!dt_ok(dtype) || mb < 1 || S < 1 || nh < 1 || d < 8 || d % 8 || d > 256 || !q || !k || !v || !o || !dout || !lse ||
+      !delta || !dq || !dk || !dv)
+    return STAGE_ERR_ARG;
+  if (impl == ATTN_MFMA && attn_select((DType)dtype, S, d, 0) != ATTN_MFMA) return STAGE_ERR_ARG;
+  return rc(attn_bwd((hipStream_t)stream, (DType)dtype, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv,
+                     ldd, impl));
+}
+
+int stage_op_embed(void* stream, int32_t dtype, int32_t T, int32_t H, int32_t V, const int32_t* ids, const void* E,
+                   void* x, const void* dx, float* dE, int32_t backward) {
+  if (!dt_ok(dtype) || T < 0 || H < 1 || H % vec_of(dtype) || V < 1 || !ids) return STAGE_ERR_ARG;
+  if (backward ? (!dx || !dE) : (!E || !x)) return STAGE_ERR_ARG;
+  if (T == 0) return STAGE_OK;
+  return rc(backward ? embed_bwd((hipStream_t)stream, (DType)dtype, T, H, V, ids, dx, dE)
+                     : embed_fwd((hipStream_t)stream, (DType)dtype, T, H, V, ids, E, x));
+}
+
+int stage_op_cross_entropy(void* stream, int32_t dtype, int32_t T, int32_t V, void* z, int64_t ldz,
+                           const int32_t* targets, float* lse, float* rowloss, float* loss, float scale,
+                           int32_t backward) {
+  if (!dt_ok(dtype) || T < 1 || V < 1 || !z || !targets || !lse) return STAGE_ERR_ARG;
+  if (!backward && (!rowloss || !loss)) return STAGE_ERR_ARG;
+  return rc(backward ? ce_bwd((hipStream_t)stream, (DType)dtype, T, V, z, ldz, targets, lse, scale)
+                     : ce_fwd((hipStream_t)stream, (DType)dtype, T, V, z, ldz, targets, lse, rowloss, loss));
+}
+
+int stage_op_adamw(void* stream, int32_t dtype, int64_t n, int64_t begin, void* params, float* master, float* grad,
+                   float* m, float* v, float lr, float beta1, float beta2, float eps, float wd, int64_t t,
+                   float grad_scale) {
+  if (!dt_ok(dtype) || n < 0 || begin < 0 || t < 1 || !params || !grad || !m || !v) return STAGE_ERR_ARG;
+  if ((dtype == 1) != (master != nullptr)) return STAGE_ERR_ARG;
+  AdamW h;
+  h.lr = lr; h.beta1 = beta1; h.beta2 = beta2; h.eps = eps; h.wd = wd;
+  h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)t)));
+  h.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)beta2, (double)t)));
+  h.grad_scale = grad_scale;
+  return rc(adamw((hipStream_t)stream, (DType)dtype, n, begin, params, master, grad, m, v, h));
+}
+
+}  // extern "C"

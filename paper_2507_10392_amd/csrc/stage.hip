@@ -1,0 +1,725 @@
+// Host side of libstage: configuration checks, flat layout, workspace plan, the schedule's
+// state machine and the sequencing of kernels for forward, backward, accumulate and the
+// optimizer step of one pipeline (mini)stage.  Schedule and memory accounting follow the
+// paper's Sections 4.1.1-4.1.3 and its memory model; the layer math is the standard GPT /
+// Llama decoder layer.
+#include "../../include/stage.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace zs;
+
+namespace {
+
+thread_local std::string g_err;  // errors raised before a stage exists
+
+struct Seg { std::string name; int64_t off, rows, cols; };
+
+struct Shape {
+  int arch, L, H, nh, d, F, S, mb, T, M, V;
+  bool bf, embed, head, recompute;
+  int64_t E;  // bytes per element
+};
+
+Shape shape_of(const stage_config& c) {
+  Shape s;
+  s.arch = c.arch; s.L = c.layers; s.H = c.hidden; s.nh = c.heads; s.d = c.heads ? c.hidden / c.heads : 0;
+  s.F = c.ffn; s.S = c.seq; s.mb = c.microbatch; s.T = c.seq * c.microbatch; s.M = c.max_microbatches;
+  s.V = c.vocab; s.bf = c.dtype == STAGE_DTYPE_BF16; s.embed = c.has_embed != 0; s.head = c.has_head != 0;
+  s.recompute = c.recompute != 0; s.E = s.bf ? 2 : 4;
+  return s;
+}
+
+std::vector<Seg> make_layout(const stage_config& c) {
+  const int64_t H = c.hidden, F = c.ffn, V = c.vocab;
+  std::vector<Seg> v;
+  int64_t off = 0;
+  auto add = [&](const std::string& n, int64_t r, int64_t cc) { v.push_back({n, off, r, cc}); off += r * cc; };
+  if (c.has_embed) add("embed.E", V, H);
+  for (int l = 0; l < c.layers; ++l) {
+    const std::string p = "L" + std::to_string(l) + ".";
+    if (c.arch == STAGE_ARCH_GPT) {
+      add(p + "ln1.g", 1, H); add(p + "ln1.b", 1, H); add(p + "Wqkv", H, 3 * H); add(p + "bqkv", 1, 3 * H);
+      add(p + "Wo", H, H); add(p + "bo", 1, H); add(p + "ln2.g", 1, H); add(p + "ln2.b", 1, H);
+      add(p + "W1", H, F); add(p + "b1", 1, F); add(p + "W2", F, H); add(p + "b2", 1, H);
+    } else {
+      add(p + "rms1.g", 1, H); add(p + "Wq", H, H); add(p + "Wk", H, H); add(p + "Wv", H, H); add(p + "Wo", H, H);
+      add(p + "rms2.g", 1, H); add(p + "Wg", H, F); add(p + "Wu", H, F); add(p + "Wd", F, H);
+    }
+  }
+  if (c.has_head) { add("final_norm.g", 1, H); add("head.Wh", H, V); }
+  return v;
+}
+
+int64_t count_params(const stage_config& c) {
+  const int64_t H = c.hidden, F = c.ffn, V = c.vocab;
+  int64_t per = c.arch == STAGE_ARCH_GPT ? 4 * H * H + 2 * H * F + 9 * H + F : 4 * H * H + 3 * H * F + 2 * H;
+  int64_t n = per * c.layers;
+  if (c.has_embed) n += V * H;
+  if (c.has_head) n += H + H * V;
+  return n;
+}
+
+int validate(const stage_config* c, std::string& err) {
+  if (!c) { err = "config is NULL"; return STAGE_ERR_ARG; }
+  auto bad = [&](const char* m) { err = m; return STAGE_ERR_ARG; };
+  if (c->arch != STAGE_ARCH_GPT && c->arch != STAGE_ARCH_LLAMA) return bad("arch must be 0 (GPT) or 1 (Llama)");
+  if (c->dtype != STAGE_DTYPE_F32 && c->dtype != STAGE_DTYPE_BF16) return bad("dtype must be 0 (fp32) or 1 (bf16)");
+  if (c->layers < 1 || c->hidden < 8 || c->heads < 1 || c->ffn < 8 || c->seq < 1 || c->microbatch < 1)
+    return bad("layers, heads, seq, microbatch must be >= 1 and hidden, ffn >= 8");
+  if (c->max_microbatches < 1) return bad("max_microbatches must be >= 1");
+  if (c->hidden % c->heads) return bad("hidden must be a multiple of heads");
+  const int d = c->hidden / c->heads;
+  if (d % 8 || d > 256) return bad("head dim must be a multiple of 8 and at most 256");
+  if (c->hidden % 8 || c->ffn % 8) return bad("hidden and ffn must be multiples of 8 (16-byte rows)");
+  if ((int64_t)c->seq * c->microbatch > (1 << 24)) return bad("microbatch*seq too large");
+  if (c->has_embed || c->has_head) {
+    if (c->vocab < 8 || c->vocab % 8) return bad("vocab must be a positive multiple of 8 when has_embed or has_head");
+  }
+  if (c->recompute != 0 && c->recompute != 1) return bad("recompute must be 0 or 1");
+  if (c->act_budget_bytes < 0) return bad("act_budget_bytes must be >= 0");
+  const int64_t P = count_params(*c);
+  if (c->shard_begin < 0 || c->shard_end < c->shard_begin || c->shard_end > P) return bad("shard range outside [0, n_params]");
+  if (!(c->norm_eps > 0.f)) return bad("norm_eps must be > 0");
+  if (c->arch == STAGE_ARCH_LLAMA && !(c->rope_base > 0.f)) return bad("rope_base must be > 0");
+  if (!(c->beta1 >= 0.f && c->beta1 < 1.f && c->beta2 >= 0.f && c->beta2 < 1.f)) return bad("betas must be in [0,1)");
+  if (!(c->adam_eps > 0.f) || c->lr < 0.f || c->weight_decay < 0.f) return bad("adam_eps > 0, lr >= 0, weight_decay >= 0 required");
+  return STAGE_OK;
+}
+
+// ---- workspace plan -------------------------------------------------------------------------
+struct LayerActs {  // what a layer's backward needs from its forward
+  char *x_in, *n1, *qkv, *o, *x2, *n2, *ff /*[T,2F] gate|up, or [T,F] z*/, *a;
+  float *rstd1, *mean1, *rstd2, *mean2, *lse;
+};
+struct HeadActs { char *y, *nf, *logits; float *rstd, *lse, *rowloss; };
+
+struct Bump {
+  char* base; int64_t off = 0;
+  explicit Bump(char* b) : base(b) {}
+  template <typename P = char> P* take(int64_t bytes) {
+    off = (off + 255) & ~(int64_t)255;
+    char* p = base ? base + off : nullptr;
+    off += bytes;
+    return reinterpret_cast<P*>(p);
+  }
+};
+
+constexpr int MAX_NBLK = 128;
+
+struct Plan {
+  std::vector<LayerActs> acts;      // recompute ? 1 : M*L   (index mb*L + l)
+  std::vector<char*> stash;         // recompute: M*L layer inputs
+  std::vector<HeadActs> hacts;      // head: recompute ? 1 : M
+  std::vector<char*> hstash;        // head && recompute: M inputs of the final norm
+  std::vector<int32_t*> ids, targets;  // per slot copies
+  // scratch
+  char *gA, *gB, *gN, *gO, *gQKV, *gF1, *ytmp;
+  float* delta; float* lossdump;
+  float2* rope;
+  float* partials; int64_t partial_floats;
+  ReduceJob* jobs; int njobs_cap;
+  int nblk;
+  int64_t act_bytes = 0, scratch_bytes = 0, total = 0;
+};
+
+void plan_layer_acts(Bump& b, const Shape& s, LayerActs& a, bool with_x_in) {
+  const int64_t TH = (int64_t)s.T * s.H * s.E;
+  a.x_in = with_x_in ? b.take(TH) : nullptr;
+  a.n1 = b.take(TH);
+  a.qkv = b.take(3 * TH);
+  a.o = b.take(TH);
+  a.x2 = b.take(TH);
+  a.n2 = b.take(TH);
+  a.ff = b.take((int64_t)s.T * s.F * s.E * (s.arch == STAGE_ARCH_LLAMA ? 2 : 1));
+  a.a = b.take((int64_t)s.T * s.F * s.E);
+  a.rstd1 = b.take<float>(4ll * s.T);
+  a.rstd2 = b.take<float>(4ll * s.T);
+  a.mean1 = s.arch == STAGE_ARCH_GPT ? b.take<float>(4ll * s.T) : nullptr;
+  a.mean2 = s.arch == STAGE_ARCH_GPT ? b.take<float>(4ll * s.T) : nullptr;
+  a.lse = b.take<float>(4ll * s.mb * s.nh * s.S);
+}
+void plan_head_acts(Bump& b, const Shape& s, HeadActs& h, bool with_y) {
+  const int64_t TH = (int64_t)s.T * s.H * s.E;
+  h.y = with_y ? b.take(TH) : nullptr;
+  h.nf = b.take(TH);
+  h.logits = b.take((int64_t)s.T * s.V * s.E);
+  h.rstd = b.take<float>(4ll * s.T);
+  h.lse = b.take<float>(4ll * s.T);
+  h.rowloss = b.take<float>(4ll * s.T);
+}
+
+int64_t vector_widths_per_layer(const Shape& s) {   // summed widths of a layer's vector parameters
+  return s.arch == STAGE_ARCH_GPT ? 9ll * s.H + s.F : 2ll * s.H;
+}
+
+// One routine both sizes (base == NULL) and assigns the workspace, so the two can never disagree.
+void make_plan(const stage_config& c, char* base, Plan& p) {
+  const Shape s = shape_of(c);
+  const int64_t TH = (int64_t)s.T * s.H * s.E;
+  Bump b(base);
+  // ---- activations held between forward and backward
+  if (s.recompute) {
+    p.stash.resize((size_t)s.M * s.L);
+    // exactly M*L tensors of T*H elements, packed (Section 4.1.3's formula); TH is a multiple of 16 bytes
+    char* blockp = b.take((int64_t)s.M * s.L * TH);
+    for (int i = 0; i < s.M * s.L; ++i) p.stash[i] = blockp ? blockp + (int64_t)i * TH : nullptr;
+    if (s.head) {
+      p.hstash.resize(s.M);
+      for (int i = 0; i < s.M; ++i) p.hstash[i] = b.take(TH);
+    }
+  } else {
+    p.acts.resize((size_t)s.M * s.L);
+    for (auto& a : p.acts) plan_layer_acts(b, s, a, true);
+    if (s.head) { p.hacts.resize(s.M); for (auto& h : p.hacts) plan_head_acts(b, s, h, true); }
+  }
+  if (s.embed) { p.ids.resize(s.M); for (auto& q : p.ids) q = b.take<int32_t>(4ll * s.T); }
+  if (s.head) { p.targets.resize(s.M); for (auto& q : p.targets) q = b.take<int32_t>(4ll * s.T); }
+  p.act_bytes = b.off;
+  // ---- scratch live inside one call
+  if (s.recompute) {
+    p.acts.resize(1);
+    plan_layer_acts(b, s, p.acts[0], false);
+    if (s.head) { p.hacts.resize(1); plan_head_acts(b, s, p.hacts[0], false); }
+  }
+  p.gA = b.take(TH); p.gB = b.take(TH); p.gN = b.take(TH); p.gO = b.take(TH);
+  p.gQKV = b.take(3 * TH);
+  p.gF1 = b.take((int64_t)s.T * s.F * s.E);
+  p.ytmp = b.take(TH);
+  p.delta = b.take<float>(4ll * s.mb * s.nh * s.S);
+  p.lossdump = b.take<float>(256);
+  p.rope = s.arch == STAGE_ARCH_LLAMA ? b.take<float2>(8ll * s.S * (s.d / 2)) : nullptr;
+  p.nblk = s.T < MAX_NBLK ? s.T : MAX_NBLK;
+  p.partial_floats = (int64_t)p.nblk * (vector_widths_per_layer(s) * s.L + (s.head ? s.H : 0));
+  p.partials = b.take<float>(4 * p.partial_floats);
+  p.njobs_cap = s.L * 8 + 1;
+  p.jobs = b.take<ReduceJob>((int64_t)sizeof(ReduceJob) * p.njobs_cap);
+  p.total = (b.off + 255) & ~(int64_t)255;
+  p.scratch_bytes = p.total - p.act_bytes;
+}
+
+void memory_of(const stage_config& c, const Plan& p, stage_memory& m) {
+  const Shape s = shape_of(c);
+  const int64_t P = count_params(c), sh = c.shard_end - c.shard_begin;
+  m.params = P * s.E;
+  m.grads = P * 4;
+  m.optim = sh * 8 + (s.bf ? sh * 4 : 0);   // m, v (+ fp32 master of the shard)
+  m.activations = p.act_bytes;
+  m.scratch = p.scratch_bytes;
+  m.workspace = p.total;
+}
+
+// ---- profiling -------------------------------------------------------------------------------
+struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
+
+}  // namespace
+
+struct stage {
+  stage_config cfg;
+  Shape sh;
+  hipStream_t st;
+  char* params; float *master, *grad, *m, *v;
+  std::vector<Seg> layout;
+  Plan plan;
+  std::vector<int> slot;     // 0 empty, 1 forwarded, 2 backward done (waiting for accumulate)
+  int pending = -1;          // slot whose backward waits for stage_accumulate
+  int outstanding = 0, accumulated = 0;
+  std::vector<ReduceJob> jobs_host;
+  int njobs = 0, max_job_width = 0;
+  std::string err;
+  // profiling
+  bool prof = false;
+  std::vector<std::string> cls_names;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_used = 0;
+
+  int64_t seg_off(const std::string& n) const {
+    for (auto& s : layout) if (s.name == n) return s.off;
+    return -1;
+  }
+  char* P(int64_t off) const { return params + off * sh.E; }
+  float* G(int64_t off) const { return grad + off; }
+};
+
+namespace {
+
+int fail(stage_t* s, int code, const std::string& msg) { if (s) s->err = msg; else g_err = msg; return code; }
+
+int cls_id(stage_t* s, const char* name) {
+  for (size_t i = 0; i < s->cls_names.size(); ++i) if (s->cls_names[i] == name) return (int)i;
+  s->cls_names.push_back(name);
+  return (int)s->cls_names.size() - 1;
+}
+hipEvent_t next_event(stage_t* s) {
+  if (s->ev_used == s->ev_pool.size()) { hipEvent_t e = nullptr; (void)hipEventCreate(&e); s->ev_pool.push_back(e); }
+  return s->ev_pool[s->ev_used++];
+}
+
+// Runs one launcher, optionally bracketed by events; returns false (and sets the error) on failure.
+template <typename F> bool run(stage_t* s, const char* cls, double flops, double bytes, F&& f) {
+  hipEvent_t a = nullptr, b = nullptr;
+  if (s->prof) { a = next_event(s); b = next_event(s); (void)hipEventRecord(a, s->st); }
+  const hipError_t e = f();
+  if (s->prof) { (void)hipEventRecord(b, s->st); s->recs.push_back({cls_id(s, cls), a, b, flops, bytes}); }
+  if (e != hipSuccess) { s->err = std::string(cls) + ": " + hipGetErrorString(e); return false; }
+  return true;
+}
+
+DType dt_of(const stage_t* s) { return s->sh.bf ? BF16 : F32; }
+
+bool do_gemm(stage_t* s, const Gemm& g) {
+  const int impl = gemm_select(dt_of(s), g, GEMM_AUTO);
+  static const char* names[2][4] = {{"gemm_simple_nn", "gemm_simple_nt", "gemm_simple_tn", "gemm_simple_tt"},
+                                    {"gemm_mfma_nn", "gemm_mfma_nt", "gemm_mfma_tn", "gemm_mfma_tt"}};
+  const char* cls = names[impl == GEMM_MFMA][g.transA * 2 + g.transB];
+  const double flops = 2.0 * g.M * g.N * g.K * g.batch;
+  return run(s, cls, flops, 0.0, [&] { return gemm(s->st, dt_of(s), g, GEMM_AUTO); });
+}
+
+// ---- forward of one layer ---------------------------------------------------------------------
+// x_in -> y (y may be NULL: recompute pass, the output is not needed).
+bool layer_forward(stage_t* s, int l, const char* x_in, LayerActs& A, char* y) {
+  const Shape& h = s->sh;
+  const DType dt = dt_of(s);
+  const int T = h.T, H = h.H, F = h.F;
+  const std::string p = "L" + std::to_string(l) + ".";
+  const double thb = (double)T * H * h.E;
+  const bool gpt = h.arch == STAGE_ARCH_GPT;
+  auto W = [&](const char* n) { return s->P(s->seg_off(p + n)); };
+
+  if (!run(s, "norm_fwd", 0, 2 * thb, [&] {
+        return gpt ? norm_fwd(s->st, dt, 0, T, H, x_in, W("ln1.g"), W("ln1.b"), s->cfg.norm_eps, A.n1, A.rstd1, A.mean1)
+                   : norm_fwd(s->st, dt, 1, T, H, x_in, W("rms1.g"), nullptr, s->cfg.norm_eps, A.n1, A.rstd1, nullptr); }))
+    return false;
+  Gemm g;
+  g.M = T; g.K = H; g.A = A.n1; g.lda = H; g.C = A.qkv; g.ldc = 3 * H;
+  if (gpt) { g.N = 3 * H; g.B = W("Wqkv"); g.ldb = 3 * H; g.bias = W("bqkv"); }
+  else { g.N = H; g.B = W("Wq"); g.ldb = H; g.batch = 3; g.sB = (int64_t)H * H; g.sC = H; }
+  if (!do_gemm(s, g)) return false;
+  if (!gpt && !run(s, "rope", 0, 2.0 * 2 * thb, [&] {
+        return rope_apply(s->st, dt, T, h.S, 2 * H, h.d, A.qkv, 3 * H, s->plan.rope, 1.0f); }))
+    return false;
+  const double attn_flops = 4.0 * h.mb * h.nh * (double)h.S * (h.S + 1) / 2 * h.d;
+  if (!run(s, attn_select(dt, h.S, h.d, 0) == ATTN_MFMA ? "attn_fwd_mfma" : "attn_fwd_simple", attn_flops, 0, [&] {
+        return attn_fwd(s->st, dt, h.mb, h.S, h.nh, h.d, A.qkv, A.qkv + (int64_t)H * h.E, A.qkv + 2ll * H * h.E, 3 * H,
+                        A.o, H, A.lse, ATTN_AUTO); }))
+    return false;
+  g = Gemm();
+  g.M = T; g.N = H; g.K = H; g.A = A.o; g.lda = H; g.B = W("Wo"); g.ldb = H; g.C = A.x2; g.ldc = H;
+  g.resid = x_in; g.ldr = H; if (gpt) g.bias = W("bo");
+  if (!do_gemm(s, g)) return false;
+  if (!run(s, "norm_fwd", 0, 2 * thb, [&] {
+        return gpt ? norm_fwd(s->st, dt, 0, T, H, A.x2, W("ln2.g"), W("ln2.b"), s->cfg.norm_eps, A.n2, A.rstd2, A.mean2)
+                   : norm_fwd(s->st, dt, 1, T, H, A.x2, W("rms2.g"), nullptr, s->cfg.norm_eps, A.n2, A.rstd2, nullptr); }))
+    return false;
+  g = Gemm();
+  g.M = T; g.K = H; g.A = A.n2; g.lda = H; g.C = A.ff;
+  if (gpt) { g.N = F; g.B = W("W1"); g.ldb = F; g.ldc = F; g.bias = W("b1"); }
+  else { g.N = F; g.B = W("Wg"); g.ldb = F; g.ldc = 2 * F; g.batch = 2; g.sB = (int64_t)H * F; g.sC = F; }
+  if (!do_gemm(s, g)) return false;
+  const double tfb = (double)T * F * h.E;
+  if (!run(s, "activation", 0, gpt ? 2 * tfb : 3 * tfb, [&] {
+        return gpt ? gelu_fwd(s->st, dt, (int64_t)T * F, A.ff, A.a) : swiglu_fwd(s->st, dt, T, F, A.ff, A.a); }))
+    return false;
+  if (!y) return true;
+  g = Gemm();
+  g.M = T; g.N = H; g.K = F; g.A = A.a; g.lda = F; g.B = gpt ? W("W2") : W("Wd"); g.ldb = H; g.C = y; g.ldc = H;
+  g.resid = A.x2; g.ldr = H; if (gpt) g.bias = W("b2");
+  return do_gemm(s, g);
+}
+
+// Partials of the vector parameters: segment -> float[nblk, width] inside plan.partials.
+float* partial_of(stage_t* s, const std::string& name) {
+  for (int i = 0; i < s->njobs; ++i)
+    if (s->jobs_host[i].dst == s->G(s->seg_off(name))) return const_cast<float*>(s->jobs_host[i].part);
+  return nullptr;
+}
+
+bool colsum(stage_t* s, const std::string& seg, int N, const void* a, int64_t lda, const void* x, const float* rstd,
+            const float* mean) {
+  const Shape& h = s->sh;
+  float* part = partial_of(s, seg);
+  return run(s, "colsum", 0, (double)h.T * N * h.E * (x ? 2 : 1), [&] {
+    return colsum_partial(s->st, dt_of(s), h.T, N, a, lda, x, N, rstd, mean, part, s->plan.nblk); });
+}
+
+// ---- backward of one layer ----------------------------------------------------------------------
+// dy -> dx.  dy and dx are distinct [T,H] buffers; tmp is a third one (holds dx2).
+bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const char* dy, char* tmp, char* dx) {
+  const Shape& h = s->sh;
+  const DType dt = dt_of(s);
+  const int T = h.T, H = h.H, F = h.F;
+  const std::string p = "L" + std::to_string(l) + ".";
+  const bool gpt = h.arch == STAGE_ARCH_GPT;
+  const double thb = (double)T * H * h.E, tfb = (double)T * F * h.E;
+  Plan& pl = s->plan;
+  auto W = [&](const char* n) { return s->P(s->seg_off(p + n)); };
+  auto GW = [&](const char* n) { return s->G(s->seg_off(p + n)); };
+  Gemm g;
+
+  // FFN down projection: da = dy Wd^T ; dWd += a^T dy
+  g.M = T; g.N = F; g.K = H; g.A = dy; g.lda = H; g.B = gpt ? W("W2") : W("Wd"); g.ldb = H; g.transB = 1;
+  g.C = pl.gF1; g.ldc = F;
+  if (!do_gemm(s, g)) return false;
+  g = Gemm();
+  g.M = F; g.N = H; g.K = T; g.A = A.a; g.lda = F; g.transA = 1; g.B = dy; g.ldb = H;
+  g.C = gpt ? GW("W2") : GW("Wd"); g.ldc = H; g.c_f32_accum = 1;
+  if (!do_gemm(s, g)) return false;
+  if (gpt && !colsum(s, p + "b2", H, dy, H, nullptr, nullptr, nullptr)) return false;
+
+  // activation backward, in place over the saved pre-activations
+  if (!run(s, "activation", 0, gpt ? 3 * tfb : 5 * tfb, [&] {
+        return gpt ? gelu_bwd(s->st, dt, (int64_t)T * F, A.ff, pl.gF1, A.ff)
+                   : swiglu_bwd(s->st, dt, T, F, A.ff, pl.gF1, A.ff); }))
+    return false;
+  const char* dff = A.ff;   // dz [T,F] or [dgate | dup] [T,2F]
+
+  // FFN up projection(s): dn2 = dff W^T ; dW += n2^T dff
+  g = Gemm();
+  g.M = T; g.N = H; g.A = dff; g.transB = 1; g.C = pl.gN; g.ldc = H; g.ldb = F;
+  if (gpt) { g.K = F; g.lda = F; g.B = W("W1"); }
+  else { g.K = 2 * F; g.lda = 2 * F; g.B = W("Wg"); g.kseg = F; g.segB = (int64_t)H * F; }
+  if (!do_gemm(s, g)) return false;
+  g = Gemm();
+  g.M = H; g.N = F; g.K = T; g.A = A.n2; g.lda = H; g.transA = 1; g.B = dff; g.c_f32_accum = 1; g.ldc = F;
+  if (gpt) { g.ldb = F; g.C = GW("W1"); }
+  else { g.ldb = 2 * F; g.C = GW("Wg"); g.batch = 2; g.sB = F; g.sC = (int64_t)H * F; }
+  if (!do_gemm(s, g)) return false;
+  if (gpt && !colsum(s, p + "b1", F, dff, F, nullptr, nullptr, nullptr)) return false;
+
+  // second norm: gain (and bias) partials, dx2 = dy + norm'(x2)^T dn2
+  if (!colsum(s, p + (gpt ? "ln2.g" : "rms2.g"), H, pl.gN, H, A.x2, A.rstd2, A.mean2)) return false;
+  if (gpt && !colsum(s, p + "ln2.b", H, pl.gN, H, nullptr, nullptr, nullptr)) return false;
+  if (!run(s, "norm_bwd", 0, 4 * thb, [&] {
+        return norm_bwd(s->st, dt, gpt ? 0 : 1, T, H, pl.gN, A.x2, gpt ? W("ln2.g") : W("rms2.g"), A.rstd2, A.mean2, dy, tmp); }))
+    return false;
+
+  // attention output projection: do = dx2 Wo^T ; dWo += o^T dx2
+  g = Gemm();
+  g.M = T; g.N = H; g.K = H; g.A = tmp; g.lda = H; g.B = W("Wo"); g.ldb = H; g.transB = 1; g.C = pl.gO; g.ldc = H;
+  if (!do_gemm(s, g)) return false;
+  g = Gemm();
+  g.M = H; g.N = H; g.K = T; g.A = A.o; g.lda = H; g.transA = 1; g.B = tmp; g.ldb = H; g.C = GW("Wo"); g.ldc = H;
+  g.c_f32_accum = 1;
+  if (!do_gemm(s, g)) return false;
+  if (gpt && !colsum(s, p + "bo", H, tmp, H, nullptr, nullptr, nullptr)) return false;
+
+  // attention backward (+ inverse rotation of dq, dk)
+  // algorithmic work: dV, dP, dQ, dK over the causal half (recomputing the scores is not counted)
+  const double attn_flops = 8.0 * h.mb * h.nh * (double)h.S * (h.S + 1) / 2 * h.d;
+  const int64_t HE = (int64_t)H * h.E;
+  if (!run(s, attn_select(dt, h.S, h.d, 0) == ATTN_MFMA ? "attn_bwd_mfma" : "attn_bwd_simple", attn_flops, 0, [&] {
+        return attn_bwd(s->st, dt, h.mb, h.S, h.nh, h.d, A.qkv, A.qkv + HE, A.qkv + 2 * HE, 3 * H, A.o, pl.gO, H, A.lse,
+                        pl.delta, pl.gQKV, pl.gQKV + HE, pl.gQKV + 2 * HE, 3 * H, ATTN_AUTO); }))
+    return false;
+  if (!gpt && !run(s, "rope", 0, 2.0 * 2 * thb, [&] {
+        return rope_apply(s->st, dt, T, h.S, 2 * H, h.d, pl.gQKV, 3 * H, pl.rope, -1.0f); }))
+    return false;
+
+  // QKV projection: dn1 = dqkv [Wq|Wk|Wv]^T ; dW += n1^T dqkv
+  g = Gemm();
+  g.M = T; g.N = H; g.K = 3 * H; g.A = pl.gQKV; g.lda = 3 * H; g.transB = 1; g.C = pl.gN; g.ldc = H;
+  if (gpt) { g.B = W("Wqkv"); g.ldb = 3 * H; }
+  else { g.B = W("Wq"); g.ldb = H; g.kseg = H; g.segB = (int64_t)H * H; }
+  if (!do_gemm(s, g)) return false;
+  g = Gemm();
+  g.M = H; g.K = T; g.A = A.n1; g.lda = H; g.transA = 1; g.B = pl.gQKV; g.ldb = 3 * H; g.c_f32_accum = 1;
+  if (gpt) { g.N = 3 * H; g.C = GW("Wqkv"); g.ldc = 3 * H; }
+  else { g.N = H; g.C = GW("Wq"); g.ldc = H; g.batch = 3; g.sB = H; g.sC = (int64_t)H * H; }
+  if (!do_gemm(s, g)) return false;
+  if (gpt && !colsum(s, p + "bqkv", 3 * H, pl.gQKV, 3 * H, nullptr, nullptr, nullptr)) return false;
+
+  // first norm: dx = dx2 + norm'(x)^T dn1
+  if (!colsum(s, p + (gpt ? "ln1.g" : "rms1.g"), H, pl.gN, H, x_in, A.rstd1, A.mean1)) return false;
+  if (gpt && !colsum(s, p + "ln1.b", H, pl.gN, H, nullptr, nullptr, nullptr)) return false;
+  return run(s, "norm_bwd", 0, 4 * thb, [&] {
+    return norm_bwd(s->st, dt, gpt ? 0 : 1, T, H, pl.gN, x_in, gpt ? W("ln1.g") : W("rms1.g"), A.rstd1, A.mean1, tmp, dx); });
+}
+
+bool head_forward(stage_t* s, const char* y, HeadActs& A, const int32_t* targets, float* loss_out) {
+  const Shape& h = s->sh;
+  const DType dt = dt_of(s);
+  if (!run(s, "norm_fwd", 0, 2.0 * h.T * h.H * h.E, [&] {
+        return norm_fwd(s->st, dt, 1, h.T, h.H, y, s->P(s->seg_off("final_norm.g")), nullptr, s->cfg.norm_eps, A.nf, A.rstd, nullptr); }))
+    return false;
+  Gemm g;
+  g.M = h.T; g.N = h.V; g.K = h.H; g.A = A.nf; g.lda = h.H; g.B = s->P(s->seg_off("head.Wh")); g.ldb = h.V;
+  g.C = A.logits; g.ldc = h.V;
+  if (!do_gemm(s, g)) return false;
+  return run(s, "cross_entropy", 0, (double)h.T * h.V * h.E, [&] {
+    return ce_fwd(s->st, dt, h.T, h.V, A.logits, h.V, targets, A.lse, A.rowloss, loss_out); });
+}
+
+bool head_backward(stage_t* s, const char* y, HeadActs& A, const int32_t* targets, float loss_scale, char* dcur) {
+  const Shape& h = s->sh;
+  const DType dt = dt_of(s);
+  Plan& pl = s->plan;
+  if (!run(s, "cross_entropy", 0, 2.0 * h.T * h.V * h.E, [&] {
+        return ce_bwd(s->st, dt, h.T, h.V, A.logits, h.V, targets, A.lse, loss_scale / (float)h.T); }))
+    return false;
+  Gemm g;
+  g.M = h.H; g.N = h.V; g.K = h.T; g.A = A.nf; g.lda = h.H; g.transA = 1; g.B = A.logits; g.ldb = h.V;
+  g.C = s->G(s->seg_off("head.Wh")); g.ldc = h.V; g.c_f32_accum = 1;
+  if (!do_gemm(s, g)) return false;
+  g = Gemm();
+  g.M = h.T; g.N = h.H; g.K = h.V; g.A = A.logits; g.lda = h.V; g.B = s->P(s->seg_off("head.Wh")); g.ldb = h.V;
+  g.transB = 1; g.C = pl.gN; g.ldc = h.H;
+  if (!do_gemm(s, g)) return false;
+  if (!colsum(s, "final_norm.g", h.H, pl.gN, h.H, y, A.rstd, nullptr)) return false;
+  return run(s, "norm_bwd", 0, 3.0 * h.T * h.H * h.E, [&] {
+    return norm_bwd(s->st, dt, 1, h.T, h.H, pl.gN, y, s->P(s->seg_off("final_norm.g")), A.rstd, nullptr, nullptr, dcur); });
+}
+
+bool check_slot(stage_t* s, int mb) { return mb >= 0 && mb < s->sh.M; }
+
+}  // namespace
+
+extern "C" {
+
+int stage_query(const stage_config* cfg, int64_t* n_params, stage_memory* mem, int32_t* n_segments) {
+  std::string err;
+  const int rc = validate(cfg, err);
+  if (rc != STAGE_OK) return fail(nullptr, rc, err);
+  Plan p;
+  make_plan(*cfg, nullptr, p);
+  stage_memory m;
+  memory_of(*cfg, p, m);
+  if (n_params) *n_params = count_params(*cfg);
+  if (mem) *mem = m;
+  if (n_segments) *n_segments = (int32_t)make_layout(*cfg).size();
+  if (cfg->act_budget_bytes > 0 && m.activations + m.scratch > cfg->act_budget_bytes)
+    return fail(nullptr, STAGE_ERR_BUDGET, "activations + scratch = " + std::to_string(m.activations + m.scratch) +
+                                               " bytes exceed act_budget_bytes = " + std::to_string(cfg->act_budget_bytes));
+  return STAGE_OK;
+}
+
+int stage_layout(const stage_config* cfg, stage_segment* out, int32_t n_segments) {
+  std::string err;
+  const int rc = validate(cfg, err);
+  if (rc != STAGE_OK) return fail(nullptr, rc, err);
+  const auto lay = make_layout(*cfg);
+  if (!out || n_segments != (int32_t)lay.size()) return fail(nullptr, STAGE_ERR_ARG, "n_segments does not match stage_query");
+  for (size_t i = 0; i < lay.size(); ++i) {
+    std::memset(out[i].name, 0, sizeof(out[i].name));
+    std::strncpy(out[i].name, lay[i].name.c_str(), sizeof(out[i].name) - 1);
+    out[i].offset = lay[i].off; out[i].rows = lay[i].rows; out[i].cols = lay[i].cols;
+  }
+  return STAGE_OK;
+}
+
+int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* master, float* grad_acc, float* adam_m,
+               float* adam_v, void* workspace, int64_t workspace_bytes, stage_t** out) {
+  if (out) *out = nullptr;
+  if (!out) return fail(nullptr, STAGE_ERR_ARG, "out is NULL");
+  stage_memory mem;
+  const int rc = stage_query(cfg, nullptr, &mem, nullptr);
+  if (rc != STAGE_OK) return rc;
+  const int64_t sh = cfg->shard_end - cfg->shard_begin;
+  if (!params || !grad_acc) return fail(nullptr, STAGE_ERR_ARG, "params and grad_acc must not be NULL");
+  if (sh > 0 && (!adam_m || !adam_v)) return fail(nullptr, STAGE_ERR_ARG, "adam_m and adam_v must not be NULL");
+  if (cfg->dtype == STAGE_DTYPE_BF16 && sh > 0 && !master) return fail(nullptr, STAGE_ERR_ARG, "master must not be NULL for dtype 1");
+  if (cfg->dtype == STAGE_DTYPE_F32 && master) return fail(nullptr, STAGE_ERR_ARG, "master must be NULL for dtype 0");
+  if (((uintptr_t)params | (uintptr_t)grad_acc | (uintptr_t)master | (uintptr_t)adam_m | (uintptr_t)adam_v) & 15)
+    return fail(nullptr, STAGE_ERR_ARG, "params, master, grad_acc, adam_m, adam_v must be 16-byte aligned");
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(nullptr, STAGE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  if (workspace_bytes < mem.workspace)
+    return fail(nullptr, STAGE_ERR_WORKSPACE, "workspace has " + std::to_string(workspace_bytes) + " bytes, " +
+                                                  std::to_string(mem.workspace) + " needed");
+  stage_t* s = new stage();
+  s->cfg = *cfg;
+  s->sh = shape_of(*cfg);
+  s->st = (hipStream_t)hip_stream;
+  s->params = (char*)params; s->master = master; s->grad = grad_acc; s->m = adam_m; s->v = adam_v;
+  s->layout = make_layout(*cfg);
+  make_plan(*cfg, (char*)workspace, s->plan);
+  s->slot.assign(s->sh.M, 0);
+
+  // reduction jobs of the vector parameters, partial buffers carved in layout order
+  float* pp = s->plan.partials;
+  for (auto& seg : s->layout) {
+    if (seg.rows != 1) continue;
+    ReduceJob j;
+    j.part = pp; j.dst = s->G(seg.off); j.nblk = s->plan.nblk; j.width = (int)seg.cols;
+    pp += (int64_t)s->plan.nblk * seg.cols;
+    s->jobs_host.push_back(j);
+    if ((int)seg.cols > s->max_job_width) s->max_job_width = (int)seg.cols;
+  }
+  s->njobs = (int)s->jobs_host.size();
+  hipError_t e = hipSuccess;
+  if (s->njobs)
+    e = hipMemcpyAsync(s->plan.jobs, s->jobs_host.data(), sizeof(ReduceJob) * s->njobs, hipMemcpyHostToDevice, s->st);
+  if (e == hipSuccess && s->plan.rope) e = rope_table(s->st, s->sh.S, s->sh.d, cfg->rope_base, s->plan.rope);
+  if (e != hipSuccess) {
+    const std::string msg = std::string("stage_init: ") + hipGetErrorString(e);
+    delete s;
+    return fail(nullptr, STAGE_ERR_DEVICE, msg);
+  }
+  *out = s;
+  return STAGE_OK;
+}
+
+int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, const int32_t* targets, float* loss_out) {
+  if (!s) return STAGE_ERR_ARG;
+  const Shape& h = s->sh;
+  if (!check_slot(s, mb)) return fail(s, STAGE_ERR_ARG, "microbatch slot out of range");
+  if (!x_or_ids) return fail(s, STAGE_ERR_ARG, "x_or_ids is NULL");
+  if (h.head && (!targets || !loss_out)) return fail(s, STAGE_ERR_ARG, "targets and loss_out are required when has_head");
+  if (!h.head && !y_out) return fail(s, STAGE_ERR_ARG, "y_out is NULL");
+  if (s->pending >= 0) return fail(s, STAGE_ERR_STATE, "a backward is waiting for stage_accumulate");
+  if (s->slot[mb] != 0) return fail(s, STAGE_ERR_STATE, "slot already holds a forward that was not backpropagated");
+  Plan& pl = s->plan;
+  const DType dt = dt_of(s);
+  const int64_t TH = (int64_t)h.T * h.H * h.E;
+
+  auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)mb * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
+  char* x0 = in_of(0);
+  if (h.embed) {
+    if (!run(s, "copy", 0, 8.0 * h.T, [&] { return copy_bytes(s->st, pl.ids[mb], x_or_ids, 4ll * h.T); })) return STAGE_ERR_DEVICE;
+    if (!run(s, "embed", 0, 2.0 * TH, [&] {
+          return embed_fwd(s->st, dt, h.T, h.H, h.V, pl.ids[mb], s->P(s->seg_off("embed.E")), x0); }))
+      return STAGE_ERR_DEVICE;
+  } else if (!run(s, "copy", 0, 2.0 * TH, [&] { return copy_bytes(s->st, x0, x_or_ids, TH); })) {
+    return STAGE_ERR_DEVICE;
+  }
+  char* final_y = nullptr;
+  if (h.head) final_y = h.recompute ? pl.hstash[mb] : pl.hacts[mb].y;
+  for (int l = 0; l < h.L; ++l) {
+    LayerActs& A = h.recompute ? pl.acts[0] : pl.acts[(size_t)mb * h.L + l];
+    char* y = l + 1 < h.L ? in_of(l + 1) : (h.head ? final_y : (char*)y_out);
+    if (!layer_forward(s, l, in_of(l), A, y)) return STAGE_ERR_DEVICE;
+  }
+  if (h.head) {
+    if (!run(s, "copy", 0, 8.0 * h.T, [&] { return copy_bytes(s->st, pl.targets[mb], targets, 4ll * h.T); })) return STAGE_ERR_DEVICE;
+    HeadActs& HA = h.recompute ? pl.hacts[0] : pl.hacts[mb];
+    if (!head_forward(s, final_y, HA, pl.targets[mb], loss_out)) return STAGE_ERR_DEVICE;
+    if (y_out && !run(s, "copy", 0, 2.0 * TH, [&] { return copy_bytes(s->st, y_out, final_y, TH); })) return STAGE_ERR_DEVICE;
+  }
+  s->slot[mb] = 1;
+  s->outstanding++;
+  return STAGE_OK;
+}
+
+int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float loss_scale) {
+  if (!s) return STAGE_ERR_ARG;
+  const Shape& h = s->sh;
+  if (!check_slot(s, mb)) return fail(s, STAGE_ERR_ARG, "microbatch slot out of range");
+  if (!h.head && !dy) return fail(s, STAGE_ERR_ARG, "dy is NULL");
+  if (!h.embed && !dx_out) return fail(s, STAGE_ERR_ARG, "dx_out is NULL");
+  if (s->pending >= 0) return fail(s, STAGE_ERR_STATE, "the previous backward is waiting for stage_accumulate");
+  if (s->slot[mb] != 1) return fail(s, STAGE_ERR_STATE, "slot holds no forward");
+  Plan& pl = s->plan;
+  const int64_t TH = (int64_t)h.T * h.H * h.E;
+
+  auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)mb * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
+  // cur: gradient entering the layer (never written); its dx goes to the other scratch buffer
+  const char* cur = h.head ? pl.gA : (const char*)dy;
+  char* bufs[2] = {pl.gB, pl.gA};
+  int bi = 0;
+  if (h.head) {
+    char* final_y = h.recompute ? pl.hstash[mb] : pl.hacts[mb].y;
+    HeadActs& HA = h.recompute ? pl.hacts[0] : pl.hacts[mb];
+    if (h.recompute && !head_forward(s, final_y, HA, pl.targets[mb], pl.lossdump)) return STAGE_ERR_DEVICE;
+    if (!head_backward(s, final_y, HA, pl.targets[mb], loss_scale, pl.gA)) return STAGE_ERR_DEVICE;
+  }
+  for (int l = h.L - 1; l >= 0; --l) {
+    LayerActs& A = h.recompute ? pl.acts[0] : pl.acts[(size_t)mb * h.L + l];
+    if (h.recompute && !layer_forward(s, l, in_of(l), A, nullptr)) return STAGE_ERR_DEVICE;
+    char* dst = (l == 0 && !h.embed) ? (char*)dx_out : bufs[bi];
+    if (!layer_backward(s, l, in_of(l), A, cur, pl.ytmp, dst)) return STAGE_ERR_DEVICE;
+    cur = dst;
+    bi ^= 1;
+  }
+  if (h.embed) {
+    // cur now holds the gradient of the embedding output
+    if (!run(s, "embed", 0, 3.0 * TH, [&] {
+          return embed_bwd(s->st, dt_of(s), h.T, h.H, h.V, pl.ids[mb], cur, s->G(s->seg_off("embed.E"))); }))
+      return STAGE_ERR_DEVICE;
+  }
+  s->slot[mb] = 2;
+  s->pending = mb;
+  return STAGE_OK;
+}
+
+int stage_accumulate(stage_t* s, int32_t mb) {
+  if (!s) return STAGE_ERR_ARG;
+  if (!check_slot(s, mb)) return fail(s, STAGE_ERR_ARG, "microbatch slot out of range");
+  if (s->pending != mb) return fail(s, STAGE_ERR_STATE, "stage_accumulate must follow stage_backward of the same slot");
+  if (!run(s, "reduce_partials", 0, 4.0 * s->plan.partial_floats, [&] {
+        return reduce_partials(s->st, s->plan.jobs, s->njobs, s->max_job_width); }))
+    return STAGE_ERR_DEVICE;
+  s->slot[mb] = 0;
+  s->pending = -1;
+  s->outstanding--;
+  s->accumulated++;
+  return STAGE_OK;
+}
+
+int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale) {
+  if (!s) return STAGE_ERR_ARG;
+  if (t < 1) return fail(s, STAGE_ERR_ARG, "t is 1-based");
+  if (s->pending >= 0 || s->outstanding != 0)
+    return fail(s, STAGE_ERR_STATE, "microbatches are still outstanding (forward without backward+accumulate)");
+  if (s->accumulated == 0) return fail(s, STAGE_ERR_STATE, "no microbatch was accumulated since the last step");
+  const stage_config& c = s->cfg;
+  AdamW h;
+  h.lr = c.lr; h.beta1 = c.beta1; h.beta2 = c.beta2; h.eps = c.adam_eps; h.wd = c.weight_decay;
+  h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)c.beta1, (double)t)));
+  h.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)c.beta2, (double)t)));
+  h.grad_scale = grad_scale;
+  const int64_t P = count_params(c), b = c.shard_begin, e = c.shard_end, n = e - b;
+  const double per = s->sh.bf ? 30.0 : 28.0;
+  if (!run(s, "adamw", 0, per * n, [&] {
+        return adamw(s->st, dt_of(s), n, b, s->params, s->master, s->grad, s->m, s->v, h); }))
+    return STAGE_ERR_DEVICE;
+  // gradients outside the shard are dropped too (their owners are the data-parallel peers)
+  if (!run(s, "zero_grads", 0, 4.0 * (P - n), [&] {
+        hipError_t er = fill_zero(s->st, s->grad, b);
+        return er != hipSuccess ? er : fill_zero(s->st, s->grad + e, P - e); }))
+    return STAGE_ERR_DEVICE;
+  s->accumulated = 0;
+  return STAGE_OK;
+}
+
+int stage_profile(stage_t* s, int32_t enable) {
+  if (!s) return STAGE_ERR_ARG;
+  s->prof = enable != 0;
+  return STAGE_OK;
+}
+
+int stage_profile_read(stage_t* s, stage_kernel_stat* out, int32_t n) {
+  if (!s || !out || n < 0) return -STAGE_ERR_ARG;
+  if (hipStreamSynchronize(s->st) != hipSuccess) return -STAGE_ERR_DEVICE;
+  const int nc = (int)s->cls_names.size() < n ? (int)s->cls_names.size() : n;
+  for (int i = 0; i < nc; ++i) {
+    std::memset(&out[i], 0, sizeof(out[i]));
+    std::strncpy(out[i].name, s->cls_names[i].c_str(), sizeof(out[i].name) - 1);
+  }
+  for (auto& r : s->recs) {
+    if (r.cls >= nc) continue;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) return -STAGE_ERR_DEVICE;
+    out[r.cls].launches++;
+    out[r.cls].ms += ms;
+    out[r.cls].flops += r.flops;
+    out[r.cls].bytes += r.bytes;
+  }
+  s->recs.clear();
+  s->ev_used = 0;
+  return nc;
+}
+
+const char* stage_last_error(const stage_t* s) { return s ? s->err.c_str() : g_err.c_str(); }
+
+void stage_destroy(stage_t* s) {
+  if (!s) return;
+  for (auto e : s->ev_pool) (void)hipEventDestroy(e);
+  delete s;
+}
+
+}  // extern "C"

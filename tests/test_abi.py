@@ -1,0 +1,112 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and the host-side
+validation, layout and memory accounting behave as the header states.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2507_10392_amd as zs
+from oracle import stage_oracle as so
+from workloads import CONFIGS, get_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = []
+    for h in ("stage.h", "stage_ops.h"):
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(stage_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    L = zs.lib()
+    syms = declared_symbols()
+    assert {"stage_query", "stage_layout", "stage_init", "stage_forward", "stage_backward", "stage_accumulate",
+            "stage_optimizer_step", "stage_last_error", "stage_destroy", "stage_op_gemm", "stage_op_adamw"} <= set(syms)
+    for s in syms:
+        assert hasattr(L, s), s
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_layout_and_param_count_match_oracle(name):
+    cfg = get_config(name)
+    cc = zs.make_config(cfg)
+    P, mem, ns = zs.query(cc) if cfg.name != "C4b" else zs.query(cc)
+    assert P == cfg.n_params == so.n_params(cfg)
+    assert zs.layout(cc) == so.layout(cfg)
+    E = 2 if cfg.dtype else 4
+    sh = cfg.shard_range[1] - cfg.shard_range[0]
+    assert mem["params"] == P * E and mem["grads"] == 4 * P
+    assert mem["optim"] == sh * (12 if cfg.dtype else 8)
+    assert mem["workspace"] >= mem["activations"] + mem["scratch"] and mem["workspace"] % 256 == 0
+
+
+def test_recompute_stash_is_exactly_the_papers_formula():
+    """Section 4.1.3: B x L boundary activations of S x H x D bytes each."""
+    for name in ("C4b", "C4bt"):
+        cfg = get_config(name)
+        _, mem, _ = zs.query(zs.make_config(cfg))
+        assert mem["activations"] == cfg.num_microbatches * cfg.layers * cfg.tokens * cfg.hidden * 2
+    c3 = get_config("C3")
+    _, full, _ = zs.query(zs.make_config(c3))
+    _, rc, _ = zs.query(zs.make_config(c3.with_(recompute=1)))
+    assert rc["activations"] == 16 * 8 * 4096 * 4096 * 2 and full["activations"] > 10 * rc["activations"]
+
+
+def test_bad_configs_are_rejected_on_the_host():
+    cfg = get_config("C1")
+    for kw in (dict(heads=3), dict(hidden=250, heads=5), dict(layers=0), dict(arch=2), dict(dtype=3),
+               dict(recompute=2), dict(has_head=1, vocab=0), dict(norm_eps=0.0), dict(beta1=1.0)):
+        with pytest.raises(zs.StageError) as ei:
+            zs.query(zs.make_config(cfg.with_(**kw)))
+        assert ei.value.code == zs.STAGE_ERR_ARG, kw
+    for shard in ((-1, 10), (10, 5), (0, cfg.n_params + 1)):
+        with pytest.raises(zs.StageError) as ei:
+            zs.query(zs.make_config(cfg, shard=shard))
+        assert ei.value.code == zs.STAGE_ERR_ARG
+
+
+def test_activation_budget_is_enforced():
+    cfg = get_config("C4b")
+    zs.query(zs.make_config(cfg))                                     # 96e9 bytes: fits
+    with pytest.raises(zs.StageError) as ei:
+        zs.query(zs.make_config(cfg.with_(act_budget_bytes=10**9)))
+    assert ei.value.code == zs.STAGE_ERR_BUDGET
+    with pytest.raises(zs.StageError) as ei:                          # without recompute the 12-layer stage does not fit 40 GB
+        zs.query(zs.make_config(cfg.with_(recompute=0, act_budget_bytes=40 * 10**9)))
+    assert ei.value.code == zs.STAGE_ERR_BUDGET
+
+
+def test_init_rejects_bad_buffers_before_touching_the_device():
+    cfg = get_config("C1")
+    cc = zs.make_config(cfg)
+    L = zs.lib()
+    h = C.c_void_p()
+    fake = C.c_void_p(0x10000)          # never dereferenced: every check below fails first
+    _, mem, _ = zs.query(cc)
+    code = L.stage_init(C.byref(cc), None, None, None, fake, fake, fake, fake, mem["workspace"], C.byref(h))
+    assert code == zs.STAGE_ERR_ARG and not h.value
+    code = L.stage_init(C.byref(cc), None, fake, fake, fake, fake, fake, fake, mem["workspace"], C.byref(h))
+    assert code == zs.STAGE_ERR_ARG and b"master must be NULL" in L.stage_last_error(None)
+    code = L.stage_init(C.byref(cc), None, fake, None, fake, fake, fake, fake, mem["workspace"] - 1, C.byref(h))
+    assert code == zs.STAGE_ERR_WORKSPACE
+    code = L.stage_init(C.byref(cc), None, fake, None, fake, fake, fake, C.c_void_p(0x10010), mem["workspace"], C.byref(h))
+    assert code == zs.STAGE_ERR_WORKSPACE
+    code = L.stage_init(C.byref(cc), None, C.c_void_p(0x10004), None, fake, fake, fake, fake, mem["workspace"], C.byref(h))
+    assert code == zs.STAGE_ERR_ARG
+
+
+def test_ops_reject_bad_arguments_on_the_host():
+    L = zs.lib()
+    fake = C.c_void_p(0x10000)
+    assert L.stage_op_gemm(None, 5, 0, 0, 8, 8, 8, fake, 8, fake, 8, fake, 8, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0) == zs.STAGE_ERR_ARG
+    assert L.stage_op_gemm(None, 0, 0, 0, 8, 8, 8, None, 8, fake, 8, fake, 8, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0) == zs.STAGE_ERR_ARG
+    assert L.stage_op_gemm(None, 0, 0, 0, 8, 8, 8, fake, 8, fake, 8, fake, 8, 0, None, None, 0, 1, 0, 0, 0, 0, 3, 0, 0) == zs.STAGE_ERR_ARG
+    assert L.stage_op_adamw(None, 1, 8, 0, fake, None, fake, fake, fake, 1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 1.0) == zs.STAGE_ERR_ARG
+    assert L.stage_op_adamw(None, 0, 8, 0, fake, None, fake, fake, fake, 1e-4, 0.9, 0.999, 1e-8, 0.01, 0, 1.0) == zs.STAGE_ERR_ARG
+    assert L.stage_op_norm_fwd(None, 1, 1, 4, 12, fake, fake, None, 1e-5, fake, fake, None) == zs.STAGE_ERR_ARG
+    assert L.stage_op_attention_fwd(None, 1, 1, 16, 1, 12, fake, fake, fake, 12, fake, 12, fake, 0) == zs.STAGE_ERR_ARG
