@@ -1,11 +1,490 @@
-// bf16 MFMA flash attention (placeholder until the tiled kernel lands: reports "not supported").
+// Flash-style causal attention on the CDNA4 matrix cores, head dim 128, bf16 in, fp32 softmax.
+//
+// The S x S score matrix is never stored: K/V (forward, dQ) or Q/dO (dK/dV) tiles of 64 rows are
+// staged in LDS and every wavefront keeps its own 32 rows' operands and accumulators in
+// registers.  All products are computed TRANSPOSED (S^T = K Q^T, O^T = V^T P^T, ...): with
+// v_mfma_f32_32x32x16_bf16 a lane then owns one query (or key) column, so the softmax row
+// maximum and sum are reductions over the lane's own registers plus one exchange with lane^32,
+// and the fp32 accumulator registers of one product are, converted to bf16, already laid out
+// as the B operand of the next one.  The A operands that need the transposed tile (V^T, K^T,
+// dO^T, Q^T) are read with ds_read_b64_tr_b16, which hands a lane 4 values that are consecutive
+// along the tile's ROW index, so tiles sit in LDS exactly as they sit in memory.
+//
+// Backward is two kernels without atomics (fixed summation order): one owns 128 queries and
+// produces dQ, one owns 128 keys and produces dK and dV; both recompute P from the saved
+// log-sum-exp.  delta_i = dO_i . O_i comes from a small pre-pass.
 #include "kernels.h"
+
 namespace zs {
-bool attn_mfma_supported(DType, int, int) { return false; }
-hipError_t attn_fwd_mfma(hipStream_t, int, int, int, int, const void*, const void*, const void*, int64_t, void*, int64_t,
-                         float*) { return hipErrorNotSupported; }
-hipError_t attn_bwd_mfma(hipStream_t, int, int, int, int, const void*, const void*, const void*, int64_t, const void*,
-                         const void*, int64_t, const float*, float*, void*, void*, void*, int64_t) {
-  return hipErrorNotSupported;
+
+namespace {
+
+constexpr int D = 128;             // head dim
+constexpr int TR = 64;             // rows of a staged tile
+constexpr int LDT = D + 16;        // padded LDS row length in elements (288 bytes)
+constexpr int TILE = TR * LDT;     // elements of one staged tile
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+__device__ __forceinline__ bf16x8 zero8() {
+  bf16x8 z;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) z[i] = (bf16)0.f;
+  return z;
 }
+
+// A-operand fragment of a row-major LDS tile: lane (row = lane%32, g = lane/32) gets 8 consecutive columns.
+__device__ __forceinline__ bf16x8 lds_frag(const bf16* tile, int row0, int col0, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 31)) * LDT + col0 + 8 * (lane >> 5));
+}
+
+// A-operand fragment of the TRANSPOSE of a row-major LDS tile M[k][n]: lane (i = lane%32, g = lane/32)
+// gets M[k][n0+i] for the 8 contraction slots  k = k0 + 4g + {0,1,2,3, 8,9,10,11}.  This slot order is
+// the order in which a lane's accumulator registers 8s..8s+7 of a 32-row MFMA block hold rows, so the
+// matching B operand is just those registers.
+__device__ __forceinline__ bf16x8 lds_frag_tr(const bf16* tile, int k0, int n0, int lane) {
+  const int r = lane & 15, gi = lane >> 4;
+  const bf16* p = tile + (k0 + 4 * (gi >> 1) + (r >> 2)) * LDT + n0 + 16 * (gi & 1) + 4 * (r & 3);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * LDT));
+  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  u.s.a = lo;
+  u.s.b = hi;
+  return u.v;
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int s) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (bf16)a[8 * s + e];
+  return o;
+}
+
+// A 64 x 128 tile moves HBM -> registers (fetch, issued before the MFMAs of the current tile so the
+// latency hides behind them) -> LDS (put, after them).  Thread t carries 4 vectors of 16 bytes:
+// vector v = t + 256 i is row v/16, columns 8*(v%16)...  Rows >= nrows read as zero.
+struct TileRegs { bf16x8 v[4]; };
+__device__ __forceinline__ void fetch_tile(TileRegs& x, const bf16* __restrict__ src, int64_t ld, int row0, int nrows,
+                                           int tid) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = tid + 256 * i;
+    const int r = v >> 4, c = (v & 15) * 8;
+    x.v[i] = (row0 + r < nrows) ? *reinterpret_cast<const bf16x8*>(src + (int64_t)(row0 + r) * ld + c) : zero8();
+  }
+}
+__device__ __forceinline__ void put_tile(const TileRegs& x, bf16* tile, int tid) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int v = tid + 256 * i;
+    *reinterpret_cast<bf16x8*>(tile + (v >> 4) * LDT + (v & 15) * 8) = x.v[i];
+  }
+}
+
+// Row fragments kept in registers for a whole kernel: lane (row = row0 + lane%32, g) holds, for each of the
+// 8 contraction steps over d, 8 consecutive elements.  Rows >= nrows read as zero.
+__device__ __forceinline__ void load_row_frags(bf16x8 (&f)[8], const bf16* __restrict__ src, int64_t ld, int row0,
+                                               int nrows, int lane) {
+  const int row = row0 + (lane & 31);
+#pragma unroll
+  for (int s = 0; s < 8; ++s)
+    f[s] = row < nrows ? *reinterpret_cast<const bf16x8*>(src + (int64_t)row * ld + 16 * s + 8 * (lane >> 5)) : zero8();
+}
+
+// Row index (inside a 32-row MFMA block) held by accumulator register r of this lane.
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// ------------------------------------------------------------------------------------------ forward
+// grid (ceil(S/128), nh, mb); wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
+__global__ __launch_bounds__(256) void attn_fwd_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
+                                                       const bf16* __restrict__ v, int64_t ld, bf16* __restrict__ o,
+                                                       int64_t ldo, float* __restrict__ lse, float scale_log2) {
+  extern __shared__ __align__(16) char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);            // [2][K tile | V tile]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
+  const int64_t tok0 = (int64_t)b * S;
+  const bf16* qh = q + tok0 * ld + h * D;
+  const bf16* kh = k + tok0 * ld + h * D;
+  const bf16* vh = v + tok0 * ld + h * D;
+  const int q0 = qb * 128, wq0 = q0 + wave * 32;
+  const int my_q = wq0 + (lane & 31);
+
+  bf16x8 qf[8];
+  load_row_frags(qf, qh, ld, wq0, S, lane);
+  f32x16 oacc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const int last_q = min(q0 + 127, S - 1);
+  const int ntiles = last_q / TR + 1;
+  TileRegs kr, vr;
+  fetch_tile(kr, kh, ld, 0, S, tid);
+  fetch_tile(vr, vh, ld, 0, S, tid);
+  put_tile(kr, smem, tid);
+  put_tile(vr, smem + TILE, tid);
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const bf16* Kt = smem + (t & 1) * 2 * TILE;
+    const bf16* Vt = Kt + TILE;
+    if (t + 1 < ntiles) {
+      fetch_tile(kr, kh, ld, (t + 1) * TR, S, tid);
+      fetch_tile(vr, vh, ld, (t + 1) * TR, S, tid);
+    }
+    const int key0 = t * TR;
+    if (key0 <= wq0 + 31) {   // otherwise every key of the tile is in this wave's future
+      f32x16 sacc[2];
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[jb][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+          sacc[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Kt, jb * 32, 16 * s, lane), qf[s], sacc[jb], 0, 0, 0);
+      }
+      const bool diag = key0 + TR - 1 > wq0;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float s = sacc[jb][r] * scale_log2;
+          if (diag && key0 + jb * 32 + acc_row(r, lane) > my_q) s = -INFINITY;
+          sacc[jb][r] = s;
+          mx = fmaxf(mx, s);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(m, mx);            // finite: key 0 is visible to every query in the first tile
+      const float alpha = exp2f(m - mn);
+      float rs = 0.f;
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = exp2f(sacc[jb][r] - mn);
+          sacc[jb][r] = p;
+          rs += p;
+        }
+      rs += __shfl_xor(rs, 32, 64);
+      l = l * alpha + rs;
+      m = mn;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pf = pack8(sacc[jb], s2);
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(Vt, jb * 32 + 16 * s2, db * 32, lane), pf,
+                                                               oacc[db], 0, 0, 0);
+        }
+    }
+    if (t + 1 < ntiles) {   // the other buffer was last read before the barrier that ended the previous iteration
+      put_tile(kr, smem + ((t + 1) & 1) * 2 * TILE, tid);
+      put_tile(vr, smem + ((t + 1) & 1) * 2 * TILE + TILE, tid);
+    }
+    __syncthreads();
+  }
+  if (my_q < S) {
+    const float inv = 1.0f / l;
+    bf16* orow = o + (tok0 + my_q) * ldo + h * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16)(oacc[db][4 * c + e] * inv);
+        *reinterpret_cast<bf16x4*>(orow + db * 32 + 8 * c + 4 * (lane >> 5)) = w;
+      }
+    if (lane < 32) lse[((int64_t)b * nh + h) * S + my_q] = (m + log2f(l)) * LN2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ delta
+__global__ __launch_bounds__(256) void attn_delta_mfma_kernel(int S, const bf16* __restrict__ o,
+                                                              const bf16* __restrict__ dout, int64_t ldo,
+                                                              float* __restrict__ delta) {
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + w;
+  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
+  if (i >= S) return;
+  const int64_t off = ((int64_t)b * S + i) * ldo + h * D + lane * 2;
+  const bf16x2 a = *reinterpret_cast<const bf16x2*>(o + off);
+  const bf16x2 c = *reinterpret_cast<const bf16x2*>(dout + off);
+  float s = (float)a[0] * (float)c[0] + (float)a[1] * (float)c[1];
+  s = wave_sum(s);
+  if (lane == 0) delta[((int64_t)b * nh + h) * S + i] = s;
+}
+
+// ------------------------------------------------------------------------------------------ dQ
+// grid (ceil(S/128), nh, mb); wave w owns queries q0+32w..; loops over K/V tiles up to the diagonal.
+// dQ^T[d][q] += K^T[d][key] dS^T[key][q],  dS^T = P^T o (dP^T - delta_q),  dP^T = V dO^T.
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
+                                                          const bf16* __restrict__ v, int64_t ld,
+                                                          const bf16* __restrict__ dout, int64_t ldo,
+                                                          const float* __restrict__ lse, const float* __restrict__ delta,
+                                                          bf16* __restrict__ dq, int64_t ldd, float scale) {
+  extern __shared__ __align__(16) char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
+  const int64_t tok0 = (int64_t)b * S;
+  const bf16* qh = q + tok0 * ld + h * D;
+  const bf16* kh = k + tok0 * ld + h * D;
+  const bf16* vh = v + tok0 * ld + h * D;
+  const bf16* doh = dout + tok0 * ldo + h * D;
+  const int q0 = qb * 128, wq0 = q0 + wave * 32;
+  const int my_q = wq0 + (lane & 31);
+  const float scale_log2 = scale * LOG2E;
+
+  bf16x8 qf[8], dof[8];
+  load_row_frags(qf, qh, ld, wq0, S, lane);
+  load_row_frags(dof, doh, ldo, wq0, S, lane);
+  const int64_t stat = ((int64_t)b * nh + h) * S + min(my_q, S - 1);
+  const float lse2 = lse[stat] * LOG2E;
+  const float dlt = delta[stat];
+  f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  const int last_q = min(q0 + 127, S - 1);
+  const int ntiles = last_q / TR + 1;
+  TileRegs kr, vr;
+  fetch_tile(kr, kh, ld, 0, S, tid);
+  fetch_tile(vr, vh, ld, 0, S, tid);
+  put_tile(kr, smem, tid);
+  put_tile(vr, smem + TILE, tid);
+  __syncthreads();
+  for (int t = 0; t < ntiles; ++t) {
+    const bf16* Kt = smem + (t & 1) * 2 * TILE;
+    const bf16* Vt = Kt + TILE;
+    if (t + 1 < ntiles) {
+      fetch_tile(kr, kh, ld, (t + 1) * TR, S, tid);
+      fetch_tile(vr, vh, ld, (t + 1) * TR, S, tid);
+    }
+    const int key0 = t * TR;
+    if (key0 <= wq0 + 31) {
+      const bool diag = key0 + TR - 1 > wq0;
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb) {
+        f32x16 sacc, pacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Kt, jb * 32, 16 * s, lane), qf[s], sacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Vt, jb * 32, 16 * s, lane), dof[s], pacc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = exp2f(sacc[r] * scale_log2 - lse2);
+          if (diag && key0 + jb * 32 + acc_row(r, lane) > my_q) p = 0.f;
+          sacc[r] = p * (pacc[r] - dlt);
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 dsf = pack8(sacc, s2);
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(Kt, jb * 32 + 16 * s2, db * 32, lane), dsf,
+                                                              acc[db], 0, 0, 0);
+        }
+      }
+    }
+    if (t + 1 < ntiles) {   // the other buffer was last read before the barrier that ended the previous iteration
+      put_tile(kr, smem + ((t + 1) & 1) * 2 * TILE, tid);
+      put_tile(vr, smem + ((t + 1) & 1) * 2 * TILE + TILE, tid);
+    }
+    __syncthreads();
+  }
+  if (my_q < S) {
+    bf16* row = dq + (tok0 + my_q) * ldd + h * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (bf16)(acc[db][4 * c + e] * scale);
+        *reinterpret_cast<bf16x4*>(row + db * 32 + 8 * c + 4 * (lane >> 5)) = w;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ dK, dV
+// grid (ceil(S/128), nh, mb); wave w owns keys k0+32w..; loops over Q/dO tiles from the diagonal to the end.
+// S[q][key] = Q K^T (lane = key, registers = queries), P = exp2(S c - lse_q), dP = dO V^T,
+// dV^T[d][key] += dO^T[d][q] P[q][key],  dK^T[d][key] += Q^T[d][q] dS[q][key].
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
+                                                           const bf16* __restrict__ v, int64_t ld,
+                                                           const bf16* __restrict__ dout, int64_t ldo,
+                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+                                                           bf16* __restrict__ dk, bf16* __restrict__ dv, int64_t ldd,
+                                                           float scale) {
+  extern __shared__ __align__(16) char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);                 // [2][Q tile | dO tile]
+  float* stats = reinterpret_cast<float*>(smem + 4 * TILE);       // [2][lse2[64] | delta[64]]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kb = blockIdx.x;                                      // early key blocks (most work) first
+  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
+  const int64_t tok0 = (int64_t)b * S;
+  const bf16* qh = q + tok0 * ld + h * D;
+  const bf16* kh = k + tok0 * ld + h * D;
+  const bf16* vh = v + tok0 * ld + h * D;
+  const bf16* doh = dout + tok0 * ldo + h * D;
+  const float* lse_h = lse + ((int64_t)b * nh + h) * S;
+  const float* dlt_h = delta + ((int64_t)b * nh + h) * S;
+  const int k0 = kb * 128, wk0 = k0 + wave * 32;
+  const int my_k = wk0 + (lane & 31);
+  const float scale_log2 = scale * LOG2E;
+
+  bf16x8 kf[8], vf[8];
+  load_row_frags(kf, kh, ld, wk0, S, lane);
+  load_row_frags(vf, vh, ld, wk0, S, lane);
+  f32x16 dkacc[4], dvacc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dkacc[i][r] = dvacc[i][r] = 0.f;
+
+  TileRegs qr, dor;
+  float statr = 0.f;
+  auto fetch = [&](int t) {
+    fetch_tile(qr, qh, ld, t * TR, S, tid);
+    fetch_tile(dor, doh, ldo, t * TR, S, tid);
+    if (tid < 128) {
+      const int r = t * TR + (tid & 63);
+      statr = 0.f;
+      if (r < S) statr = tid < 64 ? lse_h[r] * LOG2E : dlt_h[r];
+    }
+  };
+  auto put = [&](int buf) {
+    put_tile(qr, smem + buf * 2 * TILE, tid);
+    put_tile(dor, smem + buf * 2 * TILE + TILE, tid);
+    if (tid < 128) stats[buf * 128 + tid] = statr;
+  };
+  const int t_begin = k0 / TR, t_end = (S - 1) / TR + 1;
+  fetch(t_begin);
+  put(0);
+  __syncthreads();
+  for (int t = t_begin; t < t_end; ++t) {
+    const int buf = (t - t_begin) & 1;
+    const bf16* Qt = smem + buf * 2 * TILE;
+    const bf16* dOt = Qt + TILE;
+    const float* st = stats + buf * 128;
+    if (t + 1 < t_end) fetch(t + 1);
+    const int qrow0 = t * TR;
+    if (qrow0 + TR - 1 >= wk0) {   // otherwise every query of the tile precedes this wave's keys
+      const bool diag = qrow0 < wk0 + 31;
+#pragma unroll
+      for (int ib = 0; ib < 2; ++ib) {
+        f32x16 sacc, pacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Qt, ib * 32, 16 * s, lane), kf[s], sacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(dOt, ib * 32, 16 * s, lane), vf[s], pacc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qi = ib * 32 + acc_row(r, lane);
+          float p = exp2f(sacc[r] * scale_log2 - st[qi]);
+          if ((diag && qrow0 + qi < my_k) || qrow0 + qi >= S) p = 0.f;
+          sacc[r] = p;
+          pacc[r] = p * (pacc[r] - st[64 + qi]);
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pf = pack8(sacc, s2), dsf = pack8(pacc, s2);
+#pragma unroll
+          for (int db = 0; db < 4; ++db) {
+            dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(dOt, ib * 32 + 16 * s2, db * 32, lane), pf,
+                                                                dvacc[db], 0, 0, 0);
+            dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(Qt, ib * 32 + 16 * s2, db * 32, lane), dsf,
+                                                                dkacc[db], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (t + 1 < t_end) put(buf ^ 1);
+    __syncthreads();
+  }
+  if (my_k < S) {
+    bf16* krow = dk + (tok0 + my_k) * ldd + h * D;
+    bf16* vrow = dv + (tok0 + my_k) * ldd + h * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        bf16x4 wk, wv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          wk[e] = (bf16)(dkacc[db][4 * c + e] * scale);
+          wv[e] = (bf16)dvacc[db][4 * c + e];
+        }
+        *reinterpret_cast<bf16x4*>(krow + db * 32 + 8 * c + 4 * (lane >> 5)) = wk;
+        *reinterpret_cast<bf16x4*>(vrow + db * 32 + 8 * c + 4 * (lane >> 5)) = wv;
+      }
+  }
+}
+
+constexpr size_t SMEM_FWD = 4 * TILE * sizeof(bf16);                    // 73728
+constexpr size_t SMEM_DKV = 4 * TILE * sizeof(bf16) + 256 * sizeof(float);
+
+template <typename K> hipError_t set_smem(K kern, size_t bytes, bool& done) {
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+}  // namespace
+
+bool attn_mfma_supported(DType dt, int S, int d) { return dt == BF16 && d == D && S >= 1; }
+
+hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
+                         int64_t ld, void* o, int64_t ldo, float* lse) {
+  static bool cfg = false;
+  hipError_t e = set_smem(attn_fwd_kernel, SMEM_FWD, cfg);
+  if (e != hipSuccess) return e;
+  dim3 grid((unsigned)cdiv(S, 128), (unsigned)nh, (unsigned)mb), blk(256);
+  hipLaunchKernelGGL(attn_fwd_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
+                     (bf16*)o, ldo, lse, LOG2E / sqrtf((float)d));
+  return hipGetLastError();
+}
+
+hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
+                         int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
+                         void* dq, void* dk, void* dv, int64_t ldd) {
+  static bool cfg1 = false, cfg2 = false;
+  hipError_t e = set_smem(attn_bwd_dq_kernel, SMEM_FWD, cfg1);
+  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel, SMEM_DKV, cfg2);
+  if (e != hipSuccess) return e;
+  const float scale = 1.0f / sqrtf((float)d);
+  dim3 grid((unsigned)cdiv(S, 128), (unsigned)nh, (unsigned)mb), blk(256);
+  hipLaunchKernelGGL(attn_delta_mfma_kernel, dim3((unsigned)cdiv(S, 4), (unsigned)nh, (unsigned)mb), blk, 0, st, S,
+                     (const bf16*)o, (const bf16*)dout, ldo, delta);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
+                     (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale);
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, blk, SMEM_DKV, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
+                     (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale);
+  return hipGetLastError();
+}
+
 }  // namespace zs

@@ -118,7 +118,9 @@ int stage_op_cross_entropy(void* stream, int32_t dtype, int32_t T, int32_t V, vo
 int stage_op_adamw(void* stream, int32_t dtype, int64_t n, int64_t begin, void* params, float* master, float* grad,
                    float* m, float* v, float lr, float beta1, float beta2, float eps, float wd, int64_t t,
                    float grad_scale) {
-  if (!dt_ok(dtype) || n < 0 || begin < 0 || t < 1 || !params || !grad || !m || !v) return STAGE_ERR_ARG;
+  if (!dt_ok(dtype) || n < 0 || begin < 0 || t < 1) return STAGE_ERR_ARG;
+  if (n == 0) return STAGE_OK;
+  if (!params || !grad || !m || !v) return STAGE_ERR_ARG;
   if ((dtype == 1) != (master != nullptr)) return STAGE_ERR_ARG;
   AdamW h;
   h.lr = lr; h.beta1 = beta1; h.beta2 = beta2; h.eps = eps; h.wd = wd;

@@ -26,14 +26,15 @@ def rel_err(a, o):
     return float(np.abs(a - o).max() / den)
 
 
-def update_err(a, o, p_new):
+def update_err(a, o, p_new, nsteps=1):
     """Max-norm relative error of a parameter update read back from fp32 storage.
 
     The update is recovered as p_new - p_old from values stored in fp32, so each element carries up
     to half an fp32 ulp of p_new that no arithmetic can avoid (for a gain of 1.0 that is 6e-8 against
-    an update of 1e-4).  That floor is subtracted before the relative error is formed.
+    an update of 1e-4), once per optimizer step taken.  That floor is subtracted before the relative
+    error is formed.
     """
-    floor = 0.5 * np.spacing(np.abs(p_new).astype(np.float32)).astype(np.float64) * 1.01
+    floor = nsteps * 0.5 * np.spacing(np.abs(p_new).astype(np.float32)).astype(np.float64) * 1.01
     d = np.maximum(np.abs(a - o) - floor, 0.0)
     return float(d.max() / np.abs(o).max())
 
@@ -126,6 +127,17 @@ def oracle_step(cfg, inp, M=None, loss_scale=None):
         ls = (1.0 / M) if loss_scale is None else loss_scale
         return so.stage_step(cfg, inp.params, inp.ids[:M], None, inp.targets[:M], ls)
     return so.stage_step(cfg, inp.params, inp.x[:M], inp.dy[:M])
+
+
+def log_report(title, rows):
+    """Appends error figures to gpurun_out/parity_report.txt when that folder exists (GPU machine runs)."""
+    import os
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "parity_report.txt"), "a") as f:
+            f.write(title + "\n")
+            for name, e in rows:
+                f.write(f"    {name:28s} {e:.3e}\n")
 
 
 def compare_step(cfg, gpu, ora, tol, report=None):

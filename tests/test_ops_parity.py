@@ -1,0 +1,352 @@
+"""GPU parity of single kernels (stage_op_* entry points) against the oracle's functions."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_10392_amd as zs
+from harness import dev, log_report, rel_err
+from oracle import stage_oracle as so
+from workloads import round_bf16
+
+pytestmark = pytest.mark.gpu
+
+TD = {0: torch.float32, 1: torch.bfloat16}
+TOL = {0: 2e-5, 1: 1e-2}        # single kernels: one rounding step, so tighter than the whole-step bar
+
+
+def draw(rng, shape, dtype, scale=1.0):
+    a = (rng.standard_normal(shape) * scale).astype(np.float32)
+    return round_bf16(a) if dtype == 1 else a
+
+
+def st():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def back(t):
+    torch.cuda.synchronize()
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+# ----------------------------------------------------------------------------- GEMM
+
+GEMM_CASES = [
+    # (M, N, K, transA, transB, batch, kseg, bias, resid, accum)
+    (256, 256, 64, 0, 1, 1, 0, False, False, False),
+    (256, 256, 128, 0, 0, 1, 0, False, False, False),
+    (256, 256, 128, 1, 0, 1, 0, False, False, True),
+    (256, 256, 128, 1, 1, 1, 0, False, False, False),
+    (512, 768, 320, 0, 0, 1, 0, True, True, False),
+    (300, 264, 200, 0, 1, 1, 0, True, False, False),      # ragged in every dimension
+    (304, 264, 200, 1, 0, 2, 0, False, False, True),
+    (72, 1376, 40, 0, 0, 3, 0, False, True, False),
+    (130, 520, 3 * 136, 0, 1, 1, 136, False, False, False),   # segmented K, segment not a multiple of 64
+    (257, 512, 1024, 0, 1, 1, 512, False, False, False),
+    (8, 8, 8, 0, 0, 1, 0, False, False, False),
+    (1000, 40, 2048, 1, 0, 1, 0, False, False, True),
+]
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("case", GEMM_CASES, ids=lambda c: "x".join(str(int(v)) for v in c))
+def test_gemm_matches_float64_matmul(gpu_device, case, dtype, impl):
+    M, N, K, ta, tb, batch, kseg, use_bias, use_res, accum = case
+    if impl == 2 and dtype == 0:
+        pytest.skip("the MFMA kernel is bf16 only")
+    print(f"[case] gemm {case} dtype={dtype} impl={impl}", flush=True)
+    rng = np.random.default_rng(hash(case) % 2**32)
+    A = draw(rng, (batch, K, M) if ta else (batch, M, K), dtype)
+    nseg = K // kseg if kseg else 1
+    if kseg:
+        B = draw(rng, (nseg, N, kseg), dtype, 0.05)             # transB=1 segments stored one after another
+    else:
+        B = draw(rng, (batch, N, K) if tb else (batch, K, N), dtype, 0.05)
+    bias = draw(rng, (batch, N), dtype) if use_bias else None
+    R = draw(rng, (batch, M, N), dtype) if use_res else None
+    C0 = rng.standard_normal((batch, M, N)).astype(np.float32) if accum else None
+    # oracle: plain float64 products
+    want = np.empty((batch, M, N))
+    for z in range(batch):
+        a = A[z].astype(np.float64).T if ta else A[z].astype(np.float64)
+        if kseg:
+            b = np.concatenate([B[s].astype(np.float64).T for s in range(nseg)], axis=0)
+        else:
+            b = B[z].astype(np.float64).T if tb else B[z].astype(np.float64)
+        want[z] = a @ b
+        if use_bias:
+            want[z] += bias[z][None, :]
+        if use_res:
+            want[z] += R[z]
+        if accum:
+            want[z] += C0[z]
+    td = TD[dtype]
+    dA, dB = dev(A, td), dev(B, td)
+    dbias = dev(bias, td) if use_bias else None
+    dR = dev(R, td) if use_res else None
+    dC = dev(C0) if accum else torch.full((batch, M, N), float("nan"), dtype=td, device="cuda")
+    lda = M if ta else K
+    ldb = (kseg if kseg else K) if tb else N
+    sB = 0 if kseg else (N * K)
+    zs.ops.gemm(st(), dtype, ta, tb, M, N, K, dA, lda, dB, ldb, dC, N, int(accum), dbias, dR, N, batch,
+                M * K, sB, M * N, N, kseg, N * kseg if kseg else 0, impl)
+    got = back(dC)
+    err = rel_err(got, want)
+    tol = 2e-5 if (dtype == 0 or accum) else 1e-2
+    log_report(f"gemm {case} dtype={dtype} impl={impl}", [("C", err)])
+    assert err <= tol
+
+
+def test_gemm_full_shape_sampled_outputs(gpu_device):
+    """The three products of the 7B-class FFN down projection at full size (T=4096, H=4096, F=11008),
+    checked on 256 sampled outputs each, every one recomputed as a float64 dot product."""
+    rng = np.random.default_rng(11)
+    T, H, F = 4096, 4096, 11008
+    g = torch.Generator(device="cuda").manual_seed(5)
+    a = torch.randn(T, F, device="cuda", generator=g).to(torch.bfloat16)
+    W = (torch.randn(F, H, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    dy = (torch.randn(T, H, device="cuda", generator=g) * 0.01).to(torch.bfloat16)
+    y = torch.empty(T, H, dtype=torch.bfloat16, device="cuda")
+    da = torch.empty(T, F, dtype=torch.bfloat16, device="cuda")
+    dW = torch.zeros(F, H, dtype=torch.float32, device="cuda")
+    print("[case] gemm full shape NN", flush=True)
+    zs.ops.gemm(st(), 1, 0, 0, T, H, F, a, F, W, H, y, H, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
+    print("[case] gemm full shape NT", flush=True)
+    zs.ops.gemm(st(), 1, 0, 1, T, F, H, dy, H, W, H, da, F, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
+    print("[case] gemm full shape TN", flush=True)
+    zs.ops.gemm(st(), 1, 1, 0, F, H, T, a, F, dy, H, dW, H, 1, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
+    torch.cuda.synchronize()
+    a64, W64, dy64 = (t.float().cpu().numpy().astype(np.float64) for t in (a, W, dy))
+    yh, dah, dWh = y.float().cpu().numpy(), da.float().cpu().numpy(), dW.cpu().numpy()
+    ii = rng.integers(0, T, 256)
+    jh, jf = rng.integers(0, H, 256), rng.integers(0, F, 256)
+    want_y = np.einsum("sk,ks->s", a64[ii, :], W64[:, jh])
+    want_da = np.einsum("sk,sk->s", dy64[ii, :], W64[jf, :])
+    want_dW = np.einsum("ks,ks->s", a64[:, jf], dy64[:, jh])
+    ey = np.abs(yh[ii, jh] - want_y).max() / np.abs(want_y).max()
+    eda = np.abs(dah[ii, jf] - want_da).max() / np.abs(want_da).max()
+    edw = np.abs(dWh[jf, jh] - want_dW).max() / np.abs(want_dW).max()
+    log_report("gemm full shape sampled", [("y", ey), ("da", eda), ("dW", edw)])
+    assert ey <= 1e-2 and eda <= 1e-2 and edw <= 1e-4
+
+
+# ----------------------------------------------------------------------------- norms
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("kind", [0, 1])
+@pytest.mark.parametrize("T,H", [(37, 256), (130, 640), (5, 8)])
+def test_norm_fwd_bwd(gpu_device, dtype, kind, T, H):
+    print(f"[case] norm kind={kind} dtype={dtype} T={T} H={H}", flush=True)
+    rng = np.random.default_rng(3)
+    x = draw(rng, (T, H), dtype, 2.0)
+    g = draw(rng, (H,), dtype) + 1
+    g = round_bf16(g) if dtype else g
+    b = draw(rng, (H,), dtype)
+    dn = draw(rng, (T, H), dtype)
+    dres = draw(rng, (T, H), dtype)
+    eps = float(np.float32(1e-5))
+    if kind == 0:
+        n_o, cache = so.layernorm_fwd(x.astype(np.float64), g, b, eps)
+        dx_o, dg_o, db_o = so.layernorm_bwd(dn.astype(np.float64), g.astype(np.float64), cache)
+    else:
+        n_o, cache = so.rmsnorm_fwd(x.astype(np.float64), g, eps)
+        dx_o, dg_o = so.rmsnorm_bwd(dn.astype(np.float64), g.astype(np.float64), cache)
+    td = TD[dtype]
+    dxd, dg_, db_, dnd, dresd = dev(x, td), dev(g, td), dev(b, td), dev(dn, td), dev(dres, td)
+    n = torch.empty(T, H, dtype=td, device="cuda")
+    rstd = torch.empty(T, device="cuda")
+    mean = torch.empty(T, device="cuda")
+    zs.ops.norm_fwd(st(), dtype, kind, T, H, dxd, dg_, db_ if kind == 0 else None, eps, n, rstd, mean if kind == 0 else None)
+    assert rel_err(back(n), n_o) <= TOL[dtype]
+    assert rel_err(back(rstd), cache[1][:, 0]) <= 2e-6
+    nblk = min(T, 7)
+    dx = torch.empty(T, H, dtype=td, device="cuda")
+    pg = torch.empty(nblk, H, device="cuda")
+    pb = torch.empty(nblk, H, device="cuda")
+    zs.ops.norm_bwd(st(), dtype, kind, T, H, dnd, dxd, dg_, rstd, mean if kind == 0 else None, dresd, dx, pg,
+                    pb if kind == 0 else None, nblk)
+    assert rel_err(back(dx), dx_o + dres) <= TOL[dtype]
+    assert rel_err(back(pg).sum(axis=0), dg_o) <= 2e-5
+    if kind == 0:
+        assert rel_err(back(pb).sum(axis=0), db_o) <= 2e-5
+
+
+# ----------------------------------------------------------------------------- RoPE, activations
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_rope_and_inverse(gpu_device, dtype):
+    print(f"[case] rope dtype={dtype}", flush=True)
+    rng = np.random.default_rng(4)
+    mb, S, nh, d = 2, 300, 3, 128
+    u = draw(rng, (mb * S, 3 * nh * d), dtype)
+    want = u.astype(np.float64).copy()
+    qk = so.rope(want[:, :2 * nh * d].reshape(mb, S, 2 * nh, d), 10000.0)
+    want[:, :2 * nh * d] = qk.reshape(mb * S, -1)
+    a = dev(u, TD[dtype])
+    table = torch.empty(S * d, device="cuda")
+    zs.ops.rope(st(), dtype, mb * S, S, 2 * nh * d, d, a, 3 * nh * d, 10000.0, 1.0, table)
+    assert rel_err(back(a), want) <= (4e-3 if dtype else 2e-6)
+    assert np.array_equal(back(a)[:, 2 * nh * d:], u[:, 2 * nh * d:].astype(np.float64))       # V untouched
+    if dtype == 0:
+        zs.ops.rope(st(), dtype, mb * S, S, 2 * nh * d, d, a, 3 * nh * d, 10000.0, -1.0, table)
+        assert rel_err(back(a), u) <= 2e-6
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_gelu_and_swiglu(gpu_device, dtype):
+    print(f"[case] activations dtype={dtype}", flush=True)
+    rng = np.random.default_rng(5)
+    T, F = 33, 1376
+    td = TD[dtype]
+    z = draw(rng, (T, F), dtype, 2.0)
+    da = draw(rng, (T, F), dtype)
+    out = torch.empty(T, F, dtype=td, device="cuda")
+    zs.ops.gelu(st(), dtype, T * F, dev(z, td), None, out, 0)
+    assert rel_err(back(out), so.gelu(z.astype(np.float64))) <= TOL[dtype]
+    zs.ops.gelu(st(), dtype, T * F, dev(z, td), dev(da, td), out, 1)
+    assert rel_err(back(out), da * so.gelu_grad(z.astype(np.float64))) <= TOL[dtype]
+    gu = draw(rng, (T, 2 * F), dtype, 2.0)
+    g64, u64 = gu[:, :F].astype(np.float64), gu[:, F:].astype(np.float64)
+    zs.ops.swiglu(st(), dtype, T, F, dev(gu, td), None, out, 0)
+    assert rel_err(back(out), g64 * so.sigmoid(g64) * u64) <= TOL[dtype]
+    dgu = torch.empty(T, 2 * F, dtype=td, device="cuda")
+    zs.ops.swiglu(st(), dtype, T, F, dev(gu, td), dev(da, td), dgu, 1)
+    sg = so.sigmoid(g64)
+    want = np.concatenate([da * u64 * sg * (1 + g64 * (1 - sg)), da * g64 * sg], axis=1)
+    assert rel_err(back(dgu), want) <= TOL[dtype]
+
+
+# ----------------------------------------------------------------------------- attention
+
+ATTN_CASES = [(2, 128, 4, 64), (1, 256, 4, 128), (2, 200, 3, 128), (1, 1, 2, 128), (1, 65, 1, 128), (1, 576, 2, 128)]
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("mb,S,nh,d", ATTN_CASES)
+def test_attention_fwd_bwd(gpu_device, mb, S, nh, d, dtype, impl):
+    if impl == 2 and (dtype == 0 or d != 128):
+        pytest.skip("the MFMA attention kernel is bf16, head dim 128")
+    print(f"[case] attention mb={mb} S={S} nh={nh} d={d} dtype={dtype} impl={impl}", flush=True)
+    rng = np.random.default_rng(6)
+    H = nh * d
+    qkv = draw(rng, (mb * S, 3 * H), dtype)
+    do = draw(rng, (mb * S, H), dtype)
+    q, k, v = (qkv[:, i * H:(i + 1) * H].astype(np.float64).reshape(mb, S, nh, d) for i in range(3))
+    o_o = so.attention_fwd(q, k, v)
+    td = TD[dtype]
+    dqkv_in = dev(qkv, td)
+    o = torch.empty(mb * S, H, dtype=td, device="cuda")
+    lse = torch.empty(mb * nh * S, device="cuda")
+    E = dqkv_in.element_size()
+    qp, kp, vp = (torch.as_strided(dqkv_in, (mb * S, H), (3 * H, 1), i * H) for i in range(3))
+    zs.ops.attention_fwd(st(), dtype, mb, S, nh, d, qp, kp, vp, 3 * H, o, H, lse, impl)
+    tol = 1e-2 if dtype else 2e-5
+    assert rel_err(back(o), o_o.reshape(mb * S, H)) <= tol
+    # lse against the definition
+    b, h = mb - 1, nh - 1
+    s = (q[b, :, h] @ k[b, :, h].T) / np.sqrt(d)
+    s = np.where(np.tril(np.ones((S, S), bool)), s, -np.inf)
+    mx = s.max(axis=1)
+    lse_o = mx + np.log(np.exp(s - mx[:, None]).sum(axis=1))
+    assert np.abs(back(lse).reshape(mb, nh, S)[b, h] - lse_o).max() <= (2e-2 if dtype else 1e-5)
+    # backward, fed with the oracle's o rounded like the forward output would be
+    dq_o, dk_o, dv_o = so.attention_bwd(do.astype(np.float64).reshape(mb, S, nh, d), q, k, v)
+    delta = torch.empty(mb * nh * S, device="cuda")
+    dqkv = torch.full((mb * S, 3 * H), float("nan"), dtype=td, device="cuda")
+    dq_, dk_, dv_ = (torch.as_strided(dqkv, (mb * S, H), (3 * H, 1), i * H) for i in range(3))
+    zs.ops.attention_bwd(st(), dtype, mb, S, nh, d, qp, kp, vp, 3 * H, o, dev(do, td), H, lse, delta, dq_, dk_, dv_,
+                         3 * H, impl)
+    got = back(dqkv)
+    errs = [("dq", rel_err(got[:, :H], dq_o.reshape(mb * S, H))), ("dk", rel_err(got[:, H:2 * H], dk_o.reshape(mb * S, H))),
+            ("dv", rel_err(got[:, 2 * H:], dv_o.reshape(mb * S, H)))]
+    log_report(f"attention mb={mb} S={S} nh={nh} d={d} dtype={dtype} impl={impl}", errs)
+    for n, e in errs:
+        assert e <= (2e-2 if dtype else 5e-5), n
+
+
+# ----------------------------------------------------------------------------- embedding, cross entropy, AdamW
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_embedding_is_bit_exact_and_scatter_matches(gpu_device, dtype):
+    print(f"[case] embedding dtype={dtype}", flush=True)
+    rng = np.random.default_rng(7)
+    T, H, V = 700, 64, 50                       # many repeated ids
+    td = TD[dtype]
+    E = draw(rng, (V, H), dtype)
+    ids = rng.integers(0, V, T).astype(np.int32)
+    dx = draw(rng, (T, H), dtype)
+    x = torch.empty(T, H, dtype=td, device="cuda")
+    dE = dev(rng.standard_normal((V, H)).astype(np.float32))
+    dE0 = back(dE).copy()
+    zs.ops.embed(st(), dtype, T, H, V, dev(ids), dev(E, td), x, None, None, 0)
+    assert np.array_equal(back(x), E[ids].astype(np.float64))           # integer indexing: bit exact
+    zs.ops.embed(st(), dtype, T, H, V, dev(ids), None, None, dev(dx, td), dE, 1)
+    want = dE0.copy()
+    np.add.at(want, ids, dx.astype(np.float64))
+    assert rel_err(back(dE), want) <= 2e-6
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_cross_entropy(gpu_device, dtype):
+    print(f"[case] cross entropy dtype={dtype}", flush=True)
+    rng = np.random.default_rng(8)
+    T, V = 97, 2000
+    td = TD[dtype]
+    z = draw(rng, (T, V), dtype, 3.0)
+    tg = rng.integers(0, V, T).astype(np.int32)
+    z64 = z.astype(np.float64)
+    mx = z64.max(axis=1, keepdims=True)
+    lse_o = (mx + np.log(np.exp(z64 - mx).sum(axis=1, keepdims=True)))[:, 0]
+    loss_o = (lse_o - z64[np.arange(T), tg]).mean()
+    zd = dev(z, td)
+    lse, rowloss, loss = torch.empty(T, device="cuda"), torch.empty(T, device="cuda"), torch.empty(1, device="cuda")
+    zs.ops.cross_entropy(st(), dtype, T, V, zd, V, dev(tg), lse, rowloss, loss, 0.0, 0)
+    assert np.abs(back(lse) - lse_o).max() <= 1e-5 * np.abs(lse_o).max()
+    assert abs(back(loss)[0] - loss_o) <= 1e-5 * abs(loss_o)
+    scale = 0.25 / T
+    zs.ops.cross_entropy(st(), dtype, T, V, zd, V, dev(tg), lse, None, None, scale, 1)
+    want = np.exp(z64 - lse_o[:, None])
+    want[np.arange(T), tg] -= 1
+    assert rel_err(back(zd), want * scale) <= (4e-3 if dtype else 1e-5)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("n,begin", [(1 << 16, 0), (100003, 8), (1001, 5), (3, 0), (0, 0)])
+def test_adamw_kernel_matches_oracle_for_t_1_2_10(gpu_device, dtype, n, begin):
+    print(f"[case] adamw dtype={dtype} n={n} begin={begin}", flush=True)
+    rng = np.random.default_rng(9)
+    f32 = lambda x: float(np.float32(x))
+    lr, b1, b2, eps, wd, gs = f32(1e-4), f32(0.9), f32(0.999), f32(1e-8), f32(0.01), f32(0.5)
+    P = begin + n + 13
+    p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
+    master = dev(p0[begin:begin + n]) if dtype else None
+    params = dev(round_bf16(p0), torch.bfloat16) if dtype else dev(p0)
+    m = torch.zeros(max(n, 1), device="cuda")
+    v = torch.zeros(max(n, 1), device="cuda")
+    po, mo, vo = p0[begin:begin + n].astype(np.float64), np.zeros(n), np.zeros(n)
+    for t in (1, 2, 10):
+        g = (rng.standard_normal(P) * 10.0 ** rng.integers(-6, 0, P)).astype(np.float32)
+        grad = dev(g)
+        zs.ops.adamw(st(), dtype, n, begin, params, master, grad, m, v, lr, b1, b2, eps, wd, t, gs)
+        prev = po
+        po, mo, vo = so.adamw(po, g[begin:begin + n].astype(np.float64), mo, vo, t, lr, b1, b2, eps, wd, gs)
+        if n == 0:
+            continue
+        got_p = back(master) if dtype else back(params)[begin:begin + n]
+        assert rel_err(back(m)[:n], mo) <= 1e-6 and rel_err(back(v)[:n], vo) <= 1e-6
+        floor = 0.5 * np.spacing(np.abs(po).astype(np.float32)).astype(np.float64) * 1.01
+        d = np.maximum(np.abs((got_p - prev) - (po - prev)) - floor, 0)
+        assert d.max() <= 2e-6 * np.abs(po - prev).max()
+        gz = back(grad)
+        assert not gz[begin:begin + n].any() and np.array_equal(gz[:begin], g[:begin].astype(np.float64))
+        assert np.array_equal(gz[begin + n:], g[begin + n:].astype(np.float64))
+        if dtype:
+            want = master.to(torch.bfloat16).cpu()
+            assert torch.equal(want.view(torch.int16), params[begin:begin + n].cpu().view(torch.int16))
+            assert np.array_equal(back(params)[:begin], round_bf16(p0)[:begin].astype(np.float64))
+        po = got_p.copy()      # continue from the GPU's fp32 state so that only one step's rounding is compared
+        mo, vo = back(m)[:n].copy(), back(v)[:n].copy()

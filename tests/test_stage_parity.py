@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from harness import TOL, GpuStage, compare_optimizer, compare_step, oracle_step
+from harness import TOL, GpuStage, compare_optimizer, compare_step, log_report, oracle_step
 from workloads import get_config, make_inputs
 
 pytestmark = pytest.mark.gpu
@@ -24,6 +24,7 @@ def test_stage_step_matches_oracle(gpu_device, name, perturbed):
     rep = []
     compare_step(cfg, gpu, ora, tol, rep)
     worst = max(rep, key=lambda r: r[1])
+    log_report(f"stage step {name} perturbed={perturbed} tol={tol:g}", sorted(rep, key=lambda r: -r[1])[:6])
     print(f"[parity] {name}: worst {worst[0]} = {worst[1]:.3e} (tol {tol:g})", flush=True)
     res = g.step(1)
     masked = compare_optimizer(cfg, inp, g.shard, gpu["grad"], res, ora["grad"], tol)
@@ -68,16 +69,21 @@ def test_second_step_and_determinism(gpu_device):
         g.stage.close()
     for a, b in zip(runs[0], runs[1]):
         assert np.array_equal(a, b)
-    # oracle: same two steps in fp64
+    # Step-2 gradient against the oracle run the same way (oracle parameters after its own first step).
     b, e = cfg.shard_range
     cfg = hp32(cfg)
+    p0 = inp.master.astype(np.float64)
     o1 = oracle_step(cfg, inp)
-    p1, m1, v1 = so.stage_optimizer_step(cfg, inp.master.astype(np.float64), o1["grad"], np.zeros(e - b), np.zeros(e - b), 1, (b, e))
+    p1, m1, v1 = so.stage_optimizer_step(cfg, p0, o1["grad"], np.zeros(e - b), np.zeros(e - b), 1, (b, e))
     inp2 = make_inputs(cfg, perturbed=True)
     inp2.params = p1
     o2 = oracle_step(cfg, inp2)
-    p2, m2, v2 = so.stage_optimizer_step(cfg, p1, o2["grad"], m1, v1, 2, (b, e))
-    from harness import rel_err
+    from harness import rel_err, update_err
     assert rel_err(runs[0][2], o2["grad"]) <= 1e-4
-    assert rel_err(runs[0][4], m2) <= 1e-4 and rel_err(runs[0][5], v2) <= 2.1e-4
-    assert rel_err(runs[0][3].astype(np.float64) - inp.master, p2 - inp.master.astype(np.float64)) <= 1e-3
+    # AdamW at t = 2 with non-zero moments: the oracle fed the GPU's own two gradients must land on the
+    # GPU's parameters and moments to fp32 rounding (the update itself is discontinuous in sign(g), so it
+    # is not compared across slightly different gradients).
+    q1, n1, w1 = so.stage_optimizer_step(cfg, p0, runs[0][0], np.zeros(e - b), np.zeros(e - b), 1, (b, e))
+    q2, n2, w2 = so.stage_optimizer_step(cfg, q1, runs[0][2], n1, w1, 2, (b, e))
+    assert rel_err(runs[0][4], n2) <= 1e-6 and rel_err(runs[0][5], w2) <= 1e-6
+    assert update_err(runs[0][3].astype(np.float64) - p0, q2 - p0, q2, nsteps=2) <= 2e-5
