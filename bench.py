@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Throughput of the per-stage training step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: M microbatch
+forwards, M backwards each followed by its gradient accumulation, then the AdamW update of the
+data-parallel shard (which also zeroes the gradient accumulators).  Inputs, parameters and
+optimizer state are resident in HBM before the timed region starts.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3]
+
+prints ONE JSON line: tokens/s of the stage step, the roofline figures of the dominant kernel
+(from HIP events recorded around every launch on the stage's stream during the timed steps), the
+model-FLOP utilisation, and the fp64 CPU oracle timed on a bounded sample of the same workload.
+Everything runs on one GPU; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (256 CUs x 4 SIMDs x 1024 flop/clk x 2.4 GHz)
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernels measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC = {}
+
+
+def model_flops_per_step(cfg):
+    """Algorithmic FLOPs: 3 x forward; forward per token per layer = 2*P_mat + 4*H*(S+1)/2 (causal half)."""
+    H, F, S = cfg.hidden, cfg.ffn, cfg.seq
+    p_mat = 4 * H * H + (3 if cfg.arch == 1 else 2) * H * F
+    per_tok = cfg.layers * (2 * p_mat + 4 * H * (S + 1) / 2)
+    if cfg.has_head:
+        per_tok += 2 * H * cfg.vocab
+    return 3.0 * per_tok * cfg.tokens * cfg.num_microbatches
+
+
+def fill_params(cfg, params, torch):
+    from workloads.configs import segments
+    for name, off, r, c, kind in segments(cfg):
+        seg = params[off:off + r * c]
+        if kind == "matrix":
+            seg.normal_(0.0, 0.02)
+        elif kind == "gain":
+            seg.fill_(1.0)
+        else:
+            seg.zero_()
+
+
+def cpu_baseline(cfg):
+    """The oracle as it stands, on the host cores: ONE decoder layer, ONE microbatch at the workload's
+    full shape, forward + backward in fp64 (numpy, BLAS threads as found).  Reported as stage-step
+    tokens/s by dividing by the number of layers; the optimizer step and, for head stages, the
+    embedding / LM head are left out of the sample, which makes the figure an upper bound."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import stage_oracle as so
+    from workloads import make_inputs
+    sample = cfg.with_(layers=1, num_microbatches=1, has_embed=0, has_head=0, vocab=0)
+    inp = make_inputs(sample)
+    t0 = time.time()
+    y, cache = so.stage_forward(sample, inp.params, inp.x[0])
+    so.stage_backward(sample, cache, inp.dy[0].astype(np.float64))
+    dt = time.time() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    tokps = sample.tokens / (dt * cfg.layers)
+    return {"value": tokps, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"1 of {cfg.layers} layers x 1 of {cfg.num_microbatches} microbatches ({sample.tokens} tokens) at full "
+                      f"shape, fwd+bwd in fp64 numpy: {dt:.1f} s; value = tokens / (time x layers), AdamW not included"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket launches with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the stage step on ONE GPU only (no collectives, no sharding across GPUs); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2507_10392_amd as zs
+    from workloads import get_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = get_config(args.workload)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    torch.manual_seed(cfg.seed)
+    cc = zs.make_config(cfg)
+    P, mem, _ = zs.query(cc)
+    b, e = cc.shard_begin, cc.shard_end
+    bf = cfg.dtype == 1
+    td = torch.bfloat16 if bf else torch.float32
+    M, T, H = cfg.num_microbatches, cfg.tokens, cfg.hidden
+
+    params = torch.empty(P, dtype=td, device=dev)
+    fill_params(cfg, params, torch)
+    master = params[b:e].float() if bf else None
+    grad = torch.zeros(P, dtype=torch.float32, device=dev)
+    m = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
+    v = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
+    ws = torch.empty(mem["workspace"], dtype=torch.uint8, device=dev)
+    if cfg.has_embed:
+        xs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)]
+    else:
+        xs = [torch.randn(T, H, device=dev).to(td) for _ in range(M)]
+    tgs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
+    losses = [torch.zeros(1, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
+    dys = [None] * M if cfg.has_head else [(torch.randn(T, H, device=dev) * 0.01).to(td) for _ in range(M)]
+    ys = [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
+    dxs = [None] * M if cfg.has_embed else [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
+    stage = zs.Stage(cc, params, master, grad, m, v, ws)
+
+    def step(t):
+        for i in range(M):
+            stage.forward(i, xs[i], ys[i], tgs[i], losses[i])
+        for i in reversed(range(M)):
+            stage.backward(i, dys[i], dxs[i], 1.0 / M)
+            stage.accumulate(i)
+        stage.optimizer_step(t)
+
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        step(t)
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        stage.profile(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        t += 1
+        step(t)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stats = stage.profile_read() if not args.no_kernel_events else {}
+    stage.profile(False)
+    finite = bool(torch.isfinite(params.float().sum()).item())
+
+    ms_per_step = dt * 1e3 / args.steps
+    tokens = T * M
+    value = tokens / (dt / args.steps)
+    mflops = model_flops_per_step(cfg)
+    mfu = mflops / (dt / args.steps) / (PEAK_BF16_TFLOPS * 1e12)
+
+    kernels = {}
+    for name, s in stats.items():
+        if s["launches"] == 0:
+            continue
+        avg_ms = s["ms"] / s["launches"]
+        k = {"launches_per_step": s["launches"] / args.steps, "avg_ms": avg_ms, "ms_per_step": s["ms"] / args.steps}
+        if s["flops"] > 0:
+            k["tflops"] = s["flops"] / s["ms"] / 1e9
+        if s["bytes"] > 0:
+            k["gbs"] = s["bytes"] / s["ms"] / 1e6
+        kernels[name] = k
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+        k = kernels[dom]
+        if "tflops" in k:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS}
+        else:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": k.get("gbs", 0.0), "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": k.get("gbs", 0.0) / PEAK_HBM_GBS}
+        roofline["avg_launch_ms"] = k["avg_ms"]
+        roofline["traffic"] = MEASURED_TRAFFIC.get((args.workload, dom))
+
+    out = {
+        "metric": "stage train tokens/s on 1 MI355X (fwd+bwd+AdamW); MFMA util % of bf16 peak",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.layers} layers, hidden {cfg.hidden}, heads {cfg.heads}, ffn {cfg.ffn}, "
+                               f"seq {cfg.seq}, microbatch {cfg.microbatch} x {M} microbatches, "
+                               f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {e - b} of {P} params, "
+                               f"recompute {cfg.recompute}",
+                   "tokens_per_step": tokens, "shard_elems": e - b},
+        "mfu_model_flops": mfu, "model_tflop_per_step": mflops / 1e12, "finite": finite,
+        "roofline": roofline, "kernels": kernels,
+    }
+    if "adamw" in kernels:
+        out["adamw_hbm_frac"] = kernels["adamw"].get("gbs", 0.0) / PEAK_HBM_GBS
+    stage.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
