@@ -66,20 +66,21 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int s) {
 // A 64 x 128 tile moves HBM -> registers (fetch, issued before the MFMAs of the current tile so the
 // latency hides behind them) -> LDS (put, after them).  Thread t carries 4 vectors of 16 bytes:
 // vector v = t + 256 i is row v/16, columns 8*(v%16)...  Rows >= nrows read as zero.
-struct TileRegs { bf16x8 v[4]; };
-__device__ __forceinline__ void fetch_tile(TileRegs& x, const bf16* __restrict__ src, int64_t ld, int row0, int nrows,
+template <int NT> struct TileRegs { bf16x8 v[1024 / NT]; };   // NT threads share the 1024 vectors of a tile
+template <int NT>
+__device__ __forceinline__ void fetch_tile(TileRegs<NT>& x, const bf16* __restrict__ src, int64_t ld, int row0, int nrows,
                                            int tid) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = tid + 256 * i;
+  for (int i = 0; i < 1024 / NT; ++i) {
+    const int v = tid + NT * i;
     const int r = v >> 4, c = (v & 15) * 8;
     x.v[i] = (row0 + r < nrows) ? *reinterpret_cast<const bf16x8*>(src + (int64_t)(row0 + r) * ld + c) : zero8();
   }
 }
-__device__ __forceinline__ void put_tile(const TileRegs& x, bf16* tile, int tid) {
+template <int NT> __device__ __forceinline__ void put_tile(const TileRegs<NT>& x, bf16* tile, int tid) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int v = tid + 256 * i;
+  for (int i = 0; i < 1024 / NT; ++i) {
+    const int v = tid + NT * i;
     *reinterpret_cast<bf16x8*>(tile + (v >> 4) * LDT + (v & 15) * 8) = x.v[i];
   }
 }
@@ -99,7 +100,7 @@ __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 
 
 // ------------------------------------------------------------------------------------------ forward
 // grid (ceil(S/128), nh, mb); wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
-__global__ __launch_bounds__(256) void attn_fwd_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                        const bf16* __restrict__ v, int64_t ld, bf16* __restrict__ o,
                                                        int64_t ldo, float* __restrict__ lse, float scale_log2) {
   extern __shared__ __align__(16) char smem_raw[];
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int S, const bf16* __rest
 
   const int last_q = min(q0 + 127, S - 1);
   const int ntiles = last_q / TR + 1;
-  TileRegs kr, vr;
+  TileRegs<256> kr, vr;
   fetch_tile(kr, kh, ld, 0, S, tid);
   fetch_tile(vr, vh, ld, 0, S, tid);
   put_tile(kr, smem, tid);
@@ -149,36 +150,44 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(int S, const bf16* __rest
         for (int s = 0; s < 8; ++s)
           sacc[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Kt, jb * 32, 16 * s, lane), qf[s], sacc[jb], 0, 0, 0);
       }
-      const bool diag = key0 + TR - 1 > wq0;
+      if (key0 + TR - 1 > wq0) {   // tile touches the diagonal: mask keys in the future of this lane's query
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (key0 + jb * 32 + acc_row(r, lane) > my_q) sacc[jb][r] = -INFINITY;
+      }
       float mx = -INFINITY;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float s = sacc[jb][r] * scale_log2;
-          if (diag && key0 + jb * 32 + acc_row(r, lane) > my_q) s = -INFINITY;
-          sacc[jb][r] = s;
-          mx = fmaxf(mx, s);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mn = fmaxf(m, mx);            // finite: key 0 is visible to every query in the first tile
-      const float alpha = exp2f(m - mn);
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[jb][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;   // scale > 0, so the maximum commutes with it
+      // Lazy rescaling: the reference maximum m only moves when some row's maximum grew by more than 2^8;
+      // until then P is formed against the old reference (values up to 2^8, harmless in bf16/fp32) and the
+      // 64 accumulator registers are left alone.  m, l and O always refer to the same reference, so
+      // O/l and m + log2(l) are exact whatever the schedule of updates.
+      if (__any(mx > m + 8.0f)) {
+        const float mn = fmaxf(m, mx);          // finite: key 0 is visible to every query in the first tile
+        const float alpha = __builtin_amdgcn_exp2f(m - mn);
+        l *= alpha;
+        m = mn;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+      }
       float rs = 0.f;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = exp2f(sacc[jb][r] - mn);
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[jb][r], scale_log2, -m));
           sacc[jb][r] = p;
           rs += p;
         }
       rs += __shfl_xor(rs, 32, 64);
-      l = l * alpha + rs;
-      m = mn;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+      l += rs;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
@@ -231,7 +240,7 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(int S, const bf16*
 // ------------------------------------------------------------------------------------------ dQ
 // grid (ceil(S/128), nh, mb); wave w owns queries q0+32w..; loops over K/V tiles up to the diagonal.
 // dQ^T[d][q] += K^T[d][key] dS^T[key][q],  dS^T = P^T o (dP^T - delta_q),  dP^T = V dO^T.
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                           const bf16* __restrict__ v, int64_t ld,
                                                           const bf16* __restrict__ dout, int64_t ldo,
                                                           const float* __restrict__ lse, const float* __restrict__ delta,
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int S, const bf16* __r
 
   const int last_q = min(q0 + 127, S - 1);
   const int ntiles = last_q / TR + 1;
-  TileRegs kr, vr;
+  TileRegs<256> kr, vr;
   fetch_tile(kr, kh, ld, 0, S, tid);
   fetch_tile(vr, vh, ld, 0, S, tid);
   put_tile(kr, smem, tid);
@@ -291,10 +300,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int S, const bf16* __r
           pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Vt, jb * 32, 16 * s, lane), dof[s], pacc, 0, 0, 0);
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = exp2f(sacc[r] * scale_log2 - lse2);
-          if (diag && key0 + jb * 32 + acc_row(r, lane) > my_q) p = 0.f;
-          sacc[r] = p * (pacc[r] - dlt);
+        for (int r = 0; r < 16; ++r) sacc[r] = __builtin_amdgcn_exp2f(fmaf(sacc[r], scale_log2, -lse2)) * (pacc[r] - dlt);
+        if (diag) {   // keys in the future of this lane's query contribute nothing
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (key0 + jb * 32 + acc_row(r, lane) > my_q) sacc[r] = 0.f;
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
@@ -327,10 +337,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(int S, const bf16* __r
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-// grid (ceil(S/128), nh, mb); wave w owns keys k0+32w..; loops over Q/dO tiles from the diagonal to the end.
+// grid (ceil(S/(32 NW)), nh, mb), NW waves; wave w owns keys k0+32w..; loops over Q/dO tiles from the diagonal to the
+// end.  With 8 waves the staged Q/dO tiles serve 256 keys and two waves share each SIMD, so one wave's
+// softmax arithmetic overlaps the other's MFMAs.
 // S[q][key] = Q K^T (lane = key, registers = queries), P = exp2(S c - lse_q), dP = dO V^T,
 // dV^T[d][key] += dO^T[d][q] P[q][key],  dK^T[d][key] += Q^T[d][q] dS[q][key].
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                            const bf16* __restrict__ v, int64_t ld,
                                                            const bf16* __restrict__ dout, int64_t ldo,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
@@ -349,7 +362,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int S, const bf16* __
   const bf16* doh = dout + tok0 * ldo + h * D;
   const float* lse_h = lse + ((int64_t)b * nh + h) * S;
   const float* dlt_h = delta + ((int64_t)b * nh + h) * S;
-  const int k0 = kb * 128, wk0 = k0 + wave * 32;
+  const int k0 = kb * 32 * NW, wk0 = k0 + wave * 32;
   const int my_k = wk0 + (lane & 31);
   const float scale_log2 = scale * LOG2E;
 
@@ -362,7 +375,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int S, const bf16* __
 #pragma unroll
     for (int r = 0; r < 16; ++r) dkacc[i][r] = dvacc[i][r] = 0.f;
 
-  TileRegs qr, dor;
+  TileRegs<64 * NW> qr, dor;
   float statr = 0.f;
   auto fetch = [&](int t) {
     fetch_tile(qr, qh, ld, t * TR, S, tid);
@@ -404,10 +417,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(int S, const bf16* __
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int qi = ib * 32 + acc_row(r, lane);
-          float p = exp2f(sacc[r] * scale_log2 - st[qi]);
-          if ((diag && qrow0 + qi < my_k) || qrow0 + qi >= S) p = 0.f;
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], scale_log2, -st[qi]));
           sacc[r] = p;
           pacc[r] = p * (pacc[r] - st[64 + qi]);
+        }
+        if (diag || qrow0 + TR > S) {   // queries before this lane's key, and rows past the end, contribute nothing
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int qi = ib * 32 + acc_row(r, lane);
+            if (qrow0 + qi < my_k || qrow0 + qi >= S) sacc[r] = pacc[r] = 0.f;
+          }
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
@@ -472,9 +491,10 @@ hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
 hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
                          void* dq, void* dk, void* dv, int64_t ldd) {
-  static bool cfg1 = false, cfg2 = false;
+  static bool cfg1 = false, cfg2 = false, cfg3 = false;
   hipError_t e = set_smem(attn_bwd_dq_kernel, SMEM_FWD, cfg1);
-  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel, SMEM_DKV, cfg2);
+  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<4>, SMEM_DKV, cfg2);
+  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<8>, SMEM_DKV, cfg3);
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)d);
   dim3 grid((unsigned)cdiv(S, 128), (unsigned)nh, (unsigned)mb), blk(256);
@@ -482,8 +502,15 @@ hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
                      (const bf16*)o, (const bf16*)dout, ldo, delta);
   hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
                      (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale);
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, grid, blk, SMEM_DKV, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                     (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale);
+  // 256 keys per workgroup when that still gives every CU a workgroup, else 128
+  if (cdiv(S, 256) * nh * mb >= 256) {
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)cdiv(S, 256), (unsigned)nh, (unsigned)mb), dim3(512), SMEM_DKV, st,
+                       S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld, (const bf16*)dout, ldo, lse, delta, (bf16*)dk,
+                       (bf16*)dv, ldd, scale);
+  } else {
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<4>, grid, blk, SMEM_DKV, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
+                       (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale);
+  }
   return hipGetLastError();
 }
 
