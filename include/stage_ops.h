@@ -20,7 +20,8 @@ extern "C" {
  * 1: C is float and the product is added to it.  bias/resid may be NULL.  batch >= 1 with element
  * strides sA, sB, sC (sC also for resid), sBias.  kseg > 0: K is cut in segments of kseg and segment
  * s reads B from B + s*segB.  impl: 0 automatic, 1 the plain fp32-FMA kernel, 2 the bf16 MFMA
- * kernel (STAGE_ERR_ARG if the shape/alignment is not supported by it). */
+ * kernel with its own choice of workgroup tile, 3 / 4 the MFMA kernel with the 256x256 / 128x128
+ * tile (STAGE_ERR_ARG if the shape/alignment is not supported by the MFMA kernel). */
 int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
                   const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
                   const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,

@@ -1,309 +1,15 @@
-// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
-//
-// One workgroup of 4 wavefronts computes a 256x256 tile of C; each wavefront owns a 128x128
-// quadrant as 4x4 MFMA blocks of 32x32 (256 accumulator registers per lane).  The K loop walks
-// 64-wide slabs.  A slab of each operand is fetched from HBM with 16-byte loads into registers
-// one iteration ahead and stored into one of two LDS buffers exactly as it lies in memory:
-//   * contraction index contiguous in memory  -> LDS [row][k], rows padded to 72 elements; an MFMA
-//     operand fragment (8 consecutive k of one row) is one ds_read_b128;
-//   * row index contiguous in memory (B of y = x W with W stored [in,out]; both operands of
-//     dW = x^T dy) -> LDS [k][row], rows padded to 272 elements; the fragment is two
-//     ds_read_b64_tr_b16, the LDS transpose read of gfx950, each returning 4 consecutive k.
-// The paddings put the 16 lanes that the LDS serves together on distinct banks.  Interior tiles
-// use unconditional loads; edge tiles and a ragged last slab go through predicated loads.
-// Workgroup ids are remapped so that the 8 XCDs (ids are dealt round-robin to them) each work
-// on a compact patch of C and re-use their own L2's A rows and B columns.
+// bf16 MFMA GEMM: argument checks and the choice of workgroup tile.  The kernels live in
+// gemm_mfma_impl.h, one translation unit per tile shape.
 #include "kernels.h"
 
 namespace zs {
 
+hipError_t gemm_mfma_256x256(hipStream_t st, const Gemm& g);   // 8 wavefronts
+hipError_t gemm_mfma_128x128(hipStream_t st, const Gemm& g);   // 4 wavefronts, two workgroups per CU
+
 namespace {
-
-constexpr int BM = 256, BN = 256, BK = 64;
-#ifndef GEMM_LDR
-#define GEMM_LDR 272
-#endif
-constexpr int LDK = BK + 8;                       // [row][k] layout: padded row length (144 bytes)
-constexpr int LDR = GEMM_LDR;                     // [k][row] layout: padded row length
-constexpr int TILE_ELEMS = BM * LDK;              // LDS elements reserved per operand slab (>= BK*LDR)
-static_assert(BK * LDR <= TILE_ELEMS, "slab size");
-constexpr int NTHREADS = 256;
-
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-struct Frag { u32x4 v[8]; };                      // one thread's share of a 256x64 slab: 8 x 16 bytes
-
-// Operands are read through raw buffer descriptors: the per-lane offset is one VGPR, the per-load
-// offset a scalar, and anything at or beyond num_records reads as zero, which handles the ragged edge
-// along each operand's OUTER dimension for free.  The edge along the inner (contiguous) dimension
-// still needs a mask, applied under a workgroup-uniform condition.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ void zero_frag(Frag& f) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) f.v[i] = u32x4{0u, 0u, 0u, 0u};
-}
-
-// Operand stored [rows, K] (k contiguous), ld = row stride.  Thread t carries vectors v = t + 256*i:
-// row = v/8, k-vector = v%8 (= t%8 for every i).  voff = ((t/8)*ld + (t%8)*8)*2 bytes (+ segment shift).
-__device__ __forceinline__ void load_kmajor(Frag& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int k0, int K,
-                                            int tid) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((row0 + 32 * i) * ld + k0) * 2, 0);
-  if (k0 + BK > K && k0 + (tid & 7) * 8 >= K) zero_frag(f);     // ragged last slab
-}
-__device__ __forceinline__ void store_kmajor(const Frag& f, bf16* lds, int tid) {
-  bf16* p = lds + (tid >> 3) * LDK + (tid & 7) * 8;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(p + 32 * i * LDK) = f.v[i];
-}
-
-// Operand stored [K, rows] (row index contiguous).  Thread t carries vectors v = t + 256*i:
-// k = v/32, row-vector = v%32 (= t%32 for every i).  voff = ((t/32)*ld + (t%32)*8)*2 bytes.
-__device__ __forceinline__ void load_rmajor(Frag& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int nrows,
-                                            int k0, int tid) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((k0 + 8 * i) * ld + row0) * 2, 0);
-  if (row0 + BM > nrows && row0 + (tid & 31) * 8 >= nrows) zero_frag(f);   // ragged edge tile
-}
-__device__ __forceinline__ void store_rmajor(const Frag& f, bf16* lds, int tid) {
-  bf16* p = lds + (tid >> 5) * LDR + (tid & 31) * 8;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(p + 8 * i * LDR) = f.v[i];
-}
-
-// MFMA operand fragment for lane (row = lane%32, g = lane/32): the 8 values k = k16 + 8g .. +7 of that row.
-__device__ __forceinline__ bf16x8 frag_kmajor(const bf16* tile, int row0, int k16, int lane) {
-  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 31)) * LDK + k16 + 8 * (lane >> 5));
-}
-// Same fragment from a [k][row] tile.  One transpose read serves 16 lanes: lane r of the group points at
-// 4 consecutive rows of k-line (r/4) and receives the 4 k-lines' values of ONE row.
-__device__ __forceinline__ bf16x8 frag_rmajor(const bf16* tile, int row0, int k16, int lane) {
-  const int r = lane & 15, gi = lane >> 4;
-  const bf16* p = tile + (k16 + 8 * (gi >> 1) + (r >> 2)) * LDR + row0 + 16 * (gi & 1) + 4 * (r & 3);
-  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-  u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-  u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * LDR));
-  return u.v;
-}
-
-// Workgroup id -> tile origin.  Ids are dealt round-robin to the 8 XCDs, so id%8 picks the XCD; each XCD
-// is given a contiguous run of the tile order, and that order walks groups of 8 tile rows column by
-// column, so the tiles an XCD works on at one time share A rows and B columns in its L2.
-__device__ __forceinline__ void tile_origin(int pid, int tiles_m, int tiles_n, int& m0, int& n0) {
-  const int ntiles = tiles_m * tiles_n;
-  const int per = ntiles / 8;                             // ids [0, 8*per) are remapped, the rest stay
-  if (pid < per * 8) pid = (pid % 8) * per + pid / 8;
-  constexpr int GROUP = 8;
-  const int width = GROUP * tiles_n;
-  const int group_id = pid / width;
-  const int first_m = group_id * GROUP;
-  const int gsz = min(tiles_m - first_m, GROUP);
-  m0 = (first_m + (pid % width) % gsz) * BM;
-  n0 = ((pid % width) / gsz) * BN;
-}
-
-// Epilogue for float accumulation (weight gradients).  The MFMAs were issued as mfma(A fragment, B fragment):
-// acc[i][j][r] is C[row, col] with row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32 inside block (i, j), so the
-// 32 lanes of a half-wave hit 128 consecutive bytes of one row with each atomic.
-__device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x16 (&acc)[4][4], int m0, int n0, int wm, int wn,
-                                               int lane) {
-  const bf16* bias = g.bias ? (const bf16*)g.bias + (int64_t)z * g.sBias : nullptr;
-  const bf16* R = g.resid ? (const bf16*)g.resid + (int64_t)z * g.sC : nullptr;
-  float* Cz = (float*)g.C + (int64_t)z * g.sC;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int col = n0 + wn + j * 32 + (lane & 31);
-    if (col >= g.N) continue;
-    const float bv = bias ? (float)bias[col] : 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row >= g.M) continue;
-        float v = acc[i][j][r] + bv;
-        if (R) v += (float)R[(int64_t)row * g.ldr + col];
-        // Hardware float add at L2 without a return value: the wave does not wait for the old value.
-        // Every element receives exactly one add per launch and launches are ordered by the stream,
-        // so the sum over microbatches is formed in a fixed order.
-        unsafeAtomicAdd(Cz + (int64_t)row * g.ldc + col, v);
-      }
-    }
-  }
-}
-
-// Epilogue for bf16 output.  The MFMAs were issued with the operands swapped, mfma(B fragment, A fragment),
-// which yields the transposed block: acc[i][j][r] is C[row, col] with row = lane%32 and
-// col = 8*(r/4) + 4*(lane/32) + r%4.  A lane then owns 4 consecutive columns per register quad and
-// stores them (and reads the residual) as one 8-byte access.
-__device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&acc)[4][4], int m0, int n0, int wm, int wn,
-                                               int lane) {
-  const bf16* bias = g.bias ? (const bf16*)g.bias + (int64_t)z * g.sBias : nullptr;
-  const bf16* R = g.resid ? (const bf16*)g.resid + (int64_t)z * g.sC : nullptr;
-  bf16* Cz = (bf16*)g.C + (int64_t)z * g.sC;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = m0 + wm + i * 32 + (lane & 31);
-    if (row >= g.M) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int col = n0 + wn + j * 32 + 8 * c + 4 * (lane >> 5);
-        if (col >= g.N) continue;
-        float v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * c + e];
-        if (col + 4 <= g.N) {
-          if (bias) {
-            const bf16x4 bb = *reinterpret_cast<const bf16x4*>(bias + col);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)bb[e];
-          }
-          if (R) {
-            const bf16x4 rr = *reinterpret_cast<const bf16x4*>(R + (int64_t)row * g.ldr + col);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)rr[e];
-          }
-          bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-          *reinterpret_cast<bf16x4*>(Cz + (int64_t)row * g.ldc + col) = o;
-        } else {
-          for (int e = 0; e < 4 && col + e < g.N; ++e) {
-            float x = v[e];
-            if (bias) x += (float)bias[col + e];
-            if (R) x += (float)R[(int64_t)row * g.ldr + col + e];
-            Cz[(int64_t)row * g.ldc + col + e] = (bf16)x;
-          }
-        }
-      }
-    }
-  }
-}
-
-template <int TA, int TB, int SEG, int ACC>
-__global__ __launch_bounds__(NTHREADS) void gemm_mfma_kernel(Gemm g, int tiles_m, int tiles_n) {
-  extern __shared__ __align__(16) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);        // [2 buffers][A slab | B slab]
-
-  int m0, n0;
-  tile_origin(blockIdx.x, tiles_m, tiles_n, m0, n0);
-
-  const int z = blockIdx.y;
-  const bf16* A = (const bf16*)g.A + (int64_t)z * g.sA;
-  const bf16* B = (const bf16*)g.B + (int64_t)z * g.sB;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
-
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const int nk = (g.K + BK - 1) / BK;
-  // One register stage: slab kt+1 is loaded into registers while slab kt is multiplied out of LDS.
-  Frag fa0, fb0;
-  const int lda = (int)g.lda, ldb = (int)g.ldb;
-  const __amdgpu_buffer_rsrc_t rsA =
-      make_rsrc(A, (uint32_t)(TA == 0 ? ((int64_t)(g.M - 1) * lda + g.K) : ((int64_t)(g.K - 1) * lda + g.M)) * 2u);
-  const int nseg = SEG ? g.K / g.kseg : 1;
-  const __amdgpu_buffer_rsrc_t rsB = make_rsrc(
-      B, (uint32_t)(TB == 1 ? ((int64_t)(nseg - 1) * g.segB + (int64_t)(g.N - 1) * ldb + (SEG ? g.kseg : g.K))
-                            : ((int64_t)(g.K - 1) * ldb + g.N)) * 2u);
-  const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : ((tid >> 5) * lda + (tid & 31) * 8) * 2;
-  const int voffB = TB == 1 ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2 : ((tid >> 5) * ldb + (tid & 31) * 8) * 2;
-
-  auto fetch = [&](int kt, Frag& fa, Frag& fb) {
-    const int k0 = kt * BK;
-    if (TA == 0) load_kmajor(fa, rsA, voffA, lda, m0, k0, g.K, tid);
-    else load_rmajor(fa, rsA, voffA, lda, m0, g.M, k0, tid);
-    if (TB == 1) {
-      int vo = voffB;
-      if (SEG) {  // the thread's k offset inside the slab is fixed, so one segment lookup per slab
-        const int seg = (k0 + (tid & 7) * 8) / g.kseg;
-        vo += seg * ((int)g.segB - g.kseg) * 2;          // element (n, k) of segment seg lies at seg*segB + n*ldb + k - seg*kseg
-      }
-      load_kmajor(fb, rsB, vo, ldb, n0, k0, g.K, tid);
-    } else {
-      load_rmajor(fb, rsB, voffB, ldb, n0, g.N, k0, tid);
-    }
-  };
-  auto stash = [&](int buf, const Frag& fa, const Frag& fb) {
-    bf16* As = smem + buf * 2 * TILE_ELEMS;
-    bf16* Bs = As + TILE_ELEMS;
-    if (TA == 0) store_kmajor(fa, As, tid); else store_rmajor(fa, As, tid);
-    if (TB == 1) store_kmajor(fb, Bs, tid); else store_rmajor(fb, Bs, tid);
-  };
-  auto multiply = [&](int buf) {
-    const bf16* As = smem + buf * 2 * TILE_ELEMS;
-    const bf16* Bs = As + TILE_ELEMS;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        a[i] = TA == 0 ? frag_kmajor(As, wm + i * 32, ks * 16, lane) : frag_rmajor(As, wm + i * 32, ks * 16, lane);
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        b[j] = TB == 1 ? frag_kmajor(Bs, wn + j * 32, ks * 16, lane) : frag_rmajor(Bs, wn + j * 32, ks * 16, lane);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = ACC ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0)
-                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
-    }
-  };
-
-  // The fetch past the last slab is issued unconditionally: its offsets lie beyond num_records (or are
-  // masked), so it reads zeros, touches no memory, and lands in a buffer nobody multiplies.
-  fetch(0, fa0, fb0);
-  stash(0, fa0, fb0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    fetch(kt + 1, fa0, fb0);                             // global loads in flight during the MFMAs below
-    multiply(buf);
-    stash(buf ^ 1, fa0, fb0);                            // the other buffer was last read before the previous barrier
-    __syncthreads();
-  }
-
-  if (ACC) epilogue_accum(g, z, acc, m0, n0, wm, wn, lane);
-  else epilogue_store(g, z, acc, m0, n0, wm, wn, lane);
-}
-
-constexpr size_t SMEM_BYTES = 2 * 2 * TILE_ELEMS * sizeof(bf16);   // 147456
-
-template <int TA, int TB, int SEG, int ACC> hipError_t launch2(hipStream_t st, const Gemm& g) {
-  static bool configured = false;
-  auto kern = gemm_mfma_kernel<TA, TB, SEG, ACC>;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  const int tiles_m = (int)cdiv(g.M, BM), tiles_n = (int)cdiv(g.N, BN);
-  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)g.batch), blk(NTHREADS);
-  hipLaunchKernelGGL(kern, grid, blk, SMEM_BYTES, st, g, tiles_m, tiles_n);
-  return hipGetLastError();
-}
-
-template <int TA, int TB, int SEG> hipError_t launch(hipStream_t st, const Gemm& g) {
-  return g.c_f32_accum ? launch2<TA, TB, SEG, 1>(st, g) : launch2<TA, TB, SEG, 0>(st, g);
-}
-
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
-
+int g_force_tile = 0;   // 0 automatic; 1: 256x256, 2: 128x128 (set through gemm_mfma_force_tile)
 }  // namespace
 
 // The kernel needs 16-byte aligned rows for its vector loads: base pointers 16-byte aligned and
@@ -334,14 +40,26 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
   return true;
 }
 
+// Which tile: the MI355X has 256 CUs.  256x256 tiles (8 waves, one workgroup per CU) move the fewest LDS and
+// L2 bytes per flop; 128x128 tiles (two workgroups per CU) run at about 0.8 of their rate (measured at
+// K = 4096) but waste less of the last round of workgroups and give small problems enough workgroups to
+// fill the chip.  The shape with the smaller estimated time wins.
+int gemm_mfma_pick_tile(const Gemm& g) {
+  if (g_force_tile) return g_force_tile;
+  const int64_t big = cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
+  const int64_t small = cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch;
+  const double t_big = (double)cdiv(big, 256) * 256.0 * 256.0;
+  // full rounds hold 512 small tiles (two per CU, each at 0.8 of the big tile's rate); a remainder of at
+  // most 256 tiles runs one per CU
+  const int64_t rem = small % 512;
+  const double t_small = ((double)(small / 512) * 2.0 + (rem == 0 ? 0.0 : rem <= 256 ? 1.0 : 2.0)) * 128.0 * 128.0 / 0.8;
+  return t_small < t_big ? 2 : 1;
+}
+
+void gemm_mfma_force_tile(int id) { g_force_tile = id; }
+
 hipError_t gemm_mfma(hipStream_t st, const Gemm& g) {
-  if (g.kseg) {
-    return g.transA ? launch<1, 1, 1>(st, g) : launch<0, 1, 1>(st, g);
-  }
-  if (!g.transA && !g.transB) return launch<0, 0, 0>(st, g);
-  if (!g.transA && g.transB) return launch<0, 1, 0>(st, g);
-  if (g.transA && !g.transB) return launch<1, 0, 0>(st, g);
-  return launch<1, 1, 0>(st, g);
+  return gemm_mfma_pick_tile(g) == 2 ? gemm_mfma_128x128(st, g) : gemm_mfma_256x256(st, g);
 }
 
 }  // namespace zs

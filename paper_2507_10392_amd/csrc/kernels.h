@@ -31,6 +31,9 @@ hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force);
 hipError_t gemm_simple(hipStream_t st, DType dt, const Gemm& g);
 bool gemm_mfma_supported(DType dt, const Gemm& g);
 hipError_t gemm_mfma(hipStream_t st, const Gemm& g);
+// Workgroup tile the MFMA kernel would use: 1 = 256x256 (8 waves), 2 = 128x128 (4 waves); force_tile(0) = automatic.
+int gemm_mfma_pick_tile(const Gemm& g);
+void gemm_mfma_force_tile(int id);
 
 // kind 0 LayerNorm (mean and rstd saved), 1 RMSNorm (rstd saved).  b and mean may be NULL for RMSNorm.
 hipError_t norm_fwd(hipStream_t st, DType dt, int kind, int T, int H, const void* x, const void* g, const void* b,

@@ -26,8 +26,12 @@ int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, i
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.c_f32_accum = c_f32_accum != 0;
   g.bias = bias; g.resid = resid; g.ldr = ldr; g.batch = batch; g.sA = sA; g.sB = sB; g.sC = sC; g.sBias = sBias;
   g.kseg = kseg; g.segB = segB;
-  if (impl == GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
-  return rc(gemm((hipStream_t)stream, (DType)dtype, g, impl));
+  if (impl < 0 || impl > 4) return STAGE_ERR_ARG;
+  if (impl >= GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
+  if (impl > GEMM_MFMA) gemm_mfma_force_tile(impl - GEMM_MFMA);     // 3, 4: fixed workgroup tile
+  const hipError_t e = gemm((hipStream_t)stream, (DType)dtype, g, impl > GEMM_MFMA ? GEMM_MFMA : impl);
+  gemm_mfma_force_tile(0);
+  return rc(e);
 }
 
 int stage_op_norm_fwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* x, const void* g,

@@ -47,12 +47,12 @@ GEMM_CASES = [
 ]
 
 
-@pytest.mark.parametrize("impl", [1, 2])
+@pytest.mark.parametrize("impl", [1, 2, 3, 4])
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("case", GEMM_CASES, ids=lambda c: "x".join(str(int(v)) for v in c))
 def test_gemm_matches_float64_matmul(gpu_device, case, dtype, impl):
     M, N, K, ta, tb, batch, kseg, use_bias, use_res, accum = case
-    if impl == 2 and dtype == 0:
+    if impl >= 2 and dtype == 0:
         pytest.skip("the MFMA kernel is bf16 only")
     print(f"[case] gemm {case} dtype={dtype} impl={impl}", flush=True)
     rng = np.random.default_rng(hash(case) % 2**32)
