@@ -14,7 +14,9 @@
 // The paddings put the 16 lanes that the LDS serves together on distinct banks.
 // Workgroup ids are remapped so that the 8 XCDs (ids are dealt round-robin to them) each work
 // on a compact patch of C and re-use their own L2's A rows and B columns.
-// The 128x128 tile needs 64 accumulator registers and 74 KB of LDS, so two workgroups share a CU.
+// The 256x256 tile runs 8 wavefronts (128 accumulator registers each, two waves per SIMD); the 128x128 tile
+// runs 4 and needs 64 accumulator registers and 74 KB of LDS, so two workgroups share a CU.  Either way a
+// SIMD always has a second wave to issue MFMAs while the first waits for memory, LDS or a barrier.
 #pragma once
 #include "kernels.h"
 
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : voff_rmajor<BM>(lda, tid);
   const int voffB = TB == 1 ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2 : voff_rmajor<BN>(ldb, tid);
 
-  auto fetch = [&](int kt) {
+  auto fetch = [&](int kt, Frag<BM, NT>& fa0, Frag<BN, NT>& fb0) {
     const int k0 = kt * BK;
     if (TA == 0) load_kmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0, g.K, tid);
     else load_rmajor<BM, NT>(fa0, rsA, voffA, lda, m0, g.M, k0, tid);
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, n0, g.N, k0, tid);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](int buf, const Frag<BM, NT>& fa0, const Frag<BN, NT>& fb0) {
     bf16* As = smem + buf * (SLAB_A + SLAB_B);
     bf16* Bs = As + SLAB_A;
     if (TA == 0) store_kmajor<BM, NT>(fa0, As, tid); else store_rmajor<BM, NT>(fa0, As, tid);
@@ -280,14 +282,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 
   // The fetch past the last slab is issued unconditionally: its offsets lie beyond num_records (or are
   // masked), so it reads zeros, touches no memory, and lands in a buffer nobody multiplies.
-  fetch(0);
-  stash(0);
+  fetch(0, fa0, fb0);
+  stash(0, fa0, fb0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    fetch(kt + 1);                                       // global loads in flight during the MFMAs below
+    fetch(kt + 1, fa0, fb0);                             // global loads in flight during the MFMAs below
     multiply(buf);
-    stash(buf ^ 1);                                      // the other buffer was last read before the previous barrier
+    stash(buf ^ 1, fa0, fb0);                            // the other buffer was last read before the previous barrier
     __syncthreads();
   }
 

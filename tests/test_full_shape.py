@@ -1,0 +1,114 @@
+"""GPU checks at the benchmark's full shapes, in the launch configuration bench.py times.
+
+One decoder layer and one microbatch of the 7B-class (C3) and 1.3B-class (C2) stages are compared
+with the oracle element by element (the oracle needs about ten seconds per layer on the host);
+whole heads of the full-size attention are compared with the oracle's attention; and properties
+that hold at any size (bit-identical repeats, recompute neutrality, two equal microbatches
+accumulate to exactly twice one) are checked on a full-shape stage.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_10392_amd as zs
+from harness import TOL, GpuStage, compare_step, dev, log_report, oracle_step, rel_err
+from oracle import stage_oracle as so
+from workloads import get_config, make_inputs, round_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["C3", "C2"])
+def test_one_layer_one_microbatch_at_full_shape(gpu_device, name):
+    cfg = get_config(name).with_(layers=1, num_microbatches=1, shard_num=1, shard_den=1)
+    print(f"[case] full-shape single layer {name}: T={cfg.tokens} H={cfg.hidden} F={cfg.ffn}", flush=True)
+    inp = make_inputs(cfg, perturbed=True)
+    g = GpuStage(cfg, inp)
+    gpu = g.run_microbatches(inp)
+    g.stage.close()
+    ora = oracle_step(cfg, inp)
+    rep = []
+    compare_step(cfg, gpu, ora, TOL[cfg.dtype], rep)
+    log_report(f"full-shape single layer {name}", sorted(rep, key=lambda r: -r[1])[:8])
+
+
+def test_attention_full_size_heads_match_oracle(gpu_device):
+    """S = 4096, 32 heads of 128: every row of the first and the last head, forward and backward."""
+    mb, S, nh, d = 1, 4096, 32, 128
+    H = nh * d
+    print(f"[case] full-size attention S={S} nh={nh}", flush=True)
+    rng = np.random.default_rng(21)
+    qkv = round_bf16(rng.standard_normal((S, 3 * H)).astype(np.float32))
+    do = round_bf16(rng.standard_normal((S, H)).astype(np.float32))
+    dq_in = dev(qkv, torch.bfloat16)
+    o = torch.empty(S, H, dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty(nh * S, device="cuda")
+    delta = torch.empty(nh * S, device="cuda")
+    dqkv = torch.empty(S, 3 * H, dtype=torch.bfloat16, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    qp, kp, vp = (torch.as_strided(dq_in, (S, H), (3 * H, 1), i * H) for i in range(3))
+    dqp, dkp, dvp = (torch.as_strided(dqkv, (S, H), (3 * H, 1), i * H) for i in range(3))
+    zs.ops.attention_fwd(st, 1, mb, S, nh, d, qp, kp, vp, 3 * H, o, H, lse, 2)
+    zs.ops.attention_bwd(st, 1, mb, S, nh, d, qp, kp, vp, 3 * H, o, dev(do, torch.bfloat16), H, lse, delta, dqp, dkp,
+                         dvp, 3 * H, 2)
+    torch.cuda.synchronize()
+    og, dg = o.float().cpu().numpy(), dqkv.float().cpu().numpy()
+    rows = []
+    for h in (0, nh - 1):
+        sl = slice(h * d, (h + 1) * d)
+        q, k, v = (qkv[:, i * H + h * d:i * H + (h + 1) * d].astype(np.float64).reshape(1, S, 1, d) for i in range(3))
+        o_o = so.attention_fwd(q, k, v)[0, :, 0]
+        dq_o, dk_o, dv_o = so.attention_bwd(do[:, sl].astype(np.float64).reshape(1, S, 1, d), q, k, v)
+        rows += [(f"o h{h}", rel_err(og[:, sl], o_o)), (f"dq h{h}", rel_err(dg[:, sl], dq_o[0, :, 0])),
+                 (f"dk h{h}", rel_err(dg[:, H + h * d:H + (h + 1) * d], dk_o[0, :, 0])),
+                 (f"dv h{h}", rel_err(dg[:, 2 * H + h * d:2 * H + (h + 1) * d], dv_o[0, :, 0]))]
+    log_report("full-size attention", rows)
+    for n, e in rows:
+        assert e <= 2e-2, (n, e)
+
+
+def test_full_shape_stage_properties(gpu_device):
+    """C3's shape with 2 layers: a repeat is bit-identical (fixed reduction orders, one atomic add per
+    element and launch), recompute changes nothing, and accumulating the same microbatch twice gives
+    exactly twice the gradient of one (fp32 x + x is exact)."""
+    cfg = get_config("C3").with_(layers=2, num_microbatches=2, shard_num=1, shard_den=1)
+    print("[case] full-shape stage properties", flush=True)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    P = cfg.n_params
+    T, H = cfg.tokens, cfg.hidden
+    params = (torch.randn(P, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    x = torch.randn(T, H, device="cuda", generator=g).to(torch.bfloat16)
+    dy = (torch.randn(T, H, device="cuda", generator=g) * 0.01).to(torch.bfloat16)
+
+    def run(recompute, n_mb):
+        c = cfg.with_(recompute=recompute)
+        cc = zs.make_config(c)
+        _, mem, _ = zs.query(cc)
+        grad = torch.zeros(P, device="cuda")
+        m, v = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+        master = params.float()
+        ws = torch.empty(mem["workspace"], dtype=torch.uint8, device="cuda")
+        stage = zs.Stage(cc, params.clone(), master, grad, m, v, ws)
+        ys, dxs = [], []
+        for i in range(n_mb):
+            y = torch.empty(T, H, dtype=torch.bfloat16, device="cuda")
+            stage.forward(i, x, y)
+            ys.append(y)
+        for i in reversed(range(n_mb)):
+            dx = torch.empty(T, H, dtype=torch.bfloat16, device="cuda")
+            stage.backward(i, dy, dx)
+            stage.accumulate(i)
+            dxs.append(dx)
+        torch.cuda.synchronize()
+        stage.close()
+        return ys, dxs, grad
+
+    y1, dx1, g1 = run(0, 1)
+    y1b, dx1b, g1b = run(0, 1)
+    assert torch.equal(y1[0], y1b[0]) and torch.equal(dx1[0], dx1b[0]) and torch.equal(g1, g1b)
+    yr, dxr, gr = run(1, 1)
+    assert torch.equal(y1[0], yr[0]) and torch.equal(dx1[0], dxr[0]) and torch.equal(g1, gr)
+    y2, dx2, g2 = run(0, 2)
+    assert torch.equal(y2[0], y1[0]) and torch.equal(y2[1], y1[0]) and torch.equal(dx2[0], dx1[0])
+    assert torch.equal(g2, 2.0 * g1)
+    assert bool(torch.isfinite(g1).all()) and float(g1.abs().max()) > 0
