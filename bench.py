@@ -27,9 +27,10 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (256 CUs x 4 SIMDs x 1024 flop/clk x 2.4 GHz)
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernels measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC = {}
+# HBM-side bytes per launch of a workload's dominant kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of `bench.py --traffic-probe`, each counter scaled by what it reads for a copy of known size
+# (profiles/gemm_wgrad_C3_hbm_traffic.txt).  Workloads that were not measured report null.
+MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn"): 888.1e6}
 
 
 def model_flops_per_step(cfg):
@@ -76,6 +77,35 @@ def cpu_baseline(cfg):
                       f"shape, fwd+bwd in fp64 numpy: {dt:.1f} s; value = tokens / (time x layers), AdamW not included"}
 
 
+def traffic_probe(cfg):
+    """For rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: launches a plain copy of known size (1 GiB read,
+    1 GiB written, torch's elementwise copy kernel) and then the weight-gradient GEMMs of one decoder
+    layer of the workload (the dominant kernel class of the step), each three times."""
+    import torch
+    import paper_2507_10392_amd as zs
+    dev = torch.device("cuda:0")
+    n = 1 << 28
+    a = torch.randn(n, device=dev)
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    T, H, F = cfg.tokens, cfg.hidden, cfg.ffn
+    st = torch.cuda.current_stream().cuda_stream
+    nup = 2 if cfg.arch == 1 else 1
+    nqkv = 3 if cfg.arch == 1 else 1
+    shapes = [("w_down", F, H, 1), ("w_up", H, F * (1 if cfg.arch == 1 else 1), nup), ("w_out", H, H, 1),
+              ("w_qkv", H, H if cfg.arch == 1 else 3 * H, nqkv)]
+    for name, M, N, batch in shapes:
+        X = torch.randn(T, M, device=dev).to(torch.bfloat16)
+        dY = (torch.randn(T, N * batch, device=dev) * 0.01).to(torch.bfloat16)
+        dW = torch.zeros(batch * M * N, device=dev)
+        for _ in range(3):
+            zs.ops.gemm(st, 1, 1, 0, M, N, T, X, M, dY, N * batch, dW, N, 1, None, None, 0, batch, 0, N, M * N, 0, 0, 0, 2)
+    torch.cuda.synchronize()
+    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": 4 * n,
+                      "gemm_shapes": [(nm, M, N, T, bt) for nm, M, N, bt in shapes]}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,6 +114,8 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket launches with HIP events")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="launch a 1 GiB copy and the workload's weight-gradient GEMMs only (for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the stage step on ONE GPU only (no collectives, no sharding across GPUs); "
@@ -100,6 +132,9 @@ def main():
     cfg = get_config(args.workload)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.traffic_probe:
+        traffic_probe(cfg)
+        return
     torch.manual_seed(cfg.seed)
     cc = zs.make_config(cfg)
     P, mem, _ = zs.query(cc)
