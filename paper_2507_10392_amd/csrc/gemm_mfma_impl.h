@@ -225,9 +225,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (g.K + BK - 1) / BK;
-  // One register stage: slab kt+1 is loaded into registers while slab kt is multiplied out of LDS.
-  Frag<BM, NT> fa0;
-  Frag<BN, NT> fb0;
+  // Two register stages.  While slab kt is multiplied out of one LDS buffer, slab kt+1 (loaded during the
+  // previous iteration) is written into the other buffer BETWEEN the MFMA steps, and the loads of slab
+  // kt+2 are in flight.  The LDS writes thereby overlap MFMAs instead of forming a phase of their own in
+  // which every wave of the workgroup writes and the matrix cores idle.
+  Frag<BM, NT> fa0, fa1;
+  Frag<BN, NT> fb0, fb1;
   const int lda = (int)g.lda, ldb = (int)g.ldb;
   const __amdgpu_buffer_rsrc_t rsA =
       make_rsrc(A, (uint32_t)(TA == 0 ? ((int64_t)(g.M - 1) * lda + g.K) : ((int64_t)(g.K - 1) * lda + g.M)) * 2u);
@@ -253,13 +256,17 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, n0, g.N, k0, tid);
     }
   };
-  auto stash = [&](int buf, const Frag<BM, NT>& fa0, const Frag<BN, NT>& fb0) {
+  auto stash_a = [&](int buf, const Frag<BM, NT>& fa) {
     bf16* As = smem + buf * (SLAB_A + SLAB_B);
-    bf16* Bs = As + SLAB_A;
-    if (TA == 0) store_kmajor<BM, NT>(fa0, As, tid); else store_rmajor<BM, NT>(fa0, As, tid);
-    if (TB == 1) store_kmajor<BN, NT>(fb0, Bs, tid); else store_rmajor<BN, NT>(fb0, Bs, tid);
+    if (TA == 0) store_kmajor<BM, NT>(fa, As, tid); else store_rmajor<BM, NT>(fa, As, tid);
   };
-  auto multiply = [&](int buf) {
+  auto stash_b = [&](int buf, const Frag<BN, NT>& fb) {
+    bf16* Bs = smem + buf * (SLAB_A + SLAB_B) + SLAB_A;
+    if (TB == 1) store_kmajor<BN, NT>(fb, Bs, tid); else store_rmajor<BN, NT>(fb, Bs, tid);
+  };
+  // multiplies the slab in LDS buffer `buf`; after the first and second of the four MFMA steps it writes
+  // the A and B parts of the next slab (held in fa, fb) into the other buffer, which nobody reads now
+  auto multiply = [&](int buf, const Frag<BM, NT>& fa, const Frag<BN, NT>& fb) {
     const bf16* As = smem + buf * (SLAB_A + SLAB_B);
     const bf16* Bs = As + SLAB_A;
 #pragma unroll
@@ -277,19 +284,24 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = ACC ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0)
                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+      if (ks == 0) stash_a(buf ^ 1, fa);
+      if (ks == 1) stash_b(buf ^ 1, fb);
     }
   };
 
-  // The fetch past the last slab is issued unconditionally: its offsets lie beyond num_records (or are
-  // masked), so it reads zeros, touches no memory, and lands in a buffer nobody multiplies.
+  // Slabs past K read zeros (masked or beyond num_records), so the loop needs no conditions: it walks K in
+  // pairs of slabs and a surplus slab contributes nothing.
   fetch(0, fa0, fb0);
-  stash(0, fa0, fb0);
+  stash_a(0, fa0);
+  stash_b(0, fb0);
+  fetch(1, fa1, fb1);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    fetch(kt + 1, fa0, fb0);                             // global loads in flight during the MFMAs below
-    multiply(buf);
-    stash(buf ^ 1, fa0, fb0);                            // the other buffer was last read before the previous barrier
+  for (int kt = 0; kt < nk; kt += 2) {
+    fetch(kt + 2, fa0, fb0);
+    multiply(0, fa1, fb1);
+    __syncthreads();
+    fetch(kt + 3, fa1, fb1);
+    multiply(1, fa0, fb0);
     __syncthreads();
   }
 
