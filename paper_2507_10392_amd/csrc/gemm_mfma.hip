@@ -26,11 +26,16 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
   if (g.kseg) {
     if (!g.transB || g.kseg % 8 || g.segB % 8 || g.K % g.kseg) return false;
   }
-  // the bf16 epilogue moves 4 consecutive columns per 8-byte access
+  // the bf16 epilogue moves 8 consecutive columns per 16-byte access
   if (!g.c_f32_accum) {
-    if (((uintptr_t)g.C & 7) || g.ldc % 4 || g.sC % 4) return false;
-    if (g.resid && (((uintptr_t)g.resid & 7) || g.ldr % 4)) return false;
-    if (g.bias && (((uintptr_t)g.bias & 7) || g.sBias % 4)) return false;
+    if (!aligned16(g.C) || g.ldc % 8 || g.sC % 8) return false;
+    if (g.resid && (!aligned16(g.resid) || g.ldr % 8)) return false;
+    if (g.bias && (!aligned16(g.bias) || g.sBias % 8)) return false;
+  } else {
+    // the accumulating epilogue updates 4 consecutive floats per 16-byte access through 32-bit byte offsets
+    if (!aligned16(g.C) || g.ldc % 4 || g.sC % 4 || g.N % 4) return false;
+    if (g.bias || g.resid) return false;
+    if (((int64_t)g.M + 256) * g.ldc * 4 >= (1ll << 31)) return false;
   }
   // byte offsets inside one operand are 32-bit in the kernel
   const int64_t extA = (g.transA ? (int64_t)g.K * g.lda : (int64_t)g.M * g.lda) * 2;

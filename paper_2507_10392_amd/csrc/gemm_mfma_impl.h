@@ -113,82 +113,118 @@ __device__ __forceinline__ void tile_origin(int pid, int tiles_m, int tiles_n, i
   n0 = ((pid % width) / gsz) * BN;
 }
 
-// Epilogue for float accumulation (weight gradients).  The MFMAs were issued as mfma(A fragment, B fragment):
-// acc[i][j][r] is C[row, col] with row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32 inside block (i, j), so the
-// 32 lanes of a half-wave hit 128 consecutive bytes of one row with each atomic.
-template <int MI, int NJ>
-__device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wm, int wn,
-                                               int lane) {
-  const bf16* bias = g.bias ? (const bf16*)g.bias + (int64_t)z * g.sBias : nullptr;
-  const bf16* R = g.resid ? (const bf16*)g.resid + (int64_t)z * g.sC : nullptr;
-  float* Cz = (float*)g.C + (int64_t)z * g.sC;
+// Both epilogues pass the tile through LDS (free after the K loop) as fp32, in two halves of BM/2 rows.
+// The MFMAs were issued with the operands swapped, mfma(B fragment, A fragment), which yields the
+// transposed block: acc[i][j][r] is C[row, col] with row = lane%32 and col = 8*(r/4) + 4*(lane/32) + r%4,
+// so a lane owns 4 consecutive columns per register quad and writes it as one float4.
+template <int BN> struct Staging { static constexpr int LDW = BN + 4; };   // padded row (floats)
+
+template <int BN, int MI, int NJ>
+__device__ __forceinline__ void stage_quads(float* stage, f32x16 (&acc)[MI][NJ], int wn, int lane) {
+  constexpr int LDW = Staging<BN>::LDW;
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int col = n0 + wn + j * 32 + (lane & 31);
-    if (col >= g.N) continue;
-    const float bv = bias ? (float)bias[col] : 0.f;
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row >= g.M) continue;
-        float v = acc[i][j][r] + bv;
-        if (R) v += (float)R[(int64_t)row * g.ldr + col];
-        // Hardware float add at L2 without a return value: the wave does not wait for the old value.
-        // Every element receives exactly one add per launch and launches are ordered by the stream,
-        // so the sum over microbatches is formed in a fixed order.
-        unsafeAtomicAdd(Cz + (int64_t)row * g.ldc + col, v);
+      for (int c = 0; c < 4; ++c) {
+        f32x4 q;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) q[e] = acc[i][j][4 * c + e];
+        *reinterpret_cast<f32x4*>(stage + (i * 32 + (lane & 31)) * LDW + wn + j * 32 + 8 * c + 4 * (lane >> 5)) = q;
       }
+}
+
+// Epilogue for C (fp32) += product (no bias, no residual).  After staging, ALL threads walk the half tile
+// 4 columns at a time: the old values of C are loaded 16 bytes per lane (consecutive lanes, consecutive
+// pieces of a row), all loads of a half in flight across the barrier, then sum and store.  Loads and
+// stores go through a buffer descriptor over C: rows past M fall beyond num_records and columns past N
+// are sent there, so the ragged edge needs no branches.  A tile belongs to one workgroup and launches
+// are ordered by the stream, so the sum over microbatches is formed in a fixed order.
+template <int BM, int BN, int NT, int MI, int NJ>
+__device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
+                                               int wn, int tid, float* stage) {
+  constexpr int LDW = Staging<BN>::LDW;
+  static_assert((BM / 2) * LDW * 4 <= 2 * (BM + BN) * LDK * 2, "staging tile must fit the K-loop buffers");
+  constexpr int VPR = BN / 4;                              // float4 per row
+  constexpr int NV = (BM / 2) * VPR / NT;                  // float4 per thread and half
+  float* Cz = (float*)g.C + (int64_t)z * g.sC;
+  const int ldc = (int)g.ldc;
+  const __amdgpu_buffer_rsrc_t rsC = make_rsrc(Cz, (uint32_t)((int64_t)(g.M - 1) * ldc + g.N) * 4u);
+  const int lr0 = tid / VPR, cv = tid % VPR;               // vector v = tid + NT*it: row lr0 + (NT/VPR)*it, same columns
+  const bool col_ok = n0 + cv * 4 < g.N;                   // N is a multiple of 4
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    __syncthreads();
+    if (wave_m == half) stage_quads<BN, MI, NJ>(stage, acc, wn, tid & 63);
+    u32x4 old[NV];
+    uint32_t off[NV];
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int row = m0 + half * (BM / 2) + lr0 + (NT / VPR) * it;
+      off[it] = col_ok ? (uint32_t)(row * ldc + n0 + cv * 4) * 4u : 0x80000000u;
+      old[it] = __builtin_amdgcn_raw_buffer_load_b128(rsC, (int)off[it], 0, 0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const f32x4 x = *reinterpret_cast<const f32x4*>(stage + (lr0 + (NT / VPR) * it) * LDW + cv * 4);
+      union { u32x4 u; f32x4 f; } o;
+      o.u = old[it];
+      o.f += x;
+      __builtin_amdgcn_raw_buffer_store_b128(o.u, rsC, (int)off[it], 0, 0);
     }
   }
 }
 
-// Epilogue for bf16 output.  The MFMAs were issued with the operands swapped, mfma(B fragment, A fragment),
-// which yields the transposed block: acc[i][j][r] is C[row, col] with row = lane%32 and
-// col = 8*(r/4) + 4*(lane/32) + r%4.  A lane then owns 4 consecutive columns per register quad and
-// stores them (and reads the residual) as one 8-byte access.
-template <int MI, int NJ>
-__device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wm, int wn,
-                                               int lane) {
+// Epilogue for bf16 output: after staging, ALL threads read rows back 8 columns at a time, add bias and
+// residual in fp32, round once to bf16 and store 16 bytes per lane, consecutive lanes covering
+// consecutive 16-byte pieces of a row of C.
+template <int BM, int BN, int NT, int MI, int NJ>
+__device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
+                                               int wn, int tid, float* stage) {
+  constexpr int LDW = Staging<BN>::LDW;
+  static_assert((BM / 2) * LDW * 4 <= 2 * (BM + BN) * LDK * 2, "staging tile must fit the K-loop buffers");
+  const int lane = tid & 63;
   const bf16* bias = g.bias ? (const bf16*)g.bias + (int64_t)z * g.sBias : nullptr;
   const bf16* R = g.resid ? (const bf16*)g.resid + (int64_t)z * g.sC : nullptr;
   bf16* Cz = (bf16*)g.C + (int64_t)z * g.sC;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int row = m0 + wm + i * 32 + (lane & 31);
-    if (row >= g.M) continue;
+  for (int half = 0; half < 2; ++half) {
+    __syncthreads();                                       // K-loop reads / previous half's reads are done
+    if (wave_m == half) stage_quads<BN, MI, NJ>(stage, acc, wn, lane);
+    __syncthreads();
+    constexpr int VPR = BN / 8;                            // 16-byte output vectors per row
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
+    for (int it = 0; it < (BM / 2) * VPR / NT; ++it) {
+      const int v = tid + NT * it;
+      const int lr = v / VPR, col = n0 + (v % VPR) * 8;
+      const int row = m0 + half * (BM / 2) + lr;
+      if (row >= g.M || col >= g.N) continue;
+      const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + (v % VPR) * 8);
+      const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + (v % VPR) * 8 + 4);
+      float x[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+      if (col + 8 <= g.N) {
+        if (bias) {
+          const bf16x8 bb = *reinterpret_cast<const bf16x8*>(bias + col);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int col = n0 + wn + j * 32 + 8 * c + 4 * (lane >> 5);
-        if (col >= g.N) continue;
-        float v[4];
+          for (int e = 0; e < 8; ++e) x[e] += (float)bb[e];
+        }
+        if (R) {
+          const bf16x8 rr = *reinterpret_cast<const bf16x8*>(R + (int64_t)row * g.ldr + col);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * c + e];
-        if (col + 4 <= g.N) {
-          if (bias) {
-            const bf16x4 bb = *reinterpret_cast<const bf16x4*>(bias + col);
+          for (int e = 0; e < 8; ++e) x[e] += (float)rr[e];
+        }
+        bf16x8 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)bb[e];
-          }
-          if (R) {
-            const bf16x4 rr = *reinterpret_cast<const bf16x4*>(R + (int64_t)row * g.ldr + col);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)rr[e];
-          }
-          bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-          *reinterpret_cast<bf16x4*>(Cz + (int64_t)row * g.ldc + col) = o;
-        } else {
-          for (int e = 0; e < 4 && col + e < g.N; ++e) {
-            float x = v[e];
-            if (bias) x += (float)bias[col + e];
-            if (R) x += (float)R[(int64_t)row * g.ldr + col + e];
-            Cz[(int64_t)row * g.ldc + col + e] = (bf16)x;
-          }
+        for (int e = 0; e < 8; ++e) o[e] = (bf16)x[e];
+        *reinterpret_cast<bf16x8*>(Cz + (int64_t)row * g.ldc + col) = o;
+      } else {
+        for (int e = 0; e < 8 && col + e < g.N; ++e) {
+          float y = x[e];
+          if (bias) y += (float)bias[col + e];
+          if (R) y += (float)R[(int64_t)row * g.ldr + col + e];
+          Cz[(int64_t)row * g.ldc + col + e] = (bf16)y;
         }
       }
     }
@@ -282,8 +318,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          acc[i][j] = ACC ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0)
-                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
       if (ks == 0) stash_a(buf ^ 1, fa);
       if (ks == 1) stash_b(buf ^ 1, fb);
     }
@@ -305,8 +340,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     __syncthreads();
   }
 
-  if (ACC) epilogue_accum<MI, NJ>(g, z, acc, m0, n0, wm, wn, lane);
-  else epilogue_store<MI, NJ>(g, z, acc, m0, n0, wm, wn, lane);
+  if (ACC) epilogue_accum<BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
+  else epilogue_store<BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
 }
 
 template <int BM, int BN, int NW, int TA, int TB, int SEG, int ACC> hipError_t launch2(hipStream_t st, const Gemm& g) {
