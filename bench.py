@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM-side bytes per launch of a workload's dominant kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --traffic-probe`, each counter scaled by what it reads for a copy of known size
 # (profiles/gemm_wgrad_C3_hbm_traffic.txt).  Workloads that were not measured report null.
-MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn"): 888.1e6}
+MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn"): 1092.8e6}
 
 
 def model_flops_per_step(cfg):

@@ -98,16 +98,28 @@ __device__ __forceinline__ void load_row_frags(bf16x8 (&f)[8], const bf16* __res
 // Row index (inside a 32-row MFMA block) held by accumulator register r of this lane.
 __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
+// Causal blocks differ in work by up to the number of tiles, so the launch order matters: workgroups are
+// dispatched in increasing linear id, and id -> (rank, head) with the rank (0 = most work) in the slow
+// position puts the heavy blocks of ALL heads first and leaves light blocks for the tail.  Consecutive
+// ids go to different XCDs round-robin; with nh*mb a multiple of 8 a head keeps its XCD, whose L2 then
+// holds the K/V (or Q/dO) rows its blocks stream.
+struct BlockId { int rank, h, b; };
+__device__ __forceinline__ BlockId block_id(int nh, int mb) {
+  const int nhb = nh * mb, id = blockIdx.x, hb = id % nhb;
+  return BlockId{id / nhb, hb % nh, hb / nh};
+}
+
 // ------------------------------------------------------------------------------------------ forward
-// grid (ceil(S/128), nh, mb); wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
+// grid ceil(S/128)*nh*mb; wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                        const bf16* __restrict__ v, int64_t ld, bf16* __restrict__ o,
-                                                       int64_t ldo, float* __restrict__ lse, float scale_log2) {
+                                                       int64_t ldo, float* __restrict__ lse, float scale_log2, int nh,
+                                                       int mb) {
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);            // [2][K tile | V tile]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int qb = gridDim.x - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
+  const BlockId bid = block_id(nh, mb);
+  const int qb = (S + 127) / 128 - 1 - bid.rank, h = bid.h, b = bid.b;
   const int64_t tok0 = (int64_t)b * S;
   const bf16* qh = q + tok0 * ld + h * D;
   const bf16* kh = k + tok0 * ld + h * D;
@@ -238,18 +250,19 @@ __global__ __launch_bounds__(256) void attn_delta_mfma_kernel(int S, const bf16*
 }
 
 // ------------------------------------------------------------------------------------------ dQ
-// grid (ceil(S/128), nh, mb); wave w owns queries q0+32w..; loops over K/V tiles up to the diagonal.
+// grid ceil(S/128)*nh*mb; wave w owns queries q0+32w..; loops over K/V tiles up to the diagonal.
 // dQ^T[d][q] += K^T[d][key] dS^T[key][q],  dS^T = P^T o (dP^T - delta_q),  dP^T = V dO^T.
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                           const bf16* __restrict__ v, int64_t ld,
                                                           const bf16* __restrict__ dout, int64_t ldo,
                                                           const float* __restrict__ lse, const float* __restrict__ delta,
-                                                          bf16* __restrict__ dq, int64_t ldd, float scale) {
+                                                          bf16* __restrict__ dq, int64_t ldd, float scale, int nh,
+                                                          int mb) {
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int qb = gridDim.x - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
+  const BlockId bid = block_id(nh, mb);
+  const int qb = (S + 127) / 128 - 1 - bid.rank, h = bid.h, b = bid.b;
   const int64_t tok0 = (int64_t)b * S;
   const bf16* qh = q + tok0 * ld + h * D;
   const bf16* kh = k + tok0 * ld + h * D;
@@ -337,7 +350,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-// grid (ceil(S/(32 NW)), nh, mb), NW waves; wave w owns keys k0+32w..; loops over Q/dO tiles from the diagonal to the
+// grid ceil(S/(32 NW))*nh*mb, NW waves; wave w owns keys k0+32w..; loops over Q/dO tiles from the diagonal to the
 // end.  With 8 waves the staged Q/dO tiles serve 256 keys and two waves share each SIMD, so one wave's
 // softmax arithmetic overlaps the other's MFMAs.
 // S[q][key] = Q K^T (lane = key, registers = queries), P = exp2(S c - lse_q), dP = dO V^T,
@@ -348,13 +361,13 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
                                                            const bf16* __restrict__ dout, int64_t ldo,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16* __restrict__ dk, bf16* __restrict__ dv, int64_t ldd,
-                                                           float scale) {
+                                                           float scale, int nh, int mb) {
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);                 // [2][Q tile | dO tile]
   float* stats = reinterpret_cast<float*>(smem + 4 * TILE);       // [2][lse2[64] | delta[64]]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int kb = blockIdx.x;                                      // early key blocks (most work) first
-  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
+  const BlockId bid = block_id(nh, mb);
+  const int kb = bid.rank, h = bid.h, b = bid.b;                   // early key blocks (most work) first
   const int64_t tok0 = (int64_t)b * S;
   const bf16* qh = q + tok0 * ld + h * D;
   const bf16* kh = k + tok0 * ld + h * D;
@@ -482,9 +495,9 @@ hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
   static bool cfg = false;
   hipError_t e = set_smem(attn_fwd_kernel, SMEM_FWD, cfg);
   if (e != hipSuccess) return e;
-  dim3 grid((unsigned)cdiv(S, 128), (unsigned)nh, (unsigned)mb), blk(256);
+  dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
   hipLaunchKernelGGL(attn_fwd_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                     (bf16*)o, ldo, lse, LOG2E / sqrtf((float)d));
+                     (bf16*)o, ldo, lse, LOG2E / sqrtf((float)d), nh, mb);
   return hipGetLastError();
 }
 
@@ -497,19 +510,19 @@ hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
   if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<8>, SMEM_DKV, cfg3);
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)d);
-  dim3 grid((unsigned)cdiv(S, 128), (unsigned)nh, (unsigned)mb), blk(256);
+  dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
   hipLaunchKernelGGL(attn_delta_mfma_kernel, dim3((unsigned)cdiv(S, 4), (unsigned)nh, (unsigned)mb), blk, 0, st, S,
                      (const bf16*)o, (const bf16*)dout, ldo, delta);
   hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                     (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale);
+                     (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale, nh, mb);
   // 256 keys per workgroup when that still gives every CU a workgroup, else 128
   if (cdiv(S, 256) * nh * mb >= 256) {
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)cdiv(S, 256), (unsigned)nh, (unsigned)mb), dim3(512), SMEM_DKV, st,
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), SMEM_DKV, st,
                        S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld, (const bf16*)dout, ldo, lse, delta, (bf16*)dk,
-                       (bf16*)dv, ldd, scale);
+                       (bf16*)dv, ldd, scale, nh, mb);
   } else {
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<4>, grid, blk, SMEM_DKV, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                       (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale);
+                       (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale, nh, mb);
   }
   return hipGetLastError();
 }
