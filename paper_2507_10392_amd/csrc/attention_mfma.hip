@@ -65,16 +65,23 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int s) {
 
 // A 64 x 128 tile moves HBM -> registers (fetch, issued before the MFMAs of the current tile so the
 // latency hides behind them) -> LDS (put, after them).  Thread t carries 4 vectors of 16 bytes:
-// vector v = t + 256 i is row v/16, columns 8*(v%16)...  Rows >= nrows read as zero.
+// vector v = t + 256 i is row v/16, columns 8*(v%16)...
 template <int NT> struct TileRegs { bf16x8 v[1024 / NT]; };   // NT threads share the 1024 vectors of a tile
+// Rows of one (batch, head) are read through a raw buffer descriptor over [first row, last row's 128 columns]:
+// the per-lane offset is one register, the tile's row offset a scalar, and rows at or past nrows fall
+// beyond num_records and read as zero without a branch.  Offsets are 32-bit: nrows * ld * 2 < 2^31.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const bf16* base, int64_t ld, int nrows) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, (int)((((int64_t)nrows - 1) * ld + D) * 2), 0x00020000);
+}
 template <int NT>
-__device__ __forceinline__ void fetch_tile(TileRegs<NT>& x, const bf16* __restrict__ src, int64_t ld, int row0, int nrows,
-                                           int tid) {
+__device__ __forceinline__ void fetch_tile(TileRegs<NT>& x, __amdgpu_buffer_rsrc_t rs, int ld, int row0, int tid) {
+  const int voff = ((tid >> 4) * ld + (tid & 15) * 8) * 2;
 #pragma unroll
   for (int i = 0; i < 1024 / NT; ++i) {
-    const int v = tid + NT * i;
-    const int r = v >> 4, c = (v & 15) * 8;
-    x.v[i] = (row0 + r < nrows) ? *reinterpret_cast<const bf16x8*>(src + (int64_t)(row0 + r) * ld + c) : zero8();
+    union { u32x4 u; bf16x8 h; } c;
+    c.u = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, (row0 + (NT / 16) * i) * ld * 2, 0);
+    x.v[i] = c.h;
   }
 }
 template <int NT> __device__ __forceinline__ void put_tile(const TileRegs<NT>& x, bf16* tile, int tid) {
@@ -124,6 +131,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
   const bf16* qh = q + tok0 * ld + h * D;
   const bf16* kh = k + tok0 * ld + h * D;
   const bf16* vh = v + tok0 * ld + h * D;
+  const __amdgpu_buffer_rsrc_t rsk = head_rsrc(kh, ld, S), rsv = head_rsrc(vh, ld, S);
   const int q0 = qb * 128, wq0 = q0 + wave * 32;
   const int my_q = wq0 + (lane & 31);
 
@@ -139,8 +147,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
   const int last_q = min(q0 + 127, S - 1);
   const int ntiles = last_q / TR + 1;
   TileRegs<256> kr, vr;
-  fetch_tile(kr, kh, ld, 0, S, tid);
-  fetch_tile(vr, vh, ld, 0, S, tid);
+  fetch_tile(kr, rsk, (int)ld, 0, tid);
+  fetch_tile(vr, rsv, (int)ld, 0, tid);
   put_tile(kr, smem, tid);
   put_tile(vr, smem + TILE, tid);
   __syncthreads();
@@ -148,8 +156,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
     const bf16* Kt = smem + (t & 1) * 2 * TILE;
     const bf16* Vt = Kt + TILE;
     if (t + 1 < ntiles) {
-      fetch_tile(kr, kh, ld, (t + 1) * TR, S, tid);
-      fetch_tile(vr, vh, ld, (t + 1) * TR, S, tid);
+      fetch_tile(kr, rsk, (int)ld, (t + 1) * TR, tid);
+      fetch_tile(vr, rsv, (int)ld, (t + 1) * TR, tid);
     }
     const int key0 = t * TR;
     if (key0 <= wq0 + 31) {   // otherwise every key of the tile is in this wave's future
@@ -268,6 +276,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
   const bf16* kh = k + tok0 * ld + h * D;
   const bf16* vh = v + tok0 * ld + h * D;
   const bf16* doh = dout + tok0 * ldo + h * D;
+  const __amdgpu_buffer_rsrc_t rsk = head_rsrc(kh, ld, S), rsv = head_rsrc(vh, ld, S);
   const int q0 = qb * 128, wq0 = q0 + wave * 32;
   const int my_q = wq0 + (lane & 31);
   const float scale_log2 = scale * LOG2E;
@@ -287,8 +296,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
   const int last_q = min(q0 + 127, S - 1);
   const int ntiles = last_q / TR + 1;
   TileRegs<256> kr, vr;
-  fetch_tile(kr, kh, ld, 0, S, tid);
-  fetch_tile(vr, vh, ld, 0, S, tid);
+  fetch_tile(kr, rsk, (int)ld, 0, tid);
+  fetch_tile(vr, rsv, (int)ld, 0, tid);
   put_tile(kr, smem, tid);
   put_tile(vr, smem + TILE, tid);
   __syncthreads();
@@ -296,8 +305,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
     const bf16* Kt = smem + (t & 1) * 2 * TILE;
     const bf16* Vt = Kt + TILE;
     if (t + 1 < ntiles) {
-      fetch_tile(kr, kh, ld, (t + 1) * TR, S, tid);
-      fetch_tile(vr, vh, ld, (t + 1) * TR, S, tid);
+      fetch_tile(kr, rsk, (int)ld, (t + 1) * TR, tid);
+      fetch_tile(vr, rsv, (int)ld, (t + 1) * TR, tid);
     }
     const int key0 = t * TR;
     if (key0 <= wq0 + 31) {
@@ -373,15 +382,25 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
   const bf16* kh = k + tok0 * ld + h * D;
   const bf16* vh = v + tok0 * ld + h * D;
   const bf16* doh = dout + tok0 * ldo + h * D;
+  const __amdgpu_buffer_rsrc_t rsq = head_rsrc(qh, ld, S), rsdo = head_rsrc(doh, ldo, S);
   const float* lse_h = lse + ((int64_t)b * nh + h) * S;
   const float* dlt_h = delta + ((int64_t)b * nh + h) * S;
   const int k0 = kb * 32 * NW, wk0 = k0 + wave * 32;
   const int my_k = wk0 + (lane & 31);
   const float scale_log2 = scale * LOG2E;
 
-  bf16x8 kf[8], vf[8];
+  // K fragments stay in registers; the wave's 32 rows of V go to a private LDS block instead and are
+  // read back as B operands (same fragment pattern as the A operands), which keeps the kernel within
+  // the register budget of two waves per SIMD.
+  bf16x8 kf[8];
   load_row_frags(kf, kh, ld, wk0, S, lane);
-  load_row_frags(vf, vh, ld, wk0, S, lane);
+  bf16* Vw = reinterpret_cast<bf16*>(stats + 256) + wave * 32 * LDT;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int vv = lane + 64 * i, r = vv >> 4, c = (vv & 15) * 8;
+    *reinterpret_cast<bf16x8*>(Vw + r * LDT + c) =
+        wk0 + r < S ? *reinterpret_cast<const bf16x8*>(vh + (int64_t)(wk0 + r) * ld + c) : zero8();
+  }
   f32x16 dkacc[4], dvacc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -391,8 +410,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
   TileRegs<64 * NW> qr, dor;
   float statr = 0.f;
   auto fetch = [&](int t) {
-    fetch_tile(qr, qh, ld, t * TR, S, tid);
-    fetch_tile(dor, doh, ldo, t * TR, S, tid);
+    fetch_tile(qr, rsq, (int)ld, t * TR, tid);
+    fetch_tile(dor, rsdo, (int)ldo, t * TR, tid);
     if (tid < 128) {
       const int r = t * TR + (tid & 63);
       statr = 0.f;
@@ -425,7 +444,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
           sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Qt, ib * 32, 16 * s, lane), kf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(dOt, ib * 32, 16 * s, lane), vf[s], pacc, 0, 0, 0);
+          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(dOt, ib * 32, 16 * s, lane), lds_frag(Vw, 0, 16 * s, lane), pacc,
+                                                         0, 0, 0);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -477,7 +497,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
 }
 
 constexpr size_t SMEM_FWD = 4 * TILE * sizeof(bf16);                    // 73728
-constexpr size_t SMEM_DKV = 4 * TILE * sizeof(bf16) + 256 * sizeof(float);
+constexpr size_t smem_dkv(int nw) { return 4 * TILE * sizeof(bf16) + 256 * sizeof(float) + (size_t)nw * 32 * LDT * sizeof(bf16); }
 
 template <typename K> hipError_t set_smem(K kern, size_t bytes, bool& done) {
   if (done) return hipSuccess;
@@ -492,6 +512,7 @@ bool attn_mfma_supported(DType dt, int S, int d) { return dt == BF16 && d == D &
 
 hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, void* o, int64_t ldo, float* lse) {
+  if ((int64_t)S * ld * 2 >= (1ll << 31)) return hipErrorInvalidValue;      // 32-bit buffer offsets
   static bool cfg = false;
   hipError_t e = set_smem(attn_fwd_kernel, SMEM_FWD, cfg);
   if (e != hipSuccess) return e;
@@ -504,10 +525,11 @@ hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
 hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
                          void* dq, void* dk, void* dv, int64_t ldd) {
+  if ((int64_t)S * (ld > ldo ? ld : ldo) * 2 >= (1ll << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets
   static bool cfg1 = false, cfg2 = false, cfg3 = false;
   hipError_t e = set_smem(attn_bwd_dq_kernel, SMEM_FWD, cfg1);
-  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<4>, SMEM_DKV, cfg2);
-  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<8>, SMEM_DKV, cfg3);
+  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<4>, smem_dkv(4), cfg2);
+  if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<8>, smem_dkv(8), cfg3);
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)d);
   dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
@@ -517,11 +539,11 @@ hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
                      (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale, nh, mb);
   // 256 keys per workgroup when that still gives every CU a workgroup, else 128
   if (cdiv(S, 256) * nh * mb >= 256) {
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), SMEM_DKV, st,
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), smem_dkv(8), st,
                        S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld, (const bf16*)dout, ldo, lse, delta, (bf16*)dk,
                        (bf16*)dv, ldd, scale, nh, mb);
   } else {
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<4>, grid, blk, SMEM_DKV, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<4>, grid, blk, smem_dkv(4), st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
                        (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale, nh, mb);
   }
   return hipGetLastError();
