@@ -135,45 +135,69 @@ hipError_t norm_bwd(hipStream_t st, DType dt, int kind, int T, int H, const void
 }
 
 // ------------------------------------------------------------------ column partial sums
-// grid (column chunks of 256*V, nblk); each thread owns V columns and walks its row block.
+// grid (column chunks of 64*V, nblk).  A workgroup is 64 column threads (V columns each) x 4 row groups:
+// row group q walks rows r0+q, r0+q+4, ... of the block, four rows in flight per thread, and the four
+// groups' sums are added in the order 0..3 through LDS, so the result does not depend on timing.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(int Trows, int N, const T* __restrict__ a, int64_t lda,
                                                      const T* __restrict__ x, int64_t ldx,
                                                      const float* __restrict__ rstd, const float* __restrict__ mean,
                                                      float* __restrict__ part, int rows_per_blk) {
   constexpr int V = Vec<T>::N;
-  const int col = (blockIdx.x * 256 + threadIdx.x) * V;
-  if (col >= N) return;
+  __shared__ float red[3][64][V];
+  const int ct = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int col = (blockIdx.x * 64 + ct) * V;
+  const bool live = col < N;
   const int r0 = blockIdx.y * rows_per_blk;
   const int r1 = min(Trows, r0 + rows_per_blk);
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
-  for (int t = r0; t < r1; ++t) {
-    float av[V];
-    load_vec(a + (int64_t)t * lda + col, av);
-    if (x) {
-      float xv[V];
-      load_vec(x + (int64_t)t * ldx + col, xv);
-      const float r = rstd[t];
-      const float mu = mean ? mean[t] : 0.f;
+  if (live) {
+    for (int t0 = r0 + q; t0 < r1; t0 += 16) {
+      float av[4][V], xv[4][V];
 #pragma unroll
-      for (int i = 0; i < V; ++i) acc[i] += av[i] * ((xv[i] - mu) * r);
-    } else {
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + 4 * u;
+        if (t < r1) {
+          load_vec(a + (int64_t)t * lda + col, av[u]);
+          if (x) load_vec(x + (int64_t)t * ldx + col, xv[u]);
+        }
+      }
 #pragma unroll
-      for (int i = 0; i < V; ++i) acc[i] += av[i];
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + 4 * u;
+        if (t < r1) {
+          if (x) {
+            const float r = rstd[t];
+            const float mu = mean ? mean[t] : 0.f;
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] += av[u][i] * ((xv[u][i] - mu) * r);
+          } else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] += av[u][i];
+          }
+        }
+      }
     }
   }
-  float* p = part + (int64_t)blockIdx.y * N + col;
+  if (q > 0) {
 #pragma unroll
-  for (int i = 0; i < V; ++i) p[i] = acc[i];
+    for (int i = 0; i < V; ++i) red[q - 1][ct][i] = acc[i];
+  }
+  __syncthreads();
+  if (q == 0 && live) {
+    float* p = part + (int64_t)blockIdx.y * N + col;
+#pragma unroll
+    for (int i = 0; i < V; ++i) p[i] = ((acc[i] + red[0][ct][i]) + red[1][ct][i]) + red[2][ct][i];
+  }
 }
 
 hipError_t colsum_partial(hipStream_t st, DType dt, int T, int N, const void* a, int64_t lda, const void* x,
                           int64_t ldx, const float* rstd, const float* mean, float* part, int nblk) {
   const int rows_per_blk = (int)cdiv(T, nblk);
   const int V = dt == F32 ? 4 : 8;
-  dim3 grid((unsigned)cdiv(N, 256 * V), (unsigned)nblk), blk(256);
+  dim3 grid((unsigned)cdiv(N, 64 * V), (unsigned)nblk), blk(256);
   if (dt == F32)
     hipLaunchKernelGGL(colsum_kernel<float>, grid, blk, 0, st, T, N, (const float*)a, lda, (const float*)x, ldx, rstd, mean, part, rows_per_blk);
   else
