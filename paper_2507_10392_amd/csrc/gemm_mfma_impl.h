@@ -53,10 +53,13 @@ __device__ __forceinline__ void load_kmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc
     f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((row0 + (NT / 8) * i) * ld + k0) * 2, 0);
   if (k0 + BK > K && k0 + (tid & 7) * 8 >= K) zero_frag(f);     // ragged last slab
 }
-template <int R, int NT> __device__ __forceinline__ void store_kmajor(const Frag<R, NT>& f, bf16* lds, int tid) {
+// Stores vectors [i0, i1) of the thread's share.
+template <int R, int NT>
+__device__ __forceinline__ void store_kmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
   bf16* p = lds + (tid >> 3) * LDK + (tid & 7) * 8;
 #pragma unroll
-  for (int i = 0; i < R * 8 / NT; ++i) *reinterpret_cast<u32x4*>(p + (NT / 8) * i * LDK) = f.v[i];
+  for (int i = 0; i < R * 8 / NT; ++i)
+    if (i >= i0 && i < i1) *reinterpret_cast<u32x4*>(p + (NT / 8) * i * LDK) = f.v[i];
 }
 
 // Operand stored [K, rows] (row index contiguous).  A k-line of the slab is R/8 vectors; thread t carries
@@ -73,11 +76,13 @@ __device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc
     f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((k0 + KSTEP * i) * ld + row0) * 2, 0);
   if (row0 + R > nrows && row0 + (tid % (R / 8)) * 8 >= nrows) zero_frag(f);   // ragged edge tile
 }
-template <int R, int NT> __device__ __forceinline__ void store_rmajor(const Frag<R, NT>& f, bf16* lds, int tid) {
+template <int R, int NT>
+__device__ __forceinline__ void store_rmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
   constexpr int KSTEP = NT / (R / 8), LDR = R + 16;
   bf16* p = lds + (tid / (R / 8)) * LDR + (tid % (R / 8)) * 8;
 #pragma unroll
-  for (int i = 0; i < R * 8 / NT; ++i) *reinterpret_cast<u32x4*>(p + KSTEP * i * LDR) = f.v[i];
+  for (int i = 0; i < R * 8 / NT; ++i)
+    if (i >= i0 && i < i1) *reinterpret_cast<u32x4*>(p + KSTEP * i * LDR) = f.v[i];
 }
 
 // MFMA operand fragment for lane (row = lane%32, g = lane/32): the 8 values k = k16 + 8g .. +7 of that row.
@@ -292,16 +297,18 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, n0, g.N, k0, tid);
     }
   };
-  auto stash_a = [&](int buf, const Frag<BM, NT>& fa) {
+  constexpr int VA = BM * 8 / NT, VB = BN * 8 / NT;        // 16-byte vectors per thread and slab
+  static_assert(VA % 4 == 0 && VB % 4 == 0, "a quarter of the slab is stored per MFMA step");
+  auto stash_a = [&](int buf, const Frag<BM, NT>& fa, int i0 = 0, int i1 = 64) {
     bf16* As = smem + buf * (SLAB_A + SLAB_B);
-    if (TA == 0) store_kmajor<BM, NT>(fa, As, tid); else store_rmajor<BM, NT>(fa, As, tid);
+    if (TA == 0) store_kmajor<BM, NT>(fa, As, tid, i0, i1); else store_rmajor<BM, NT>(fa, As, tid, i0, i1);
   };
-  auto stash_b = [&](int buf, const Frag<BN, NT>& fb) {
+  auto stash_b = [&](int buf, const Frag<BN, NT>& fb, int i0 = 0, int i1 = 64) {
     bf16* Bs = smem + buf * (SLAB_A + SLAB_B) + SLAB_A;
-    if (TB == 1) store_kmajor<BN, NT>(fb, Bs, tid); else store_rmajor<BN, NT>(fb, Bs, tid);
+    if (TB == 1) store_kmajor<BN, NT>(fb, Bs, tid, i0, i1); else store_rmajor<BN, NT>(fb, Bs, tid, i0, i1);
   };
-  // multiplies the slab in LDS buffer `buf`; after the first and second of the four MFMA steps it writes
-  // the A and B parts of the next slab (held in fa, fb) into the other buffer, which nobody reads now
+  // multiplies the slab in LDS buffer `buf`; after each of the four MFMA steps it writes a quarter of the
+  // next slab (held in fa, fb) into the other buffer, which nobody reads now
   auto multiply = [&](int buf, const Frag<BM, NT>& fa, const Frag<BN, NT>& fb) {
     const bf16* As = smem + buf * (SLAB_A + SLAB_B);
     const bf16* Bs = As + SLAB_A;
@@ -319,8 +326,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
-      if (ks == 0) stash_a(buf ^ 1, fa);
-      if (ks == 1) stash_b(buf ^ 1, fb);
+      stash_a(buf ^ 1, fa, ks * VA / 4, (ks + 1) * VA / 4);
+      stash_b(buf ^ 1, fb, ks * VB / 4, (ks + 1) * VB / 4);
     }
   };
 

@@ -44,6 +44,12 @@ GEMM_CASES = [
     (257, 512, 1024, 0, 1, 1, 512, False, False, False),
     (8, 8, 8, 0, 0, 1, 0, False, False, False),
     (1000, 40, 2048, 1, 0, 1, 0, False, False, True),
+    # K a multiple of 32, ragged in M and N
+    (300, 264, 224, 0, 1, 1, 0, True, False, False),
+    (304, 264, 224, 1, 0, 2, 0, False, False, True),
+    (264, 1376, 96, 0, 0, 3, 0, False, True, False),
+    (296, 520, 160, 1, 1, 1, 0, False, False, False),
+    (130, 520, 3 * 160, 0, 1, 1, 160, False, False, False),
 ]
 
 
