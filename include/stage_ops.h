@@ -27,6 +27,17 @@ int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, i
                   const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,
                   int64_t sBias, int32_t kseg, int64_t segB, int32_t impl);
 
+/* stage_op_gemm with the rotary rotation fused into the store (Llama-style Q and K projections): for
+ * batch indices z < rope_batches, adjacent column pairs (2i, 2i+1) of every rope_d-wide head of C are
+ * rotated by the angle of rope_table[(row mod rope_S), i] = (cos, sin), after bias and residual and
+ * before rounding.  rope_table: float[rope_S, rope_d/2, 2] as written by stage_op_rope_table, 16-byte
+ * aligned; NULL = plain stage_op_gemm.  Needs c_f32_accum = 0 and N a multiple of rope_d. */
+int stage_op_gemm_rope(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
+                       const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
+                       const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB,
+                       int64_t sC, int64_t sBias, int32_t kseg, int64_t segB, int32_t impl, const float* rope_table,
+                       int32_t rope_S, int32_t rope_d, int32_t rope_batches);
+
 /* kind 0: LayerNorm n = (x-mean)/sqrt(var+eps)*g + b (biased variance), saves rstd[T], mean[T].
  * kind 1: RMSNorm n = x/sqrt(mean(x^2)+eps)*g, saves rstd[T].  x, n: [T,H]. */
 int stage_op_norm_fwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* x, const void* g,
@@ -42,6 +53,9 @@ int stage_op_norm_bwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int3
 int stage_op_rope(void* stream, int32_t dtype, int32_t T, int32_t S, int32_t ncols, int32_t d, void* a, int64_t ld,
                   float base, float sign, float* table);
 
+/* table[s, i] = (cos, sin)(s * base^(-2i/d)) for s < S, i < d/2, angles formed in double precision. */
+int stage_op_rope_table(void* stream, int32_t S, int32_t d, float base, float* table);
+
 /* GELU(z) = z*Phi(z) (erf form) and its derivative; SwiGLU a = silu(gate)*up with gu = [gate | up] [T,2F]. */
 int stage_op_gelu(void* stream, int32_t dtype, int64_t n, const void* z, const void* da, void* out, int32_t backward);
 int stage_op_swiglu(void* stream, int32_t dtype, int32_t T, int32_t F, const void* gu, const void* da, void* out,
@@ -56,6 +70,14 @@ int stage_op_attention_fwd(void* stream, int32_t dtype, int32_t mb, int32_t S, i
 int stage_op_attention_bwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
                            const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
                            const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl);
+
+/* stage_op_attention_bwd whose dq and dk are rotated back by the rotary angles before they are stored
+ * (gradients of the un-rotated projections): pair (2i, 2i+1) of every head by -angle(s, i), with
+ * rope_table as for stage_op_gemm_rope (rope_S = S, rope_d = d); NULL = plain stage_op_attention_bwd. */
+int stage_op_attention_bwd_rope(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                                const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
+                                const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl,
+                                const float* rope_table);
 
 /* x[t,:] = E[ids[t],:] ; dE[id,:] += sum of dx rows of the tokens carrying id (token order). */
 int stage_op_embed(void* stream, int32_t dtype, int32_t T, int32_t H, int32_t V, const int32_t* ids, const void* E,

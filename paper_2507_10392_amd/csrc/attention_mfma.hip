@@ -116,6 +116,19 @@ __device__ __forceinline__ BlockId block_id(int nh, int mb) {
   return BlockId{id / nhb, hb % nh, hb / nh};
 }
 
+// Inverse rotary rotation of 4 consecutive head-dim values (two adjacent pairs) of position pos, first
+// value at head-dim index d0 (a multiple of 4): (u, w) -> (u c + w s, -u s + w c).
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void unrotate4(float (&x)[4], const float2* __restrict__ rope, int pos, int d0) {
+  const f32x4v t = *reinterpret_cast<const f32x4v*>(rope + (int64_t)pos * (D / 2) + d0 / 2);   // (cos, sin) x 2
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float c = t[2 * i], sn = t[2 * i + 1], u = x[2 * i], w = x[2 * i + 1];
+    x[2 * i] = u * c + w * sn;
+    x[2 * i + 1] = w * c - u * sn;
+  }
+}
+
 // ------------------------------------------------------------------------------------------ forward
 // grid ceil(S/128)*nh*mb; wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
@@ -265,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
                                                           const bf16* __restrict__ dout, int64_t ldo,
                                                           const float* __restrict__ lse, const float* __restrict__ delta,
                                                           bf16* __restrict__ dq, int64_t ldd, float scale, int nh,
-                                                          int mb) {
+                                                          int mb, const float2* __restrict__ rope) {
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -350,9 +363,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = acc[db][4 * c + e] * scale;
+        if (rope) unrotate4(x, rope, my_q, db * 32 + 8 * c + 4 * (lane >> 5));
         bf16x4 w;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (bf16)(acc[db][4 * c + e] * scale);
+        for (int e = 0; e < 4; ++e) w[e] = (bf16)x[e];
         *reinterpret_cast<bf16x4*>(row + db * 32 + 8 * c + 4 * (lane >> 5)) = w;
       }
   }
@@ -370,7 +387,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
                                                            const bf16* __restrict__ dout, int64_t ldo,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
                                                            bf16* __restrict__ dk, bf16* __restrict__ dv, int64_t ldd,
-                                                           float scale, int nh, int mb) {
+                                                           float scale, int nh, int mb, const float2* __restrict__ rope) {
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);                 // [2][Q tile | dO tile]
   float* stats = reinterpret_cast<float*>(smem + 4 * TILE);       // [2][lse2[64] | delta[64]]
@@ -484,10 +501,14 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = dkacc[db][4 * c + e] * scale;
+        if (rope) unrotate4(x, rope, my_k, db * 32 + 8 * c + 4 * (lane >> 5));
         bf16x4 wk, wv;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          wk[e] = (bf16)(dkacc[db][4 * c + e] * scale);
+          wk[e] = (bf16)x[e];
           wv[e] = (bf16)dvacc[db][4 * c + e];
         }
         *reinterpret_cast<bf16x4*>(krow + db * 32 + 8 * c + 4 * (lane >> 5)) = wk;
@@ -524,7 +545,7 @@ hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
 
 hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
-                         void* dq, void* dk, void* dv, int64_t ldd) {
+                         void* dq, void* dk, void* dv, int64_t ldd, const float2* rope) {
   if ((int64_t)S * (ld > ldo ? ld : ldo) * 2 >= (1ll << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets
   static bool cfg1 = false, cfg2 = false, cfg3 = false;
   hipError_t e = set_smem(attn_bwd_dq_kernel, SMEM_FWD, cfg1);
@@ -536,15 +557,15 @@ hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
   hipLaunchKernelGGL(attn_delta_mfma_kernel, dim3((unsigned)cdiv(S, 4), (unsigned)nh, (unsigned)mb), blk, 0, st, S,
                      (const bf16*)o, (const bf16*)dout, ldo, delta);
   hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                     (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale, nh, mb);
+                     (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale, nh, mb, rope);
   // 256 keys per workgroup when that still gives every CU a workgroup, else 128
   if (cdiv(S, 256) * nh * mb >= 256) {
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), smem_dkv(8), st,
                        S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld, (const bf16*)dout, ldo, lse, delta, (bf16*)dk,
-                       (bf16*)dv, ldd, scale, nh, mb);
+                       (bf16*)dv, ldd, scale, nh, mb, rope);
   } else {
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<4>, grid, blk, smem_dkv(4), st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                       (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale, nh, mb);
+                       (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale, nh, mb, rope);
   }
   return hipGetLastError();
 }

@@ -207,7 +207,7 @@ hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
                          int64_t ld, void* o, int64_t ldo, float* lse);
 hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
-                         void* dq, void* dk, void* dv, int64_t ldd);
+                         void* dq, void* dk, void* dv, int64_t ldd, const float2* rope);
 bool attn_mfma_supported(DType dt, int S, int d);
 
 int attn_select(DType dt, int S, int d, int force) {
@@ -223,11 +223,14 @@ hipError_t attn_fwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, cons
 }
 hipError_t attn_bwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, const void* q, const void* k,
                     const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse,
-                    float* delta, void* dq, void* dk, void* dv, int64_t ldd, int force) {
-  if (attn_select(dt, S, d, force) == ATTN_MFMA)
-    return attn_bwd_mfma(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd);
-  return dt == F32 ? bwd_simple<float>(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd)
-                   : bwd_simple<bf16>(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd);
+                    float* delta, void* dq, void* dk, void* dv, int64_t ldd, const float2* rope, int force) {
+  if (attn_select(dt, S, d, force) == ATTN_MFMA)   // rotation fused into the kernels' stores
+    return attn_bwd_mfma(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd, rope);
+  hipError_t e = dt == F32 ? bwd_simple<float>(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd)
+                           : bwd_simple<bf16>(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd);
+  if (e == hipSuccess && rope) e = rope_apply(st, dt, mb * S, S, nh * d, d, dq, ldd, rope, -1.0f);
+  if (e == hipSuccess && rope) e = rope_apply(st, dt, mb * S, S, nh * d, d, dk, ldd, rope, -1.0f);
+  return e;
 }
 
 }  // namespace zs

@@ -31,7 +31,10 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
     if (!aligned16(g.C) || g.ldc % 8 || g.sC % 8) return false;
     if (g.resid && (!aligned16(g.resid) || g.ldr % 8)) return false;
     if (g.bias && (!aligned16(g.bias) || g.sBias % 8)) return false;
+    // the fused rotation works on whole 8-column vectors that do not straddle heads
+    if (g.rope && (g.N % 8 || g.rope_d % 8 || g.rope_S < 1 || ((uintptr_t)g.rope & 15))) return false;
   } else {
+    if (g.rope) return false;
     // the accumulating epilogue updates 4 consecutive floats per 16-byte access through 32-bit byte offsets
     if (!aligned16(g.C) || g.ldc % 4 || g.sC % 4 || g.N % 4) return false;
     if (g.bias || g.resid) return false;

@@ -194,6 +194,7 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
   const bf16* bias = g.bias ? (const bf16*)g.bias + (int64_t)z * g.sBias : nullptr;
   const bf16* R = g.resid ? (const bf16*)g.resid + (int64_t)z * g.sC : nullptr;
   bf16* Cz = (bf16*)g.C + (int64_t)z * g.sC;
+  const bool rope = g.rope && z < g.rope_batches;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     __syncthreads();                                       // K-loop reads / previous half's reads are done
@@ -219,6 +220,17 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
           const bf16x8 rr = *reinterpret_cast<const bf16x8*>(R + (int64_t)row * g.ldr + col);
 #pragma unroll
           for (int e = 0; e < 8; ++e) x[e] += (float)rr[e];
+        }
+        if (rope) {   // rotate the 4 adjacent pairs by the angles of this row's position
+          const f32x4* cs = reinterpret_cast<const f32x4*>(g.rope + (int64_t)(row % g.rope_S) * (g.rope_d / 2) + (col % g.rope_d) / 2);
+          const f32x4 t0 = cs[0], t1 = cs[1];          // (cos, sin) of pairs 0,1 and 2,3
+          const float c4[4] = {t0[0], t0[2], t1[0], t1[2]}, s4[4] = {t0[1], t0[3], t1[1], t1[3]};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float u = x[2 * i], w = x[2 * i + 1];
+            x[2 * i] = u * c4[i] - w * s4[i];
+            x[2 * i + 1] = u * s4[i] + w * c4[i];
+          }
         }
         bf16x8 o;
 #pragma unroll

@@ -108,8 +108,12 @@ int gemm_select(DType dt, const Gemm& g, int force) {
 }
 
 hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
-  if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, g);
-  return gemm_simple(st, dt, g);
+  if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, g);   // rotation fused into its epilogue
+  hipError_t e = gemm_simple(st, dt, g);
+  const int elem = dt == F32 ? 4 : 2;
+  for (int z = 0; e == hipSuccess && g.rope && z < g.rope_batches && z < g.batch; ++z)
+    e = rope_apply(st, dt, g.M, g.rope_S, g.N, g.rope_d, (char*)g.C + (int64_t)z * g.sC * elem, g.ldc, g.rope, 1.0f);
+  return e;
 }
 
 }  // namespace zs

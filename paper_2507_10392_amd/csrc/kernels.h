@@ -13,6 +13,9 @@ namespace zs {
 //   batch > 1: operand z uses A + z*sA, B + z*sB, C + z*sC, bias + z*sBias, R + z*sC.
 //   kseg > 0: the K range is cut in segments of kseg; segment s reads B from B + s*segB
 //             (dgrad through several weight matrices stored one after another).
+//   rope != NULL (c_f32_accum = 0 only): for batch indices z < rope_batches the adjacent column pairs of
+//             every head (rope_d columns wide) of C are rotated, after bias and residual and before the
+//             result is rounded, by the angle table[(row % rope_S) * rope_d/2 + pair] (cos, sin).
 struct Gemm {
   int M = 0, N = 0, K = 0, transA = 0, transB = 0;
   const void* A = nullptr; int64_t lda = 0;
@@ -23,6 +26,7 @@ struct Gemm {
   const void* resid = nullptr; int64_t ldr = 0;
   int batch = 1; int64_t sA = 0, sB = 0, sC = 0, sBias = 0;
   int kseg = 0; int64_t segB = 0;
+  const float2* rope = nullptr; int rope_S = 0, rope_d = 0, rope_batches = 0;
 };
 enum GemmImpl { GEMM_AUTO = 0, GEMM_SIMPLE = 1, GEMM_MFMA = 2 };
 // Returns which implementation a call with these arguments runs (GEMM_SIMPLE or GEMM_MFMA).
@@ -69,9 +73,11 @@ int attn_select(DType dt, int S, int d, int force);
 hipError_t attn_fwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, const void* q, const void* k,
                     const void* v, int64_t ld, void* o, int64_t ldo, float* lse, int force);
 // delta is float[mb, nh, S] scratch.  dq, dk, dv are laid out like q, k, v with row stride ldd.
+// rope != NULL: dq and dk are rotated back (angle -table[s, pair]) before they are stored, i.e. they are
+// the gradients of the un-rotated projections.
 hipError_t attn_bwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, const void* q, const void* k,
                     const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse,
-                    float* delta, void* dq, void* dk, void* dv, int64_t ldd, int force);
+                    float* delta, void* dq, void* dk, void* dv, int64_t ldd, const float2* rope, int force);
 
 // x[t,:] = E[ids[t],:] (rows of ids outside [0,V) give zeros).
 hipError_t embed_fwd(hipStream_t st, DType dt, int T, int H, int V, const int32_t* ids, const void* E, void* x);

@@ -15,10 +15,11 @@ int vec_of(int d) { return d == 0 ? 4 : 8; }
 
 extern "C" {
 
-int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
-                  const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
-                  const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,
-                  int64_t sBias, int32_t kseg, int64_t segB, int32_t impl) {
+int stage_op_gemm_rope(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
+                       const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
+                       const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB,
+                       int64_t sC, int64_t sBias, int32_t kseg, int64_t segB, int32_t impl, const float* rope_table,
+                       int32_t rope_S, int32_t rope_d, int32_t rope_batches) {
   if (!dt_ok(dtype) || M < 0 || N < 0 || K < 0 || batch < 1 || !A || !B || !C || kseg < 0) return STAGE_ERR_ARG;
   if (kseg > 0 && K % kseg) return STAGE_ERR_ARG;
   Gemm g;
@@ -26,12 +27,24 @@ int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, i
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc; g.c_f32_accum = c_f32_accum != 0;
   g.bias = bias; g.resid = resid; g.ldr = ldr; g.batch = batch; g.sA = sA; g.sB = sB; g.sC = sC; g.sBias = sBias;
   g.kseg = kseg; g.segB = segB;
+  if (rope_table) {
+    if (c_f32_accum || rope_S < 1 || rope_d < 8 || rope_d % 8 || N % rope_d || rope_batches < 0) return STAGE_ERR_ARG;
+    g.rope = (const float2*)rope_table; g.rope_S = rope_S; g.rope_d = rope_d; g.rope_batches = rope_batches;
+  }
   if (impl < 0 || impl > 4) return STAGE_ERR_ARG;
   if (impl >= GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
   if (impl > GEMM_MFMA) gemm_mfma_force_tile(impl - GEMM_MFMA);     // 3, 4: fixed workgroup tile
   const hipError_t e = gemm((hipStream_t)stream, (DType)dtype, g, impl > GEMM_MFMA ? GEMM_MFMA : impl);
   gemm_mfma_force_tile(0);
   return rc(e);
+}
+
+int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
+                  const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
+                  const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,
+                  int64_t sBias, int32_t kseg, int64_t segB, int32_t impl) {
+  return stage_op_gemm_rope(stream, dtype, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, c_f32_accum, bias, resid, ldr,
+                            batch, sA, sB, sC, sBias, kseg, segB, impl, nullptr, 0, 0, 0);
 }
 
 int stage_op_norm_fwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* x, const void* g,
@@ -67,6 +80,11 @@ int stage_op_rope(void* stream, int32_t dtype, int32_t T, int32_t S, int32_t nco
   return rc(e);
 }
 
+int stage_op_rope_table(void* stream, int32_t S, int32_t d, float base, float* table) {
+  if (S < 1 || d < 2 || d % 2 || !table || !(base > 0.f)) return STAGE_ERR_ARG;
+  return rc(rope_table((hipStream_t)stream, S, d, base, (float2*)table));
+}
+
 int stage_op_gelu(void* stream, int32_t dtype, int64_t n, const void* z, const void* da, void* out, int32_t backward) {
   if (!dt_ok(dtype) || n < 0 || n % vec_of(dtype) || !z || !out || (backward && !da)) return STAGE_ERR_ARG;
   if (n == 0) return STAGE_OK;
@@ -90,15 +108,23 @@ int stage_op_attention_fwd(void* stream, int32_t dtype, int32_t mb, int32_t S, i
   return rc(attn_fwd((hipStream_t)stream, (DType)dtype, mb, S, nh, d, q, k, v, ld, o, ldo, lse, impl));
 }
 
-int stage_op_attention_bwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
-                           const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
-                           const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl) {
+int stage_op_attention_bwd_rope(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                                const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
+                                const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl,
+                                const float* rope_table) {
   if (!dt_ok(dtype) || mb < 1 || S < 1 || nh < 1 || d < 8 || d % 8 || d > 256 || !q || !k || !v || !o || !dout || !lse ||
       !delta || !dq || !dk || !dv)
     return STAGE_ERR_ARG;
   if (impl == ATTN_MFMA && attn_select((DType)dtype, S, d, 0) != ATTN_MFMA) return STAGE_ERR_ARG;
   return rc(attn_bwd((hipStream_t)stream, (DType)dtype, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv,
-                     ldd, impl));
+                     ldd, (const float2*)rope_table, impl));
+}
+
+int stage_op_attention_bwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                           const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
+                           const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl) {
+  return stage_op_attention_bwd_rope(stream, dtype, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd,
+                                     impl, nullptr);
 }
 
 int stage_op_embed(void* stream, int32_t dtype, int32_t T, int32_t H, int32_t V, const int32_t* ids, const void* E,

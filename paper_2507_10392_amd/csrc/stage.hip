@@ -300,11 +300,11 @@ bool layer_forward(stage_t* s, int l, const char* x_in, LayerActs& A, char* y) {
   Gemm g;
   g.M = T; g.K = H; g.A = A.n1; g.lda = H; g.C = A.qkv; g.ldc = 3 * H;
   if (gpt) { g.N = 3 * H; g.B = W("Wqkv"); g.ldb = 3 * H; g.bias = W("bqkv"); }
-  else { g.N = H; g.B = W("Wq"); g.ldb = H; g.batch = 3; g.sB = (int64_t)H * H; g.sC = H; }
+  else {   // Q and K leave the projection already rotated
+    g.N = H; g.B = W("Wq"); g.ldb = H; g.batch = 3; g.sB = (int64_t)H * H; g.sC = H;
+    g.rope = s->plan.rope; g.rope_S = h.S; g.rope_d = h.d; g.rope_batches = 2;
+  }
   if (!do_gemm(s, g)) return false;
-  if (!gpt && !run(s, "rope", 0, 2.0 * 2 * thb, [&] {
-        return rope_apply(s->st, dt, T, h.S, 2 * H, h.d, A.qkv, 3 * H, s->plan.rope, 1.0f); }))
-    return false;
   const double attn_flops = 4.0 * h.mb * h.nh * (double)h.S * (h.S + 1) / 2 * h.d;
   if (!run(s, attn_select(dt, h.S, h.d, 0) == ATTN_MFMA ? "attn_fwd_mfma" : "attn_fwd_simple", attn_flops, 0, [&] {
         return attn_fwd(s->st, dt, h.mb, h.S, h.nh, h.d, A.qkv, A.qkv + (int64_t)H * h.E, A.qkv + 2ll * H * h.E, 3 * H,
@@ -416,10 +416,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   const int64_t HE = (int64_t)H * h.E;
   if (!run(s, attn_select(dt, h.S, h.d, 0) == ATTN_MFMA ? "attn_bwd_mfma" : "attn_bwd_simple", attn_flops, 0, [&] {
         return attn_bwd(s->st, dt, h.mb, h.S, h.nh, h.d, A.qkv, A.qkv + HE, A.qkv + 2 * HE, 3 * H, A.o, pl.gO, H, A.lse,
-                        pl.delta, pl.gQKV, pl.gQKV + HE, pl.gQKV + 2 * HE, 3 * H, ATTN_AUTO); }))
-    return false;
-  if (!gpt && !run(s, "rope", 0, 2.0 * 2 * thb, [&] {
-        return rope_apply(s->st, dt, T, h.S, 2 * H, h.d, pl.gQKV, 3 * H, pl.rope, -1.0f); }))
+                        pl.delta, pl.gQKV, pl.gQKV + HE, pl.gQKV + 2 * HE, 3 * H, gpt ? nullptr : pl.rope, ATTN_AUTO); }))
     return false;
 
   // QKV projection: dn1 = dqkv [Wq|Wk|Wv]^T ; dW += n1^T dqkv

@@ -273,6 +273,73 @@ def test_attention_fwd_bwd(gpu_device, mb, S, nh, d, dtype, impl):
         assert e <= (2e-2 if dtype else 5e-5), n
 
 
+@pytest.mark.parametrize("impl", [1, 2, 3, 4])
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_gemm_with_fused_rotation(gpu_device, dtype, impl):
+    """Q|K|V projection as a batch of three products whose first two results are rotated in the store:
+    against float64 matmul followed by the oracle's rotation; V must be the plain product."""
+    if impl >= 2 and dtype == 0:
+        pytest.skip("the MFMA kernel is bf16 only")
+    print(f"[case] gemm+rope dtype={dtype} impl={impl}", flush=True)
+    rng = np.random.default_rng(31)
+    mb, S, nh, d, K = 2, 150, 3, 128, 96          # 300 rows (ragged tile), 384 columns
+    T, H = mb * S, nh * d
+    td = TD[dtype]
+    A = draw(rng, (T, K), dtype)
+    B = draw(rng, (3, K, H), dtype, 0.1)
+    R = draw(rng, (3, T, H), dtype)
+    want = np.stack([A.astype(np.float64) @ B[z].astype(np.float64) + R[z] for z in range(3)])
+    for z in range(2):
+        want[z] = so.rope(want[z].reshape(mb, S, nh, d), 10000.0).reshape(T, H)
+    table = torch.empty(S * d, device="cuda")
+    zs.ops.rope_table(st(), S, d, 10000.0, table)
+    C = torch.full((3, T, H), float("nan"), dtype=td, device="cuda")
+    zs.ops.gemm_rope(st(), dtype, 0, 0, T, H, K, dev(A, td), K, dev(B, td), H, C, H, 0, None, dev(R, td), H, 3, 0, K * H,
+                     T * H, 0, 0, 0, impl, table, S, d, 2)
+    got = back(C)
+    errs = [(f"z{z}", rel_err(got[z], want[z])) for z in range(3)]
+    log_report(f"gemm+rope dtype={dtype} impl={impl}", errs)
+    for n, e in errs:
+        assert e <= (1e-2 if dtype else 2e-5), n
+
+
+@pytest.mark.parametrize("impl", [1, 2])
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_attention_bwd_with_fused_inverse_rotation(gpu_device, dtype, impl):
+    """dq and dk leave the backward kernels rotated back: against the oracle's gradients, rotated by
+    the oracle with sign -1; dv is unchanged."""
+    if impl == 2 and dtype == 0:
+        pytest.skip("the MFMA attention kernel is bf16")
+    print(f"[case] attention bwd + inverse rope dtype={dtype} impl={impl}", flush=True)
+    rng = np.random.default_rng(32)
+    mb, S, nh, d = 2, 200, 2, 128
+    H = nh * d
+    td = TD[dtype]
+    qkv = draw(rng, (mb * S, 3 * H), dtype)
+    do = draw(rng, (mb * S, H), dtype)
+    q, k, v = (qkv[:, i * H:(i + 1) * H].astype(np.float64).reshape(mb, S, nh, d) for i in range(3))
+    dq_o, dk_o, dv_o = so.attention_bwd(do.astype(np.float64).reshape(mb, S, nh, d), q, k, v)
+    dq_o, dk_o = so.rope(dq_o, 10000.0, sign=-1.0), so.rope(dk_o, 10000.0, sign=-1.0)
+    dqkv_in = dev(qkv, td)
+    qp, kp, vp = (torch.as_strided(dqkv_in, (mb * S, H), (3 * H, 1), i * H) for i in range(3))
+    o = torch.empty(mb * S, H, dtype=td, device="cuda")
+    lse = torch.empty(mb * nh * S, device="cuda")
+    zs.ops.attention_fwd(st(), dtype, mb, S, nh, d, qp, kp, vp, 3 * H, o, H, lse, impl)
+    table = torch.empty(S * d, device="cuda")
+    zs.ops.rope_table(st(), S, d, 10000.0, table)
+    delta = torch.empty(mb * nh * S, device="cuda")
+    dqkv = torch.full((mb * S, 3 * H), float("nan"), dtype=td, device="cuda")
+    dq_, dk_, dv_ = (torch.as_strided(dqkv, (mb * S, H), (3 * H, 1), i * H) for i in range(3))
+    zs.ops.attention_bwd_rope(st(), dtype, mb, S, nh, d, qp, kp, vp, 3 * H, o, dev(do, td), H, lse, delta, dq_, dk_, dv_,
+                              3 * H, impl, table)
+    got = back(dqkv)
+    errs = [("dq", rel_err(got[:, :H], dq_o.reshape(mb * S, H))), ("dk", rel_err(got[:, H:2 * H], dk_o.reshape(mb * S, H))),
+            ("dv", rel_err(got[:, 2 * H:], dv_o.reshape(mb * S, H)))]
+    log_report(f"attention bwd + inverse rope dtype={dtype} impl={impl}", errs)
+    for n, e in errs:
+        assert e <= (2e-2 if dtype else 5e-5), n
+
+
 # ----------------------------------------------------------------------------- embedding, cross entropy, AdamW
 
 
