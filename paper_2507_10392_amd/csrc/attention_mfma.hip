@@ -12,7 +12,7 @@
 //
 // Backward is two kernels without atomics (fixed summation order): one owns 128 queries and
 // produces dQ, one owns 128 keys and produces dK and dV; both recompute P from the saved
-// log-sum-exp.  delta_i = dO_i . O_i comes from a small pre-pass.
+// log-sum-exp.  delta_i = dO_i . O_i is formed by the dQ kernel for its own rows and stored for the other.
 #include "kernels.h"
 
 namespace zs {
@@ -254,29 +254,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
   }
 }
 
-// ------------------------------------------------------------------------------------------ delta
-__global__ __launch_bounds__(256) void attn_delta_mfma_kernel(int S, const bf16* __restrict__ o,
-                                                              const bf16* __restrict__ dout, int64_t ldo,
-                                                              float* __restrict__ delta) {
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i = blockIdx.x * 4 + w;
-  const int h = blockIdx.y, b = blockIdx.z, nh = gridDim.y;
-  if (i >= S) return;
-  const int64_t off = ((int64_t)b * S + i) * ldo + h * D + lane * 2;
-  const bf16x2 a = *reinterpret_cast<const bf16x2*>(o + off);
-  const bf16x2 c = *reinterpret_cast<const bf16x2*>(dout + off);
-  float s = (float)a[0] * (float)c[0] + (float)a[1] * (float)c[1];
-  s = wave_sum(s);
-  if (lane == 0) delta[((int64_t)b * nh + h) * S + i] = s;
-}
-
 // ------------------------------------------------------------------------------------------ dQ
 // grid ceil(S/128)*nh*mb; wave w owns queries q0+32w..; loops over K/V tiles up to the diagonal.
 // dQ^T[d][q] += K^T[d][key] dS^T[key][q],  dS^T = P^T o (dP^T - delta_q),  dP^T = V dO^T.
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
                                                           const bf16* __restrict__ v, int64_t ld,
-                                                          const bf16* __restrict__ dout, int64_t ldo,
-                                                          const float* __restrict__ lse, const float* __restrict__ delta,
+                                                          const bf16* __restrict__ o, const bf16* __restrict__ dout,
+                                                          int64_t ldo, const float* __restrict__ lse,
+                                                          float* __restrict__ delta,
                                                           bf16* __restrict__ dq, int64_t ldd, float scale, int nh,
                                                           int mb, const float2* __restrict__ rope) {
   extern __shared__ __align__(16) char smem_raw[];
@@ -299,7 +284,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
   load_row_frags(dof, doh, ldo, wq0, S, lane);
   const int64_t stat = ((int64_t)b * nh + h) * S + min(my_q, S - 1);
   const float lse2 = lse[stat] * LOG2E;
-  const float dlt = delta[stat];
+  // delta_q = dO_q . O_q: each lane sums its 64 of the row's 128 products, lane^32 holds the others.
+  // The value is also stored for the dK/dV kernel, which runs after this one.
+  float dlt = 0.f;
+  {
+    bf16x8 of[8];
+    load_row_frags(of, o + tok0 * ldo + h * D, ldo, wq0, S, lane);
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dlt = fmaf((float)dof[s][e], (float)of[s][e], dlt);
+    dlt += __shfl_xor(dlt, 32, 64);
+    if (lane < 32 && my_q < S) delta[stat] = dlt;
+  }
   f32x16 acc[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -554,10 +551,8 @@ hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)d);
   dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
-  hipLaunchKernelGGL(attn_delta_mfma_kernel, dim3((unsigned)cdiv(S, 4), (unsigned)nh, (unsigned)mb), blk, 0, st, S,
-                     (const bf16*)o, (const bf16*)dout, ldo, delta);
   hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                     (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale, nh, mb, rope);
+                     (const bf16*)o, (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale, nh, mb, rope);
   // 256 keys per workgroup when that still gives every CU a workgroup, else 128
   if (cdiv(S, 256) * nh * mb >= 256) {
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), smem_dkv(8), st,

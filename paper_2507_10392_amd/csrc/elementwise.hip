@@ -483,7 +483,9 @@ __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, vo
   if (i >= n) return;
   float* pm = BF ? master + i : (float*)params + begin + i;
   if (VEC) {
-    f32x4 p4 = *(f32x4*)pm, g4 = *(f32x4*)(grad + begin + i), m4 = *(f32x4*)(m + i), v4 = *(f32x4*)(v + i);
+    // every byte is touched once per step: non-temporal accesses keep the streams out of the caches
+    f32x4 p4 = __builtin_nontemporal_load((f32x4*)pm), g4 = __builtin_nontemporal_load((f32x4*)(grad + begin + i)),
+          m4 = __builtin_nontemporal_load((f32x4*)(m + i)), v4 = __builtin_nontemporal_load((f32x4*)(v + i));
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       float mm = m4[k], vv = v4[k];
@@ -491,16 +493,16 @@ __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, vo
       m4[k] = mm;
       v4[k] = vv;
     }
-    *(f32x4*)pm = p4;
-    *(f32x4*)(m + i) = m4;
-    *(f32x4*)(v + i) = v4;
+    __builtin_nontemporal_store(p4, (f32x4*)pm);
+    __builtin_nontemporal_store(m4, (f32x4*)(m + i));
+    __builtin_nontemporal_store(v4, (f32x4*)(v + i));
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    *(f32x4*)(grad + begin + i) = zero;
+    __builtin_nontemporal_store(zero, (f32x4*)(grad + begin + i));
     if (BF) {
       bf16x4 b;
 #pragma unroll
       for (int k = 0; k < 4; ++k) b[k] = (bf16)p4[k];
-      *(bf16x4*)((bf16*)params + begin + i) = b;
+      __builtin_nontemporal_store(b, (bf16x4*)((bf16*)params + begin + i));
     }
   } else {
     float mm = m[i], vv = v[i];

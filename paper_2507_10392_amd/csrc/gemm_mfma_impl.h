@@ -33,25 +33,26 @@ template <int R, int NT> struct Frag { u32x4 v[R * 8 / NT]; };   // one thread's
 
 // Operands are read through raw buffer descriptors: the per-lane offset is one VGPR, the per-load
 // offset a scalar, and anything at or beyond num_records reads as zero, which handles the ragged edge
-// along each operand's OUTER dimension for free.  The edge along the inner (contiguous) dimension
-// still needs a mask, applied under a workgroup-uniform condition.
+// along each operand's OUTER dimension for free.  Along the inner (contiguous) dimension the pieces past
+// the edge get a per-lane offset that is out of range (DEAD, below).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
-template <int R, int NT> __device__ __forceinline__ void zero_frag(Frag<R, NT>& f) {
-#pragma unroll
-  for (int i = 0; i < R * 8 / NT; ++i) f.v[i] = u32x4{0u, 0u, 0u, 0u};
-}
+// A per-lane byte offset of DEAD lies beyond every num_records (operand extents are below 2^30 bytes), so a
+// lane whose piece must read as zero is simply sent there: no masks or branches in the K loop.
+constexpr int DEAD = 0x40000000;
 
 // Operand stored [rows, K] (k contiguous), ld = row stride.  With NT threads, thread t carries vectors
 // v = t + NT*i: row = v/8, k-vector = v%8 (= t%8 for every i).  voff = ((t/8)*ld + (t%8)*8)*2 bytes (+ segment shift).
+// Rows past the operand's last row lie beyond num_records; k-vectors at or past K (ragged last slab, and
+// slabs past the end) would run into the next row and are sent out of range.
 template <int R, int NT>
 __device__ __forceinline__ void load_kmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int k0,
                                             int K, int tid) {
+  const int vo = k0 + (tid & 7) * 8 >= K ? DEAD : voff;
 #pragma unroll
   for (int i = 0; i < R * 8 / NT; ++i)
-    f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((row0 + (NT / 8) * i) * ld + k0) * 2, 0);
-  if (k0 + BK > K && k0 + (tid & 7) * 8 >= K) zero_frag(f);     // ragged last slab
+    f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, vo, ((row0 + (NT / 8) * i) * ld + k0) * 2, 0);
 }
 // Stores vectors [i0, i1) of the thread's share.
 template <int R, int NT>
@@ -64,17 +65,16 @@ __device__ __forceinline__ void store_kmajor(const Frag<R, NT>& f, bf16* lds, in
 
 // Operand stored [K, rows] (row index contiguous).  A k-line of the slab is R/8 vectors; thread t carries
 // vectors v = t + NT*i: k = v/(R/8), row-vector = v%(R/8) (= t%(R/8) for every i).
-template <int R> __device__ __forceinline__ int voff_rmajor(int ld, int tid) {
-  return ((tid / (R / 8)) * ld + (tid % (R / 8)) * 8) * 2;
+// Row-vectors at or past the operand's last row (ragged edge tile) would read the next k-line: out of range.
+template <int R> __device__ __forceinline__ int voff_rmajor(int ld, int tid, int row0, int nrows) {
+  return row0 + (tid % (R / 8)) * 8 >= nrows ? DEAD : ((tid / (R / 8)) * ld + (tid % (R / 8)) * 8) * 2;
 }
 template <int R, int NT>
-__device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0,
-                                            int nrows, int k0, int tid) {
+__device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int k0) {
   constexpr int KSTEP = NT / (R / 8);             // k-lines covered by one pass of the NT threads
 #pragma unroll
   for (int i = 0; i < R * 8 / NT; ++i)
     f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((k0 + KSTEP * i) * ld + row0) * 2, 0);
-  if (row0 + R > nrows && row0 + (tid % (R / 8)) * 8 >= nrows) zero_frag(f);   // ragged edge tile
 }
 template <int R, int NT>
 __device__ __forceinline__ void store_rmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
@@ -291,13 +291,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   const __amdgpu_buffer_rsrc_t rsB = make_rsrc(
       B, (uint32_t)(TB == 1 ? ((int64_t)(nseg - 1) * g.segB + (int64_t)(g.N - 1) * ldb + (SEG ? g.kseg : g.K))
                             : ((int64_t)(g.K - 1) * ldb + g.N)) * 2u);
-  const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : voff_rmajor<BM>(lda, tid);
-  const int voffB = TB == 1 ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2 : voff_rmajor<BN>(ldb, tid);
+  const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : voff_rmajor<BM>(lda, tid, m0, g.M);
+  const int voffB = TB == 1 ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2 : voff_rmajor<BN>(ldb, tid, n0, g.N);
 
   auto fetch = [&](int kt, Frag<BM, NT>& fa0, Frag<BN, NT>& fb0) {
     const int k0 = kt * BK;
     if (TA == 0) load_kmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0, g.K, tid);
-    else load_rmajor<BM, NT>(fa0, rsA, voffA, lda, m0, g.M, k0, tid);
+    else load_rmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0);
     if (TB == 1) {
       int vo = voffB;
       if (SEG) {  // the thread's k offset inside the slab is fixed, so one segment lookup per slab
@@ -306,7 +306,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       }
       load_kmajor<BN, NT>(fb0, rsB, vo, ldb, n0, k0, g.K, tid);
     } else {
-      load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, n0, g.N, k0, tid);
+      load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, n0, k0);
     }
   };
   constexpr int VA = BM * 8 / NT, VB = BN * 8 / NT;        // 16-byte vectors per thread and slab
@@ -343,7 +343,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     }
   };
 
-  // Slabs past K read zeros (masked or beyond num_records), so the loop needs no conditions: it walks K in
+  // Slabs past K read zeros (their loads are out of range), so the loop needs no conditions: it walks K in
   // pairs of slabs and a surplus slab contributes nothing.
   fetch(0, fa0, fb0);
   stash_a(0, fa0);
