@@ -25,6 +25,10 @@ namespace gemm_impl {
 
 constexpr int BK = 64;
 constexpr int LDK = BK + 8;                       // [row][k] layout: padded row length (144 bytes)
+// [k][row] slabs: k-lines are padded by RPAD elements.  A transpose read serves 32 lanes per cycle, which
+// touch 4 k-lines x 64 bytes; with k-lines 16 banks apart (mod 64) those are 64 different banks.
+constexpr int RPAD = 32;
+constexpr int slab_elems(int R) { return R * LDK > BK * (R + RPAD) ? R * LDK : BK * (R + RPAD); }
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -78,7 +82,7 @@ __device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc
 }
 template <int R, int NT>
 __device__ __forceinline__ void store_rmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
-  constexpr int KSTEP = NT / (R / 8), LDR = R + 16;
+  constexpr int KSTEP = NT / (R / 8), LDR = R + RPAD;
   bf16* p = lds + (tid / (R / 8)) * LDR + (tid % (R / 8)) * 8;
 #pragma unroll
   for (int i = 0; i < R * 8 / NT; ++i)
@@ -92,7 +96,7 @@ __device__ __forceinline__ bf16x8 frag_kmajor(const bf16* tile, int row0, int k1
 // Same fragment from a [k][row] tile.  One transpose read serves 16 lanes: lane r of the group points at
 // 4 consecutive rows of k-line (r/4) and receives the 4 k-lines' values of ONE row.
 template <int R> __device__ __forceinline__ bf16x8 frag_rmajor(const bf16* tile, int row0, int k16, int lane) {
-  constexpr int LDR = R + 16;
+  constexpr int LDR = R + RPAD;
   const int r = lane & 15, gi = lane >> 4;
   const bf16* p = tile + (k16 + 8 * (gi >> 1) + (r >> 2)) * LDR + row0 + 16 * (gi & 1) + 4 * (r & 3);
   union { struct { s16x4 a, b; } s; bf16x8 v; } u;
@@ -150,7 +154,7 @@ template <int BM, int BN, int NT, int MI, int NJ>
 __device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
                                                int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
-  static_assert((BM / 2) * LDW * 4 <= 2 * (BM + BN) * LDK * 2, "staging tile must fit the K-loop buffers");
+  static_assert((BM / 2) * LDW * 4 <= 2 * (slab_elems(BM) + slab_elems(BN)) * 2, "staging tile must fit the K-loop buffers");
   constexpr int VPR = BN / 4;                              // float4 per row
   constexpr int NV = (BM / 2) * VPR / NT;                  // float4 per thread and half
   float* Cz = (float*)g.C + (int64_t)z * g.sC;
@@ -189,7 +193,7 @@ template <int BM, int BN, int NT, int MI, int NJ>
 __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
                                                int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
-  static_assert((BM / 2) * LDW * 4 <= 2 * (BM + BN) * LDK * 2, "staging tile must fit the K-loop buffers");
+  static_assert((BM / 2) * LDW * 4 <= 2 * (slab_elems(BM) + slab_elems(BN)) * 2, "staging tile must fit the K-loop buffers");
   const int lane = tid & 63;
   const bf16* bias = g.bias ? (const bf16*)g.bias + (int64_t)z * g.sBias : nullptr;
   const bf16* R = g.resid ? (const bf16*)g.resid + (int64_t)z * g.sC : nullptr;
@@ -255,7 +259,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
                                                                                                         int tiles_n) {
   constexpr int NT = 64 * NW, WN = NW / 2;               // threads; waves along n (2 along m)
   constexpr int MI = BM / 64, NJ = BN / (32 * WN);       // 32x32 blocks per wave along m and n
-  constexpr int SLAB_A = BM * LDK, SLAB_B = BN * LDK;    // LDS elements per operand slab (>= 64*(R+16))
+  constexpr int SLAB_A = slab_elems(BM), SLAB_B = slab_elems(BN);   // LDS elements per operand slab, either layout
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);        // [2 buffers][A slab | B slab]
 
@@ -364,7 +368,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 }
 
 template <int BM, int BN, int NW, int TA, int TB, int SEG, int ACC> hipError_t launch2(hipStream_t st, const Gemm& g) {
-  constexpr size_t SMEM_BYTES = 2 * (BM + BN) * LDK * sizeof(bf16);
+  constexpr size_t SMEM_BYTES = 2 * (slab_elems(BM) + slab_elems(BN)) * sizeof(bf16);
   static bool configured = false;
   auto kern = gemm_mfma_kernel<BM, BN, NW, TA, TB, SEG, ACC>;
   if (!configured) {
