@@ -21,7 +21,10 @@ namespace {
 
 constexpr int D = 128;             // head dim
 constexpr int TR = 64;             // rows of a staged tile
-constexpr int LDT = D + 16;        // padded LDS row length in elements (288 bytes)
+// Padded LDS row length in elements: 304 bytes = 76 banks = 12 (mod 64).  The 16 rows that one cycle of a
+// row-fragment read touches then start in 16 different 4-bank groups (no conflicts); the 4 rows x 64 bytes
+// of a transposing read overlap in 4 of their 16 banks, the least any padding allows next to that.
+constexpr int LDT = D + 24;
 constexpr int TILE = TR * LDT;     // elements of one staged tile
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
@@ -514,7 +517,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
   }
 }
 
-constexpr size_t SMEM_FWD = 4 * TILE * sizeof(bf16);                    // 73728
+constexpr size_t SMEM_FWD = 4 * TILE * sizeof(bf16);                    // 77824
 constexpr size_t smem_dkv(int nw) { return 4 * TILE * sizeof(bf16) + 256 * sizeof(float) + (size_t)nw * 32 * LDT * sizeof(bf16); }
 
 template <typename K> hipError_t set_smem(K kern, size_t bytes, bool& done) {
