@@ -176,12 +176,16 @@ def main():
     torch.cuda.synchronize()
     if not args.no_kernel_events:
         stage.profile(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the stage's stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         t += 1
         step(t)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     stats = stage.profile_read() if not args.no_kernel_events else {}
     stage.profile(False)
     finite = bool(torch.isfinite(params.float().sum()).item())
@@ -226,7 +230,9 @@ def main():
                                f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {e - b} of {P} params, "
                                f"recompute {cfg.recompute}",
                    "tokens_per_step": tokens, "shard_elems": e - b},
-        "mfu_model_flops": mfu, "model_tflop_per_step": mflops / 1e12, "finite": finite,
+        "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
+        "mfu_model_flops": mfu, "hfu_executed_flops": mfu * (4.0 / 3.0 if cfg.recompute else 1.0),
+        "model_tflop_per_step": mflops / 1e12, "finite": finite,
         "roofline": roofline, "kernels": kernels,
     }
     if "adamw" in kernels:

@@ -67,14 +67,81 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(int Trows, int H, const T
   }
 }
 
+// Same arithmetic with the row kept in registers (one global read): H = 64 lanes x V x J exactly.  The
+// element -> lane assignment and the order of every sum equal the kernel above, so the results are identical.
+template <typename T, int KIND, int J>
+__global__ __launch_bounds__(256) void norm_fwd_reg_kernel(int Trows, const T* __restrict__ x, const T* __restrict__ g,
+                                                           const T* __restrict__ b, float eps, T* __restrict__ n,
+                                                           float* __restrict__ rstd, float* __restrict__ mean) {
+  constexpr int V = Vec<T>::N, H = 64 * V * J;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Trows) return;
+  const T* xr = x + (int64_t)row * H;
+  float a[J][V];
+#pragma unroll
+  for (int j = 0; j < J; ++j) load_vec(xr + (j * 64 + lane) * V, a[j]);
+  float mu = 0.f;
+  if (KIND == 0) {
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+#pragma unroll
+      for (int i = 0; i < V; ++i) s += a[j][i];
+    mu = wave_sum(s) / (float)H;
+  }
+  float s2 = 0.f;
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+#pragma unroll
+    for (int i = 0; i < V; ++i) s2 += (a[j][i] - mu) * (a[j][i] - mu);
+  const float r = 1.0f / sqrtf(wave_sum(s2) / (float)H + eps);
+  if (lane == 0) {
+    rstd[row] = r;
+    if (KIND == 0) mean[row] = mu;
+  }
+  T* nr = n + (int64_t)row * H;
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = (j * 64 + lane) * V;
+    float gg[V], bb[V], o[V];
+    load_vec(g + c, gg);
+    if (KIND == 0) load_vec(b + c, bb);
+#pragma unroll
+    for (int i = 0; i < V; ++i) o[i] = (a[j][i] - mu) * r * gg[i] + (KIND == 0 ? bb[i] : 0.f);
+    store_vec(nr + c, o);
+  }
+}
+
+// J (row = 64 x V x J elements) for which the register-resident norm kernels are instantiated, else 0.
+static int reg_chunks(DType dt, int H) {
+  const int per = 64 * (dt == F32 ? 4 : 8);
+  if (H % per) return 0;
+  const int J = H / per;
+  return (J == 1 || J == 2 || J == 4 || J == 8 || J == 10) ? J : 0;
+}
+
 hipError_t norm_fwd(hipStream_t st, DType dt, int kind, int T, int H, const void* x, const void* g, const void* b,
                     float eps, void* n, float* rstd, float* mean) {
   dim3 grid((unsigned)cdiv(T, 4)), blk(256);
+  const int J = reg_chunks(dt, H);
+#define LR(TT, KK, JJ) \
+  hipLaunchKernelGGL((norm_fwd_reg_kernel<TT, KK, JJ>), grid, blk, 0, st, T, (const TT*)x, (const TT*)g, (const TT*)b, eps, (TT*)n, rstd, mean)
+#define LJ(TT, KK) \
+  switch (J) { case 1: LR(TT, KK, 1); break; case 2: LR(TT, KK, 2); break; case 4: LR(TT, KK, 4); break; \
+               case 8: LR(TT, KK, 8); break; default: LR(TT, KK, 10); break; }
 #define L(TT, KK) \
   hipLaunchKernelGGL((norm_fwd_kernel<TT, KK>), grid, blk, 0, st, T, H, (const TT*)x, (const TT*)g, (const TT*)b, eps, (TT*)n, rstd, mean)
-  if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
-  else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+  if (J) {
+    if (dt == F32) { if (kind == 0) { LJ(float, 0) } else { LJ(float, 1) } }
+    else { if (kind == 0) { LJ(bf16, 0) } else { LJ(bf16, 1) } }
+  } else {
+    if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
+    else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+  }
 #undef L
+#undef LJ
+#undef LR
   return hipGetLastError();
 }
 
@@ -123,14 +190,74 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(int Trows, int H, const T
   }
 }
 
+// ------------------------------------------------------------------ norm backward, row in registers
+// dx as norm_bwd_kernel with each row read once and kept in registers as stored (H = 64 x V x J); same
+// element -> lane assignment and summation order, hence identical results.
+template <typename T, int KIND, int J>
+__global__ __launch_bounds__(256) void norm_bwd_reg_kernel(int Trows, const T* __restrict__ dn, const T* __restrict__ x,
+                                                           const T* __restrict__ g, const float* __restrict__ rstd,
+                                                           const float* __restrict__ mean, const T* dres, T* dx) {
+  constexpr int V = Vec<T>::N, H = 64 * V * J;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= Trows) return;
+  const float r = rstd[row];
+  const float mu = (KIND == 0) ? mean[row] : 0.f;
+  const int64_t off = (int64_t)row * H;
+  typename Vec<T>::type xv[J], dv[J];
+  float su = 0.f, sux = 0.f;
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = (j * 64 + lane) * V;
+    xv[j] = *reinterpret_cast<const typename Vec<T>::type*>(x + off + c);
+    dv[j] = *reinterpret_cast<const typename Vec<T>::type*>(dn + off + c);
+    float gg[V];
+    load_vec(g + c, gg);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const float u = to_f(dv[j][i]) * gg[i];
+      su += u;
+      sux += u * (to_f(xv[j][i]) - mu) * r;
+    }
+  }
+  const float mu_u = (KIND == 0) ? wave_sum(su) / (float)H : 0.f;
+  const float mu_ux = wave_sum(sux) / (float)H;
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = (j * 64 + lane) * V;
+    float o[V], rs[V], gg[V];
+    load_vec(g + c, gg);
+    if (dres) load_vec(dres + off + c, rs);
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const float u = to_f(dv[j][i]) * gg[i];
+      o[i] = r * (u - mu_u - (to_f(xv[j][i]) - mu) * r * mu_ux) + (dres ? rs[i] : 0.f);
+    }
+    store_vec(dx + off + c, o);
+  }
+}
+
 hipError_t norm_bwd(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x, const void* g,
                     const float* rstd, const float* mean, const void* dres, void* dx) {
   dim3 grid((unsigned)cdiv(T, 4)), blk(256);
+  const int J = reg_chunks(dt, H);
+#define LR(TT, KK, JJ) \
+  hipLaunchKernelGGL((norm_bwd_reg_kernel<TT, KK, JJ>), grid, blk, 0, st, T, (const TT*)dn, (const TT*)x, (const TT*)g, rstd, mean, (const TT*)dres, (TT*)dx)
+#define LJ(TT, KK) \
+  switch (J) { case 1: LR(TT, KK, 1); break; case 2: LR(TT, KK, 2); break; case 4: LR(TT, KK, 4); break; \
+               case 8: LR(TT, KK, 8); break; default: LR(TT, KK, 10); break; }
 #define L(TT, KK) \
   hipLaunchKernelGGL((norm_bwd_kernel<TT, KK>), grid, blk, 0, st, T, H, (const TT*)dn, (const TT*)x, (const TT*)g, rstd, mean, (const TT*)dres, (TT*)dx)
-  if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
-  else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+  if (J) {
+    if (dt == F32) { if (kind == 0) { LJ(float, 0) } else { LJ(float, 1) } }
+    else { if (kind == 0) { LJ(bf16, 0) } else { LJ(bf16, 1) } }
+  } else {
+    if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
+    else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+  }
 #undef L
+#undef LJ
+#undef LR
   return hipGetLastError();
 }
 
@@ -205,13 +332,30 @@ hipError_t colsum_partial(hipStream_t st, DType dt, int T, int N, const void* a,
   return hipGetLastError();
 }
 
+hipError_t norm_bwd_partials(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x, const void* g,
+                             const float* rstd, const float* mean, const void* dres, void* dx, float* part_g,
+                             float* part_b, int nblk) {
+  hipError_t e = colsum_partial(st, dt, T, H, dn, H, x, H, rstd, kind == 0 ? mean : nullptr, part_g, nblk);
+  if (e == hipSuccess && kind == 0) e = colsum_partial(st, dt, T, H, dn, H, nullptr, H, nullptr, nullptr, part_b, nblk);
+  if (e == hipSuccess) e = norm_bwd(st, dt, kind, T, H, dn, x, g, rstd, mean, dres, dx);
+  return e;
+}
+
+// dst[c] += sum over the blocks, formed as four interleaved running sums (blocks b, b+4, ...) that are
+// added in the order 0..3 at the end: a fixed order, with four loads in flight per thread.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const ReduceJob* __restrict__ jobs) {
   const ReduceJob j = jobs[blockIdx.x];
   const int c = blockIdx.y * 256 + threadIdx.x;
   if (c >= j.width) return;
-  float s = 0.f;
-  for (int b = 0; b < j.nblk; ++b) s += j.part[(int64_t)b * j.width + c];
-  j.dst[c] += s;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  const float* p = j.part + c;
+  int b = 0;
+  for (; b + 4 <= j.nblk; b += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s[u] += p[(int64_t)(b + u) * j.width];
+  }
+  for (int u = 0; b < j.nblk; ++b, ++u) s[u] += p[(int64_t)b * j.width];
+  j.dst[c] += ((s[0] + s[1]) + s[2]) + s[3];
 }
 
 hipError_t reduce_partials(hipStream_t st, const ReduceJob* jobs_dev, int njobs, int max_width) {

@@ -45,6 +45,12 @@ hipError_t norm_fwd(hipStream_t st, DType dt, int kind, int T, int H, const void
 // dx = (dres ? dres : 0) + norm'(x)^T dn.  dres may alias dx.
 hipError_t norm_bwd(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x, const void* g,
                     const float* rstd, const float* mean, const void* dres, void* dx);
+// norm_bwd plus the partial column sums of the gain (and, for LayerNorm, bias) gradient over row blocks of
+// cdiv(T, nblk) rows: part_g[blk, c] = sum_t dn * xhat, part_b[blk, c] = sum_t dn (part_b may be NULL for
+// RMSNorm): colsum_partial and norm_bwd one after the other.
+hipError_t norm_bwd_partials(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x,
+                             const void* g, const float* rstd, const float* mean, const void* dres, void* dx,
+                             float* part_g, float* part_b, int nblk);
 // part[blk, n] = sum over the rows t of block blk of a[t,n] * (x ? (x[t,n]-mean[t])*rstd[t] : 1)
 // (mean may be NULL = 0).  Rows are cut in nblk equal blocks.  part is float[nblk, N].
 hipError_t colsum_partial(hipStream_t st, DType dt, int T, int N, const void* a, int64_t lda, const void* x,

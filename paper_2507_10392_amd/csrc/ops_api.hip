@@ -64,10 +64,7 @@ int stage_op_norm_bwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int3
     return STAGE_ERR_ARG;
   if (kind == 0 && (!mean || !db_part)) return STAGE_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = colsum_partial(st, (DType)dtype, T, H, dn, H, x, H, rstd, kind == 0 ? mean : nullptr, dg_part, nblk);
-  if (e == hipSuccess && kind == 0) e = colsum_partial(st, (DType)dtype, T, H, dn, H, nullptr, H, nullptr, nullptr, db_part, nblk);
-  if (e == hipSuccess) e = norm_bwd(st, (DType)dtype, kind, T, H, dn, x, g, rstd, mean, dres, dx);
-  return rc(e);
+  return rc(norm_bwd_partials(st, (DType)dtype, kind, T, H, dn, x, g, rstd, mean, dres, dx, dg_part, db_part, nblk));
 }
 
 int stage_op_rope(void* stream, int32_t dtype, int32_t T, int32_t S, int32_t ncols, int32_t d, void* a, int64_t ld,

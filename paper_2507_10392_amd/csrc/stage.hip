@@ -110,8 +110,9 @@ struct Bump {
   }
 };
 
-constexpr int MAX_NBLK = 128;
 
+
+constexpr int MAX_NBLK = 128;
 struct Plan {
   std::vector<LayerActs> acts;      // recompute ? 1 : M*L   (index mb*L + l)
   std::vector<char*> stash;         // recompute: M*L layer inputs
@@ -394,10 +395,10 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   if (gpt && !colsum(s, p + "b1", F, dff, F, nullptr, nullptr, nullptr)) return false;
 
   // second norm: gain (and bias) partials, dx2 = dy + norm'(x2)^T dn2
-  if (!colsum(s, p + (gpt ? "ln2.g" : "rms2.g"), H, pl.gN, H, A.x2, A.rstd2, A.mean2)) return false;
-  if (gpt && !colsum(s, p + "ln2.b", H, pl.gN, H, nullptr, nullptr, nullptr)) return false;
   if (!run(s, "norm_bwd", 0, 4 * thb, [&] {
-        return norm_bwd(s->st, dt, gpt ? 0 : 1, T, H, pl.gN, A.x2, gpt ? W("ln2.g") : W("rms2.g"), A.rstd2, A.mean2, dy, tmp); }))
+        return norm_bwd_partials(s->st, dt, gpt ? 0 : 1, T, H, pl.gN, A.x2, gpt ? W("ln2.g") : W("rms2.g"), A.rstd2,
+                                 A.mean2, dy, tmp, partial_of(s, p + (gpt ? "ln2.g" : "rms2.g")),
+                                 gpt ? partial_of(s, p + "ln2.b") : nullptr, s->plan.nblk); }))
     return false;
 
   // attention output projection: do = dx2 Wo^T ; dWo += o^T dx2
@@ -433,10 +434,10 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   if (gpt && !colsum(s, p + "bqkv", 3 * H, pl.gQKV, 3 * H, nullptr, nullptr, nullptr)) return false;
 
   // first norm: dx = dx2 + norm'(x)^T dn1
-  if (!colsum(s, p + (gpt ? "ln1.g" : "rms1.g"), H, pl.gN, H, x_in, A.rstd1, A.mean1)) return false;
-  if (gpt && !colsum(s, p + "ln1.b", H, pl.gN, H, nullptr, nullptr, nullptr)) return false;
   return run(s, "norm_bwd", 0, 4 * thb, [&] {
-    return norm_bwd(s->st, dt, gpt ? 0 : 1, T, H, pl.gN, x_in, gpt ? W("ln1.g") : W("rms1.g"), A.rstd1, A.mean1, tmp, dx); });
+    return norm_bwd_partials(s->st, dt, gpt ? 0 : 1, T, H, pl.gN, x_in, gpt ? W("ln1.g") : W("rms1.g"), A.rstd1, A.mean1,
+                             tmp, dx, partial_of(s, p + (gpt ? "ln1.g" : "rms1.g")),
+                             gpt ? partial_of(s, p + "ln1.b") : nullptr, s->plan.nblk); });
 }
 
 bool head_forward(stage_t* s, const char* y, HeadActs& A, const int32_t* targets, float* loss_out) {
@@ -468,9 +469,9 @@ bool head_backward(stage_t* s, const char* y, HeadActs& A, const int32_t* target
   g.M = h.T; g.N = h.H; g.K = h.V; g.A = A.logits; g.lda = h.V; g.B = s->P(s->seg_off("head.Wh")); g.ldb = h.V;
   g.transB = 1; g.C = pl.gN; g.ldc = h.H;
   if (!do_gemm(s, g)) return false;
-  if (!colsum(s, "final_norm.g", h.H, pl.gN, h.H, y, A.rstd, nullptr)) return false;
   return run(s, "norm_bwd", 0, 3.0 * h.T * h.H * h.E, [&] {
-    return norm_bwd(s->st, dt, 1, h.T, h.H, pl.gN, y, s->P(s->seg_off("final_norm.g")), A.rstd, nullptr, nullptr, dcur); });
+    return norm_bwd_partials(s->st, dt, 1, h.T, h.H, pl.gN, y, s->P(s->seg_off("final_norm.g")), A.rstd, nullptr, nullptr,
+                             dcur, partial_of(s, "final_norm.g"), nullptr, s->plan.nblk); });
 }
 
 bool check_slot(stage_t* s, int mb) { return mb >= 0 && mb < s->sh.M; }

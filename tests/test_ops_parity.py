@@ -141,9 +141,12 @@ def test_gemm_full_shape_sampled_outputs(gpu_device):
 
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("kind", [0, 1])
-@pytest.mark.parametrize("T,H", [(37, 256), (130, 640), (5, 8)])
-def test_norm_fwd_bwd(gpu_device, dtype, kind, T, H):
-    print(f"[case] norm kind={kind} dtype={dtype} T={T} H={H}", flush=True)
+# (T, H, blocks of the vector-gradient partials; 0 = rows/8); H = 64 lanes x vector x {1,2,4,8,10} selects the
+# register-resident kernels
+@pytest.mark.parametrize("T,H,nblk", [(37, 256, 7), (130, 640, 7), (5, 8, 5), (37, 512, 0), (130, 2048, 0), (61, 1024, 0),
+                                      (21, 5120, 0), (9, 4096, 0), (40, 2560, 0)])
+def test_norm_fwd_bwd(gpu_device, dtype, kind, T, H, nblk):
+    print(f"[case] norm kind={kind} dtype={dtype} T={T} H={H} nblk={nblk}", flush=True)
     rng = np.random.default_rng(3)
     x = draw(rng, (T, H), dtype, 2.0)
     g = draw(rng, (H,), dtype) + 1
@@ -166,7 +169,7 @@ def test_norm_fwd_bwd(gpu_device, dtype, kind, T, H):
     zs.ops.norm_fwd(st(), dtype, kind, T, H, dxd, dg_, db_ if kind == 0 else None, eps, n, rstd, mean if kind == 0 else None)
     assert rel_err(back(n), n_o) <= TOL[dtype]
     assert rel_err(back(rstd), cache[1][:, 0]) <= 2e-6
-    nblk = min(T, 7)
+    nblk = nblk or (T + 7) // 8
     dx = torch.empty(T, H, dtype=td, device="cuda")
     pg = torch.empty(nblk, H, device="cuda")
     pb = torch.empty(nblk, H, device="cuda")
