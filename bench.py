@@ -114,6 +114,9 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket launches with HIP events")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the microbatch loop of a step in a HIP graph and replay it (for launch-bound stages); "
+                         "per-kernel events are off in this mode")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a 1 GiB copy and the workload's weight-gradient GEMMs only (for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -161,15 +164,39 @@ def main():
     dxs = [None] * M if cfg.has_embed else [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
     stage = zs.Stage(cc, params, master, grad, m, v, ws)
 
-    def step(t):
+    def microbatches():
         for i in range(M):
             stage.forward(i, xs[i], ys[i], tgs[i], losses[i])
         for i in reversed(range(M)):
             stage.backward(i, dys[i], dxs[i], 1.0 / M)
             stage.accumulate(i)
+
+    graph = None
+
+    def step(t):
+        if graph is not None:
+            graph.replay()
+            stage.graph_replayed(M)
+        else:
+            microbatches()
         stage.optimizer_step(t)
 
     t = 0
+    if args.graph:
+        # one eager step configures every kernel; then the loop is captured on a side stream the stage is bound to
+        args.no_kernel_events = True
+        stage.close()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            stage = zs.Stage(cc, params, master, grad, m, v, ws, stream=side)
+            t += 1
+            step(t)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                microbatches()
+            graph = g
+        torch.cuda.set_stream(side)
     for _ in range(args.warmup):
         t += 1
         step(t)
@@ -233,7 +260,7 @@ def main():
         "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
         "mfu_model_flops": mfu, "hfu_executed_flops": mfu * (4.0 / 3.0 if cfg.recompute else 1.0),
         "model_tflop_per_step": mflops / 1e12, "finite": finite,
-        "roofline": roofline, "kernels": kernels,
+        "roofline": roofline, "kernels": kernels, "hip_graph": bool(args.graph),
     }
     if "adamw" in kernels:
         out["adamw_hbm_frac"] = kernels["adamw"].get("gbs", 0.0) / PEAK_HBM_GBS

@@ -134,6 +134,14 @@ int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float l
  * preceding stage_backward(mb) in a fixed order into grad_acc and releases slot mb. */
 int stage_accumulate(stage_t* s, int32_t mb);
 
+/* For callers that captured stage_forward / stage_backward / stage_accumulate calls of n_microbatches
+ * complete microbatches into a HIP graph on the stage's stream (the calls only enqueue kernels and one
+ * device-to-device copy, so they can be captured once the same sequence has run eagerly): after each
+ * replay of that graph, this call does the bookkeeping the captured calls did when they were recorded,
+ * so that stage_optimizer_step accepts the step.  Host side only, enqueues nothing.
+ * STAGE_ERR_STATE if an eagerly started microbatch is still outstanding. */
+int stage_graph_replayed(stage_t* stage, int32_t n_microbatches);
+
 /* AdamW step t (1-based) with decoupled weight decay on flat indices [shard_begin, shard_end):
  *   g' = grad_scale*g;  m = b1*m + (1-b1)*g';  v = b2*v + (1-b2)*g'^2;
  *   p = p - lr*( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd*p )

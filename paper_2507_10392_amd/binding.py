@@ -66,6 +66,7 @@ def lib():
         L.stage_backward.argtypes = [vp, i32, vp, vp, f32]
         L.stage_accumulate.argtypes = [vp, i32]
         L.stage_optimizer_step.argtypes = [vp, i64, f32]
+        L.stage_graph_replayed.argtypes = [vp, i32]
         L.stage_profile.argtypes = [vp, i32]
         L.stage_profile_read.argtypes = [vp, C.POINTER(StageKernelStatC), i32]
         L.stage_last_error.argtypes = [vp]
@@ -146,6 +147,9 @@ class Stage:
 
     def accumulate(self, mb):
         _check(lib().stage_accumulate(self.h, mb), self.h)
+
+    def graph_replayed(self, n_microbatches):
+        _check(lib().stage_graph_replayed(self.h, n_microbatches), self.h)
 
     def optimizer_step(self, t, grad_scale=1.0):
         _check(lib().stage_optimizer_step(self.h, t, grad_scale), self.h)

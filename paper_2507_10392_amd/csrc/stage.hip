@@ -658,6 +658,15 @@ int stage_accumulate(stage_t* s, int32_t mb) {
   return STAGE_OK;
 }
 
+int stage_graph_replayed(stage_t* s, int32_t n_microbatches) {
+  if (!s) return STAGE_ERR_ARG;
+  if (n_microbatches < 1 || n_microbatches > s->sh.M) return fail(s, STAGE_ERR_ARG, "n_microbatches must be in 1..max_microbatches");
+  if (s->pending >= 0 || s->outstanding != 0)
+    return fail(s, STAGE_ERR_STATE, "microbatches are still outstanding (forward without backward+accumulate)");
+  s->accumulated += n_microbatches;
+  return STAGE_OK;
+}
+
 int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale) {
   if (!s) return STAGE_ERR_ARG;
   if (t < 1) return fail(s, STAGE_ERR_ARG, "t is 1-based");

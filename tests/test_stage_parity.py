@@ -32,6 +32,23 @@ def test_stage_step_matches_oracle(gpu_device, name, perturbed):
     g.stage.close()
 
 
+@pytest.mark.parametrize("name,seq,mb", [("C3t", 200, 2), ("C5t", 72, 3), ("C2t", 136, 1)])
+def test_stage_step_with_ragged_sequence_lengths(gpu_device, name, seq, mb):
+    """Sequence lengths that are no multiple of the attention tiles (64 keys, 128 queries) and token counts
+    that are no multiple of the GEMM tiles, several sequences per microbatch: positions, causal masks and
+    the fused rotation must follow the sequence boundaries."""
+    cfg = get_config(name).with_(seq=seq, microbatch=mb, num_microbatches=3)
+    print(f"[case] ragged stage step {name} S={seq} mb={mb}", flush=True)
+    inp = make_inputs(cfg, perturbed=True)
+    g = GpuStage(cfg, inp)
+    gpu = g.run_microbatches(inp)
+    g.stage.close()
+    ora = oracle_step(cfg, inp)
+    rep = []
+    compare_step(cfg, gpu, ora, TOL[cfg.dtype], rep)
+    log_report(f"ragged stage step {name} S={seq} mb={mb}", sorted(rep, key=lambda r: -r[1])[:6])
+
+
 @pytest.mark.parametrize("name", ["C3t", "C5t", "C2t"])
 def test_recompute_is_result_neutral(gpu_device, name):
     """Per-layer checkpointing recomputes what it dropped (Section 4.1.3): same kernels, same inputs,
