@@ -114,6 +114,8 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket launches with HIP events")
+    ap.add_argument("--no-pair-wgrad", action="store_true",
+                    help="do not fold every other backward's weight-gradient products into the next one's (stage_config.pair_wgrad = 0)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the microbatch loop of a step in a HIP graph and replay it (for launch-bound stages); "
                          "per-kernel events are off in this mode")
@@ -132,7 +134,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    cfg = get_config(args.workload)
+    cfg = get_config(args.workload).with_(pair_wgrad=0 if args.no_pair_wgrad else 1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.traffic_probe:
@@ -259,7 +261,7 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers, hidden {cfg.hidden}, heads {cfg.heads}, ffn {cfg.ffn}, "
                                f"seq {cfg.seq}, microbatch {cfg.microbatch} x {M} microbatches, "
                                f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {e - b} of {P} params, "
-                               f"recompute {cfg.recompute}",
+                               f"recompute {cfg.recompute}, pair_wgrad {cfg.pair_wgrad}",
                    "tokens_per_step": tokens, "shard_elems": e - b},
         "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
         "mfu_model_flops": mfu, "hfu_executed_flops": mfu * (4.0 / 3.0 if cfg.recompute else 1.0),

@@ -38,6 +38,14 @@ int stage_op_gemm_rope(void* stream, int32_t dtype, int32_t transA, int32_t tran
                        int64_t sC, int64_t sBias, int32_t kseg, int64_t segB, int32_t impl, const float* rope_table,
                        int32_t rope_S, int32_t rope_d, int32_t rope_batches);
 
+/* Weight gradients of two microbatches in one product: C[M,N] (float) += A1^T B1 + A2^T B2 with A1 stored
+ * [K1,M], A2 [K2,M] (row stride lda), B1 [K1,N], B2 [K2,N] (row stride ldb); batch >= 1 with element strides
+ * sA, sB (applied to both parts) and sC.  impl as for stage_op_gemm; the MFMA kernel needs K1 to be a multiple
+ * of 64 (STAGE_ERR_ARG otherwise when it is forced), impl 0 falls back to two plain products. */
+int stage_op_wgrad_pair(void* stream, int32_t dtype, int32_t M, int32_t N, int32_t K1, int32_t K2, const void* A1,
+                        const void* A2, int64_t lda, const void* B1, const void* B2, int64_t ldb, float* C, int64_t ldc,
+                        int32_t batch, int64_t sA, int64_t sB, int64_t sC, int32_t impl);
+
 /* kind 0: LayerNorm n = (x-mean)/sqrt(var+eps)*g + b (biased variance), saves rstd[T], mean[T].
  * kind 1: RMSNorm n = x/sqrt(mean(x^2)+eps)*g, saves rstd[T].  x, n: [T,H]. */
 int stage_op_norm_fwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* x, const void* g,

@@ -28,7 +28,7 @@ class StageConfigC(C.Structure):
     _fields_ = [("arch", C.c_int32), ("dtype", C.c_int32), ("layers", C.c_int32), ("hidden", C.c_int32),
                 ("heads", C.c_int32), ("ffn", C.c_int32), ("seq", C.c_int32), ("microbatch", C.c_int32),
                 ("max_microbatches", C.c_int32), ("vocab", C.c_int32), ("has_embed", C.c_int32),
-                ("has_head", C.c_int32), ("recompute", C.c_int32), ("reserved0", C.c_int32),
+                ("has_head", C.c_int32), ("recompute", C.c_int32), ("pair_wgrad", C.c_int32),
                 ("act_budget_bytes", C.c_int64), ("shard_begin", C.c_int64), ("shard_end", C.c_int64),
                 ("norm_eps", C.c_float), ("rope_base", C.c_float), ("lr", C.c_float), ("beta1", C.c_float),
                 ("beta2", C.c_float), ("adam_eps", C.c_float), ("weight_decay", C.c_float), ("reserved1", C.c_float)]
@@ -77,6 +77,7 @@ def lib():
                                     i64, i64, i64, i64, i32, i64, i32]
         L.stage_op_gemm_rope.argtypes = L.stage_op_gemm.argtypes + [vp, i32, i32, i32]
         L.stage_op_rope_table.argtypes = [vp, i32, i32, f32, vp]
+        L.stage_op_wgrad_pair.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, vp, i64, vp, i64, i32, i64, i64, i64, i32]
         L.stage_op_norm_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, f32, vp, vp, vp]
         L.stage_op_norm_bwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32]
         L.stage_op_rope.argtypes = [vp, i32, i32, i32, i32, i32, vp, i64, f32, f32, vp]
@@ -98,7 +99,8 @@ def make_config(cfg, shard=None, max_microbatches=None) -> StageConfigC:
     b, e = cfg.shard_range if shard is None else shard
     return StageConfigC(cfg.arch, cfg.dtype, cfg.layers, cfg.hidden, cfg.heads, cfg.ffn, cfg.seq, cfg.microbatch,
                         cfg.num_microbatches if max_microbatches is None else max_microbatches, cfg.vocab,
-                        cfg.has_embed, cfg.has_head, cfg.recompute, 0, cfg.act_budget_bytes, b, e, cfg.norm_eps,
+                        cfg.has_embed, cfg.has_head, cfg.recompute, int(getattr(cfg, "pair_wgrad", 0)), cfg.act_budget_bytes, b, e,
+                        cfg.norm_eps,
                         cfg.rope_base, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay, 0.0)
 
 

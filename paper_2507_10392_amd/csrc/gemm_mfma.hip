@@ -23,7 +23,10 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
   if (g.K % 8) return false;                       // k-contiguous operands are read 8 k at a time; tails are zero-filled
   if (g.transA && g.M % 8) return false;           // row-contiguous operands are read 8 rows at a time
   if (!g.transB && g.N % 8) return false;
-  if (g.kseg) {
+  if (g.A2) {   // two-part K range of an accumulating product
+    if (!g.transA || g.transB || !g.c_f32_accum || !g.B2 || g.kseg <= 0 || g.kseg >= g.K || g.kseg % 64) return false;
+    if (!aligned16(g.A2) || !aligned16(g.B2)) return false;
+  } else if (g.kseg) {
     if (!g.transB || g.kseg % 8 || g.segB % 8 || g.K % g.kseg) return false;
   }
   // the bf16 epilogue moves 8 consecutive columns per 16-byte access

@@ -289,22 +289,35 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   Frag<BM, NT> fa0, fa1;
   Frag<BN, NT> fb0, fb1;
   const int lda = (int)g.lda, ldb = (int)g.ldb;
+  // PAIR: K rows [0, kseg) come from A, B and rows [kseg, K) from A2, B2 (both operands row-contiguous)
+  constexpr bool PAIR = SEG && TA == 1 && TB == 0;
+  const int K1 = PAIR ? g.kseg : g.K;                    // rows of the first (or only) part
   const __amdgpu_buffer_rsrc_t rsA =
-      make_rsrc(A, (uint32_t)(TA == 0 ? ((int64_t)(g.M - 1) * lda + g.K) : ((int64_t)(g.K - 1) * lda + g.M)) * 2u);
-  const int nseg = SEG ? g.K / g.kseg : 1;
+      make_rsrc(A, (uint32_t)(TA == 0 ? ((int64_t)(g.M - 1) * lda + g.K) : ((int64_t)(K1 - 1) * lda + g.M)) * 2u);
+  const int nseg = (SEG && !PAIR) ? g.K / g.kseg : 1;
   const __amdgpu_buffer_rsrc_t rsB = make_rsrc(
       B, (uint32_t)(TB == 1 ? ((int64_t)(nseg - 1) * g.segB + (int64_t)(g.N - 1) * ldb + (SEG ? g.kseg : g.K))
-                            : ((int64_t)(g.K - 1) * ldb + g.N)) * 2u);
+                            : ((int64_t)(K1 - 1) * ldb + g.N)) * 2u);
+  const __amdgpu_buffer_rsrc_t rsA2 =
+      PAIR ? make_rsrc((const bf16*)g.A2 + (int64_t)z * g.sA, (uint32_t)((int64_t)(g.K - K1 - 1) * lda + g.M) * 2u) : rsA;
+  const __amdgpu_buffer_rsrc_t rsB2 =
+      PAIR ? make_rsrc((const bf16*)g.B2 + (int64_t)z * g.sB, (uint32_t)((int64_t)(g.K - K1 - 1) * ldb + g.N) * 2u) : rsB;
   const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : voff_rmajor<BM>(lda, tid, m0, g.M);
   const int voffB = TB == 1 ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2 : voff_rmajor<BN>(ldb, tid, n0, g.N);
 
   auto fetch = [&](int kt, Frag<BM, NT>& fa0, Frag<BN, NT>& fb0) {
     const int k0 = kt * BK;
+    if (PAIR) {   // a slab lies in one part (kseg is a multiple of the slab); rows past a part's end are out of its range
+      const bool second = k0 >= K1;
+      load_rmajor<BM, NT>(fa0, second ? rsA2 : rsA, voffA, lda, m0, second ? k0 - K1 : k0);
+      load_rmajor<BN, NT>(fb0, second ? rsB2 : rsB, voffB, ldb, n0, second ? k0 - K1 : k0);
+      return;
+    }
     if (TA == 0) load_kmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0, g.K, tid);
     else load_rmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0);
     if (TB == 1) {
       int vo = voffB;
-      if (SEG) {  // the thread's k offset inside the slab is fixed, so one segment lookup per slab
+      if (SEG && !PAIR) {  // the thread's k offset inside the slab is fixed, so one segment lookup per slab
         const int seg = (k0 + (tid & 7) * 8) / g.kseg;
         vo += seg * ((int)g.segB - g.kseg) * 2;          // element (n, k) of segment seg lies at seg*segB + n*ldb + k - seg*kseg
       }
@@ -387,6 +400,7 @@ template <int BM, int BN, int NW, int TA, int TB, int SEG> hipError_t launch(hip
 }
 
 template <int BM, int BN, int NW> hipError_t gemm_mfma_tile(hipStream_t st, const Gemm& g) {
+  if (g.A2) return launch<BM, BN, NW, 1, 0, 1>(st, g);
   if (g.kseg) return g.transA ? launch<BM, BN, NW, 1, 1, 1>(st, g) : launch<BM, BN, NW, 0, 1, 1>(st, g);
   if (!g.transA && !g.transB) return launch<BM, BN, NW, 0, 0, 0>(st, g);
   if (!g.transA && g.transB) return launch<BM, BN, NW, 0, 1, 0>(st, g);

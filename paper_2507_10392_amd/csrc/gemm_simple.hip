@@ -109,6 +109,13 @@ int gemm_select(DType dt, const Gemm& g, int force) {
 
 hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
   if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, g);   // rotation fused into its epilogue
+  if (g.A2) {   // two-part K range: one plain product per part
+    Gemm a = g, b = g;
+    a.A2 = a.B2 = nullptr; a.K = g.kseg; a.kseg = 0;
+    b.A = g.A2; b.B = g.B2; b.A2 = b.B2 = nullptr; b.K = g.K - g.kseg; b.kseg = 0;
+    const hipError_t e2 = gemm_simple(st, dt, a);
+    return e2 != hipSuccess ? e2 : gemm_simple(st, dt, b);
+  }
   hipError_t e = gemm_simple(st, dt, g);
   const int elem = dt == F32 ? 4 : 2;
   for (int z = 0; e == hipSuccess && g.rope && z < g.rope_batches && z < g.batch; ++z)

@@ -39,6 +39,22 @@ int stage_op_gemm_rope(void* stream, int32_t dtype, int32_t transA, int32_t tran
   return rc(e);
 }
 
+int stage_op_wgrad_pair(void* stream, int32_t dtype, int32_t M, int32_t N, int32_t K1, int32_t K2, const void* A1,
+                        const void* A2, int64_t lda, const void* B1, const void* B2, int64_t ldb, float* C, int64_t ldc,
+                        int32_t batch, int64_t sA, int64_t sB, int64_t sC, int32_t impl) {
+  if (!dt_ok(dtype) || M < 1 || N < 1 || K1 < 1 || K2 < 1 || batch < 1 || !A1 || !A2 || !B1 || !B2 || !C) return STAGE_ERR_ARG;
+  if (impl < 0 || impl > 4) return STAGE_ERR_ARG;
+  Gemm g;
+  g.M = M; g.N = N; g.K = K1 + K2; g.transA = 1; g.transB = 0; g.A = A1; g.lda = lda; g.B = B1; g.ldb = ldb;
+  g.C = C; g.ldc = ldc; g.c_f32_accum = 1; g.batch = batch; g.sA = sA; g.sB = sB; g.sC = sC;
+  g.A2 = A2; g.B2 = B2; g.kseg = K1;
+  if (impl >= GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
+  if (impl > GEMM_MFMA) gemm_mfma_force_tile(impl - GEMM_MFMA);
+  const hipError_t e = gemm((hipStream_t)stream, (DType)dtype, g, impl > GEMM_MFMA ? GEMM_MFMA : impl);
+  gemm_mfma_force_tile(0);
+  return rc(e);
+}
+
 int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
                   const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
                   const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,

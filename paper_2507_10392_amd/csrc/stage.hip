@@ -22,7 +22,7 @@ struct Seg { std::string name; int64_t off, rows, cols; };
 
 struct Shape {
   int arch, L, H, nh, d, F, S, mb, T, M, V;
-  bool bf, embed, head, recompute;
+  bool bf, embed, head, recompute, pair;
   int64_t E;  // bytes per element
 };
 
@@ -32,6 +32,9 @@ Shape shape_of(const stage_config& c) {
   s.F = c.ffn; s.S = c.seq; s.mb = c.microbatch; s.T = c.seq * c.microbatch; s.M = c.max_microbatches;
   s.V = c.vocab; s.bf = c.dtype == STAGE_DTYPE_BF16; s.embed = c.has_embed != 0; s.head = c.has_head != 0;
   s.recompute = c.recompute != 0; s.E = s.bf ? 2 : 4;
+  // weight gradients of two microbatches in one product: needs the first one's activations to stay (no
+  // recompute), a second microbatch to pair with, and the part boundary on a K slab of the MFMA kernel
+  s.pair = c.pair_wgrad != 0 && !s.recompute && s.M >= 2 && s.T % 64 == 0;
   return s;
 }
 
@@ -121,6 +124,7 @@ struct Plan {
   std::vector<int32_t*> ids, targets;  // per slot copies
   // scratch
   char *gA, *gB, *gN, *gO, *gQKV, *gF1, *ytmp;
+  std::vector<char*> kdy, kdx2, kdqkv;   // pair_wgrad: per layer, the deferred microbatch's dy, dx2 and dqkv
   float* delta; float* lossdump;
   float2* rope;
   float* partials; int64_t partial_floats;
@@ -192,6 +196,10 @@ void make_plan(const stage_config& c, char* base, Plan& p) {
   p.gQKV = b.take(3 * TH);
   p.gF1 = b.take((int64_t)s.T * s.F * s.E);
   p.ytmp = b.take(TH);
+  if (s.pair) {
+    p.kdy.resize(s.L); p.kdx2.resize(s.L); p.kdqkv.resize(s.L);
+    for (int l = 0; l < s.L; ++l) { p.kdy[l] = b.take(TH); p.kdx2[l] = b.take(TH); p.kdqkv[l] = b.take(3 * TH); }
+  }
   p.delta = b.take<float>(4ll * s.mb * s.nh * s.S);
   p.lossdump = b.take<float>(256);
   p.rope = s.arch == STAGE_ARCH_LLAMA ? b.take<float2>(8ll * s.S * (s.d / 2)) : nullptr;
@@ -230,6 +238,7 @@ struct stage {
   std::vector<int> slot;     // 0 empty, 1 forwarded, 2 backward done (waiting for accumulate)
   int pending = -1;          // slot whose backward waits for stage_accumulate
   int outstanding = 0, accumulated = 0;
+  int deferred = -1;         // pair_wgrad: slot whose weight-gradient products wait for the next backward
   std::vector<ReduceJob> jobs_host;
   int njobs = 0, max_job_width = 0;
   std::string err;
@@ -352,7 +361,16 @@ bool colsum(stage_t* s, const std::string& seg, int N, const void* a, int64_t ld
 
 // ---- backward of one layer ----------------------------------------------------------------------
 // dy -> dx.  dy and dx are distinct [T,H] buffers; tmp is a third one (holds dx2).
-bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const char* dy, char* tmp, char* dx) {
+// Weight-gradient products of a layer: done now (mode 0), left for later (1: this microbatch's operands
+// stay where they are), or done for this microbatch and a deferred one in one product (2).
+struct WgradPlan {
+  int mode = 0;
+  const LayerActs* A2 = nullptr;                          // mode 2: the deferred microbatch's activations ...
+  const char *dy2 = nullptr, *dx2_2 = nullptr, *dqkv2 = nullptr;   // ... and its dy, dx2, dqkv of this layer
+};
+
+bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const char* dy, char* tmp, char* dx, char* gqkv,
+                    const WgradPlan& wg) {
   const Shape& h = s->sh;
   const DType dt = dt_of(s);
   const int T = h.T, H = h.H, F = h.F;
@@ -363,6 +381,12 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   auto W = [&](const char* n) { return s->P(s->seg_off(p + n)); };
   auto GW = [&](const char* n) { return s->G(s->seg_off(p + n)); };
   Gemm g;
+  // dW += X^T dY over this microbatch's tokens, and over the deferred microbatch's too when there is one
+  auto wgrad = [&](Gemm w, const void* x2, const void* dy2) {
+    if (wg.mode == 1) return true;
+    if (wg.mode == 2) { w.A2 = x2; w.B2 = dy2; w.kseg = T; w.K = 2 * T; }
+    return do_gemm(s, w);
+  };
 
   // FFN down projection: da = dy Wd^T ; dWd += a^T dy
   g.M = T; g.N = F; g.K = H; g.A = dy; g.lda = H; g.B = gpt ? W("W2") : W("Wd"); g.ldb = H; g.transB = 1;
@@ -371,7 +395,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   g = Gemm();
   g.M = F; g.N = H; g.K = T; g.A = A.a; g.lda = F; g.transA = 1; g.B = dy; g.ldb = H;
   g.C = gpt ? GW("W2") : GW("Wd"); g.ldc = H; g.c_f32_accum = 1;
-  if (!do_gemm(s, g)) return false;
+  if (!wgrad(g, wg.A2 ? wg.A2->a : nullptr, wg.dy2)) return false;
   if (gpt && !colsum(s, p + "b2", H, dy, H, nullptr, nullptr, nullptr)) return false;
 
   // activation backward, in place over the saved pre-activations
@@ -391,7 +415,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   g.M = H; g.N = F; g.K = T; g.A = A.n2; g.lda = H; g.transA = 1; g.B = dff; g.c_f32_accum = 1; g.ldc = F;
   if (gpt) { g.ldb = F; g.C = GW("W1"); }
   else { g.ldb = 2 * F; g.C = GW("Wg"); g.batch = 2; g.sB = F; g.sC = (int64_t)H * F; }
-  if (!do_gemm(s, g)) return false;
+  if (!wgrad(g, wg.A2 ? wg.A2->n2 : nullptr, wg.A2 ? wg.A2->ff : nullptr)) return false;
   if (gpt && !colsum(s, p + "b1", F, dff, F, nullptr, nullptr, nullptr)) return false;
 
   // second norm: gain (and bias) partials, dx2 = dy + norm'(x2)^T dn2
@@ -408,7 +432,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   g = Gemm();
   g.M = H; g.N = H; g.K = T; g.A = A.o; g.lda = H; g.transA = 1; g.B = tmp; g.ldb = H; g.C = GW("Wo"); g.ldc = H;
   g.c_f32_accum = 1;
-  if (!do_gemm(s, g)) return false;
+  if (!wgrad(g, wg.A2 ? wg.A2->o : nullptr, wg.dx2_2)) return false;
   if (gpt && !colsum(s, p + "bo", H, tmp, H, nullptr, nullptr, nullptr)) return false;
 
   // attention backward (+ inverse rotation of dq, dk)
@@ -417,21 +441,21 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   const int64_t HE = (int64_t)H * h.E;
   if (!run(s, attn_select(dt, h.S, h.d, 0) == ATTN_MFMA ? "attn_bwd_mfma" : "attn_bwd_simple", attn_flops, 0, [&] {
         return attn_bwd(s->st, dt, h.mb, h.S, h.nh, h.d, A.qkv, A.qkv + HE, A.qkv + 2 * HE, 3 * H, A.o, pl.gO, H, A.lse,
-                        pl.delta, pl.gQKV, pl.gQKV + HE, pl.gQKV + 2 * HE, 3 * H, gpt ? nullptr : pl.rope, ATTN_AUTO); }))
+                        pl.delta, gqkv, gqkv + HE, gqkv + 2 * HE, 3 * H, gpt ? nullptr : pl.rope, ATTN_AUTO); }))
     return false;
 
   // QKV projection: dn1 = dqkv [Wq|Wk|Wv]^T ; dW += n1^T dqkv
   g = Gemm();
-  g.M = T; g.N = H; g.K = 3 * H; g.A = pl.gQKV; g.lda = 3 * H; g.transB = 1; g.C = pl.gN; g.ldc = H;
+  g.M = T; g.N = H; g.K = 3 * H; g.A = gqkv; g.lda = 3 * H; g.transB = 1; g.C = pl.gN; g.ldc = H;
   if (gpt) { g.B = W("Wqkv"); g.ldb = 3 * H; }
   else { g.B = W("Wq"); g.ldb = H; g.kseg = H; g.segB = (int64_t)H * H; }
   if (!do_gemm(s, g)) return false;
   g = Gemm();
-  g.M = H; g.K = T; g.A = A.n1; g.lda = H; g.transA = 1; g.B = pl.gQKV; g.ldb = 3 * H; g.c_f32_accum = 1;
+  g.M = H; g.K = T; g.A = A.n1; g.lda = H; g.transA = 1; g.B = gqkv; g.ldb = 3 * H; g.c_f32_accum = 1;
   if (gpt) { g.N = 3 * H; g.C = GW("Wqkv"); g.ldc = 3 * H; }
   else { g.N = H; g.C = GW("Wq"); g.ldc = H; g.batch = 3; g.sB = H; g.sC = (int64_t)H * H; }
-  if (!do_gemm(s, g)) return false;
-  if (gpt && !colsum(s, p + "bqkv", 3 * H, pl.gQKV, 3 * H, nullptr, nullptr, nullptr)) return false;
+  if (!wgrad(g, wg.A2 ? wg.A2->n1 : nullptr, wg.dqkv2)) return false;
+  if (gpt && !colsum(s, p + "bqkv", 3 * H, gqkv, 3 * H, nullptr, nullptr, nullptr)) return false;
 
   // first norm: dx = dx2 + norm'(x)^T dn1
   return run(s, "norm_bwd", 0, 4 * thb, [&] {
@@ -475,6 +499,41 @@ bool head_backward(stage_t* s, const char* y, HeadActs& A, const int32_t* target
 }
 
 bool check_slot(stage_t* s, int mb) { return mb >= 0 && mb < s->sh.M; }
+
+// The weight-gradient products of the deferred microbatch on their own (its slot is about to be reused, or
+// the step ends).
+bool flush_deferred(stage_t* s) {
+  if (s->deferred < 0) return true;
+  const Shape& h = s->sh;
+  Plan& pl = s->plan;
+  const int T = h.T, H = h.H, F = h.F;
+  const bool gpt = h.arch == STAGE_ARCH_GPT;
+  for (int l = h.L - 1; l >= 0; --l) {
+    const LayerActs& A = pl.acts[(size_t)s->deferred * h.L + l];
+    const std::string p = "L" + std::to_string(l) + ".";
+    auto GW = [&](const char* n) { return s->G(s->seg_off(p + n)); };
+    Gemm g;
+    g.M = F; g.N = H; g.K = T; g.A = A.a; g.lda = F; g.transA = 1; g.B = pl.kdy[l]; g.ldb = H;
+    g.C = gpt ? GW("W2") : GW("Wd"); g.ldc = H; g.c_f32_accum = 1;
+    if (!do_gemm(s, g)) return false;
+    g = Gemm();
+    g.M = H; g.N = F; g.K = T; g.A = A.n2; g.lda = H; g.transA = 1; g.B = A.ff; g.c_f32_accum = 1; g.ldc = F;
+    if (gpt) { g.ldb = F; g.C = GW("W1"); }
+    else { g.ldb = 2 * F; g.C = GW("Wg"); g.batch = 2; g.sB = F; g.sC = (int64_t)H * F; }
+    if (!do_gemm(s, g)) return false;
+    g = Gemm();
+    g.M = H; g.N = H; g.K = T; g.A = A.o; g.lda = H; g.transA = 1; g.B = pl.kdx2[l]; g.ldb = H; g.C = GW("Wo"); g.ldc = H;
+    g.c_f32_accum = 1;
+    if (!do_gemm(s, g)) return false;
+    g = Gemm();
+    g.M = H; g.K = T; g.A = A.n1; g.lda = H; g.transA = 1; g.B = pl.kdqkv[l]; g.ldb = 3 * H; g.c_f32_accum = 1;
+    if (gpt) { g.N = 3 * H; g.C = GW("Wqkv"); g.ldc = 3 * H; }
+    else { g.N = H; g.C = GW("Wq"); g.ldc = H; g.batch = 3; g.sB = H; g.sC = (int64_t)H * H; }
+    if (!do_gemm(s, g)) return false;
+  }
+  s->deferred = -1;
+  return true;
+}
 
 }  // namespace
 
@@ -571,6 +630,7 @@ int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, con
   if (!h.head && !y_out) return fail(s, STAGE_ERR_ARG, "y_out is NULL");
   if (s->pending >= 0) return fail(s, STAGE_ERR_STATE, "a backward is waiting for stage_accumulate");
   if (s->slot[mb] != 0) return fail(s, STAGE_ERR_STATE, "slot already holds a forward that was not backpropagated");
+  if (s->deferred == mb && !flush_deferred(s)) return STAGE_ERR_DEVICE;   // its activations are about to be overwritten
   Plan& pl = s->plan;
   const DType dt = dt_of(s);
   const int64_t TH = (int64_t)h.T * h.H * h.E;
@@ -615,24 +675,41 @@ int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float l
   const int64_t TH = (int64_t)h.T * h.H * h.E;
 
   auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)mb * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
+  // pair_wgrad: a backward with further backwards to come leaves its weight-gradient products to the next
+  // one and keeps their dY operands in per-layer buffers; the next one multiplies for both.
+  const bool fuse = h.pair && s->deferred >= 0;
+  const bool defer = h.pair && !fuse && s->outstanding > 1;
   // cur: gradient entering the layer (never written); its dx goes to the other scratch buffer
-  const char* cur = h.head ? pl.gA : (const char*)dy;
+  char* top = defer ? pl.kdy[h.L - 1] : pl.gA;
+  const char* cur = h.head ? top : (const char*)dy;
   char* bufs[2] = {pl.gB, pl.gA};
   int bi = 0;
   if (h.head) {
     char* final_y = h.recompute ? pl.hstash[mb] : pl.hacts[mb].y;
     HeadActs& HA = h.recompute ? pl.hacts[0] : pl.hacts[mb];
     if (h.recompute && !head_forward(s, final_y, HA, pl.targets[mb], pl.lossdump)) return STAGE_ERR_DEVICE;
-    if (!head_backward(s, final_y, HA, pl.targets[mb], loss_scale, pl.gA)) return STAGE_ERR_DEVICE;
+    if (!head_backward(s, final_y, HA, pl.targets[mb], loss_scale, top)) return STAGE_ERR_DEVICE;
+  } else if (defer) {   // the caller's dy may be gone by the time the deferred products run
+    if (!run(s, "copy", 0, 2.0 * TH, [&] { return copy_bytes(s->st, top, dy, TH); })) return STAGE_ERR_DEVICE;
+    cur = top;
   }
   for (int l = h.L - 1; l >= 0; --l) {
     LayerActs& A = h.recompute ? pl.acts[0] : pl.acts[(size_t)mb * h.L + l];
     if (h.recompute && !layer_forward(s, l, in_of(l), A, nullptr)) return STAGE_ERR_DEVICE;
-    char* dst = (l == 0 && !h.embed) ? (char*)dx_out : bufs[bi];
-    if (!layer_backward(s, l, in_of(l), A, cur, pl.ytmp, dst)) return STAGE_ERR_DEVICE;
+    char* dst = (l == 0 && !h.embed) ? (char*)dx_out : (defer && l > 0) ? pl.kdy[l - 1] : bufs[bi];
+    WgradPlan wg;
+    if (defer) wg.mode = 1;
+    if (fuse) {
+      wg.mode = 2; wg.A2 = &pl.acts[(size_t)s->deferred * h.L + l];
+      wg.dy2 = pl.kdy[l]; wg.dx2_2 = pl.kdx2[l]; wg.dqkv2 = pl.kdqkv[l];
+    }
+    if (!layer_backward(s, l, in_of(l), A, cur, defer ? pl.kdx2[l] : pl.ytmp, dst, defer ? pl.kdqkv[l] : pl.gQKV, wg))
+      return STAGE_ERR_DEVICE;
     cur = dst;
     bi ^= 1;
   }
+  if (fuse) s->deferred = -1;
+  if (defer) s->deferred = mb;
   if (h.embed) {
     // cur now holds the gradient of the embedding output
     if (!run(s, "embed", 0, 3.0 * TH, [&] {
@@ -673,6 +750,7 @@ int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale) {
   if (s->pending >= 0 || s->outstanding != 0)
     return fail(s, STAGE_ERR_STATE, "microbatches are still outstanding (forward without backward+accumulate)");
   if (s->accumulated == 0) return fail(s, STAGE_ERR_STATE, "no microbatch was accumulated since the last step");
+  if (!flush_deferred(s)) return STAGE_ERR_DEVICE;
   const stage_config& c = s->cfg;
   AdamW h;
   h.lr = c.lr; h.beta1 = c.beta1; h.beta2 = c.beta2; h.eps = c.adam_eps; h.wd = c.weight_decay;

@@ -276,6 +276,30 @@ def test_attention_fwd_bwd(gpu_device, mb, S, nh, d, dtype, impl):
         assert e <= (2e-2 if dtype else 5e-5), n
 
 
+@pytest.mark.parametrize("impl", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("shape", [(296, 520, 128, 72, 2), (256, 256, 64, 64, 1), (1000, 40, 1024, 200, 1), (304, 264, 100, 64, 1)])
+def test_weight_gradient_of_two_microbatches(gpu_device, dtype, impl, shape):
+    """C += A1^T B1 + A2^T B2 in one product over both parts' rows, against float64."""
+    M, N, K1, K2, batch = shape
+    if impl >= 2 and (dtype == 0 or K1 % 64):
+        pytest.skip("the MFMA kernel is bf16 only and needs the first part to be a multiple of 64 rows")
+    print(f"[case] wgrad pair {shape} dtype={dtype} impl={impl}", flush=True)
+    rng = np.random.default_rng(41)
+    td = TD[dtype]
+    A1, A2 = draw(rng, (K1, M), dtype), draw(rng, (K2, M), dtype)
+    B1, B2 = draw(rng, (K1, N * batch), dtype, 0.05), draw(rng, (K2, N * batch), dtype, 0.05)
+    C0 = rng.standard_normal((batch, M, N)).astype(np.float32)
+    want = np.stack([C0[z] + A1.astype(np.float64).T @ B1[:, z * N:(z + 1) * N].astype(np.float64)
+                     + A2.astype(np.float64).T @ B2[:, z * N:(z + 1) * N].astype(np.float64) for z in range(batch)])
+    C = dev(C0)
+    zs.ops.wgrad_pair(st(), dtype, M, N, K1, K2, dev(A1, td), dev(A2, td), M, dev(B1, td), dev(B2, td), N * batch, C, N, batch,
+                      0, N, M * N, impl)
+    err = rel_err(back(C), want)
+    log_report(f"wgrad pair {shape} dtype={dtype} impl={impl}", [("C", err)])
+    assert err <= 2e-5
+
+
 @pytest.mark.parametrize("impl", [1, 2, 3, 4])
 @pytest.mark.parametrize("dtype", [0, 1])
 def test_gemm_with_fused_rotation(gpu_device, dtype, impl):

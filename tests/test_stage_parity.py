@@ -49,6 +49,60 @@ def test_stage_step_with_ragged_sequence_lengths(gpu_device, name, seq, mb):
     log_report(f"ragged stage step {name} S={seq} mb={mb}", sorted(rep, key=lambda r: -r[1])[:6])
 
 
+@pytest.mark.parametrize("name,M", [("C3t", 16), ("C3t", 3), ("C2t", 8), ("C5t", 5), ("C4at", 2)])
+def test_paired_weight_gradients_match_oracle(gpu_device, name, M):
+    """pair_wgrad = 1: every other backward leaves its weight-gradient products to the next one, which runs them
+    over both microbatches' tokens.  Same sums, so the accumulated gradient and everything else must match
+    the oracle as before, for even and odd numbers of microbatches."""
+    cfg = get_config(name).with_(num_microbatches=M, pair_wgrad=1)
+    print(f"[case] paired wgrad {name} M={M}", flush=True)
+    inp = make_inputs(cfg, perturbed=True)
+    g = GpuStage(cfg, inp)
+    gpu = g.run_microbatches(inp)
+    ora = oracle_step(cfg, inp)
+    rep = []
+    compare_step(cfg, gpu, ora, TOL[cfg.dtype], rep)
+    log_report(f"paired wgrad {name} M={M}", sorted(rep, key=lambda r: -r[1])[:6])
+    res = g.step(1)
+    compare_optimizer(cfg, inp, g.shard, gpu["grad"], res, ora["grad"], TOL[cfg.dtype])
+    g.stage.close()
+
+
+def test_paired_weight_gradients_with_interleaved_calls(gpu_device):
+    """Orders other than all-forwards-then-all-backwards: a deferred microbatch whose slot is reused is flushed
+    first, a backward with nothing else outstanding is not deferred, and the sum is the same."""
+    cfg = get_config("C3t").with_(num_microbatches=4, pair_wgrad=1)
+    print("[case] paired wgrad, interleaved order", flush=True)
+    inp = make_inputs(cfg, perturbed=True)
+    td = torch.bfloat16
+    T, H = cfg.tokens, cfg.hidden
+    g = GpuStage(cfg, inp)
+    x = [torch.from_numpy(np.ascontiguousarray(inp.x[i])).cuda().to(td) for i in range(4)]
+    dy = [torch.from_numpy(np.ascontiguousarray(inp.dy[i])).cuda().to(td) for i in range(4)]
+    y = [torch.empty(T, H, dtype=td, device="cuda") for _ in range(4)]
+    dx = [torch.empty(T, H, dtype=td, device="cuda") for _ in range(4)]
+    st = g.stage
+    fwd = lambda slot, i: st.forward(slot, x[i], y[i], None, None)
+    def bwd(slot, i):
+        st.backward(slot, dy[i], dx[i], 1.0)
+        st.accumulate(slot)
+    fwd(0, 0); fwd(1, 1)
+    bwd(1, 1)            # deferred (microbatch 0 is still outstanding)
+    fwd(1, 2)            # reuses the deferred slot: its products run now
+    bwd(1, 2)            # deferred again
+    fwd(2, 3)
+    bwd(2, 3)            # runs for microbatches 2 and 3
+    bwd(0, 0)            # nothing else outstanding: not deferred
+    torch.cuda.synchronize()
+    ora = oracle_step(cfg, inp)
+    err = float(np.abs(g.grad.cpu().numpy().astype(np.float64) - ora["grad"]).max() / np.abs(ora["grad"]).max())
+    log_report("paired wgrad, interleaved order", [("grad", err)])
+    assert err <= TOL[cfg.dtype]
+    for i in range(4):
+        assert float(np.abs(dx[i].float().cpu().numpy() - ora["dx"][i]).max() / np.abs(ora["dx"][i]).max()) <= TOL[cfg.dtype]
+    st.close()
+
+
 @pytest.mark.parametrize("name", ["C3t", "C5t", "C2t"])
 def test_recompute_is_result_neutral(gpu_device, name):
     """Per-layer checkpointing recomputes what it dropped (Section 4.1.3): same kernels, same inputs,
