@@ -29,8 +29,11 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM-side bytes per launch of a workload's dominant kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of `bench.py --traffic-probe`, each counter scaled by what it reads for a copy of known size
-# (profiles/gemm_wgrad_C3_hbm_traffic.txt).  Workloads that were not measured report null.
-MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn"): 1092.8e6}
+# (profiles/gemm_wgrad_C3_hbm_traffic.txt), and, for the paired launches (pair_wgrad = 1: two microbatches'
+# tokens per launch), from the same counters over one step of this file
+# (profiles/stage_step_C3_mfma_busy_hbm_bytes.txt).  Keys: workload, kernel class, pair_wgrad.  Workloads that
+# were not measured report null.
+MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 1): 1781.2e6}
 
 
 def model_flops_per_step(cfg):
@@ -251,7 +254,7 @@ def main():
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k.get("gbs", 0.0), "peak": PEAK_HBM_GBS,
                         "unit": "GB/s", "frac": k.get("gbs", 0.0) / PEAK_HBM_GBS}
         roofline["avg_launch_ms"] = k["avg_ms"]
-        roofline["traffic"] = MEASURED_TRAFFIC.get((args.workload, dom))
+        roofline["traffic"] = MEASURED_TRAFFIC.get((args.workload, dom, int(cfg.pair_wgrad)))
 
     out = {
         "metric": "stage train tokens/s on 1 MI355X (fwd+bwd+AdamW); MFMA util % of bf16 peak",
