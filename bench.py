@@ -58,11 +58,12 @@ def fill_params(cfg, params, torch):
             seg.zero_()
 
 
-def cpu_baseline(cfg):
-    """The oracle as it stands, on the host cores: ONE decoder layer, ONE microbatch at the workload's
-    full shape, forward + backward in fp64 (numpy, BLAS threads as found).  Reported as stage-step
-    tokens/s by dividing by the number of layers; the optimizer step and, for head stages, the
-    embedding / LM head are left out of the sample, which makes the figure an upper bound."""
+def cpu_baseline(cfg, shard_elems):
+    """The oracle as it stands, on the host cores, on a bounded sample: ONE decoder layer x ONE microbatch
+    at the workload's full shape, forward + backward in fp64 (numpy, BLAS threads as found), and its AdamW
+    update on 2^24 elements.  The stage-step figure extrapolates both: tokens of a step / (layer time x
+    layers x microbatches + AdamW time x shard / sample).  For head stages the embedding / LM head are
+    left out of the sample, which makes the figure an upper bound."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import stage_oracle as so
@@ -73,11 +74,20 @@ def cpu_baseline(cfg):
     y, cache = so.stage_forward(sample, inp.params, inp.x[0])
     so.stage_backward(sample, cache, inp.dy[0].astype(np.float64))
     dt = time.time() - t0
-    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    tokps = sample.tokens / (dt * cfg.layers)
+    n = 1 << 24
+    rng = np.random.default_rng(cfg.seed)
+    p, g, m, v = (rng.standard_normal(n) for _ in range(4))
+    t0 = time.time()
+    so.adamw(p, g, m, v * v, 1, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay, 1.0 / cfg.num_microbatches)
+    dt_opt = time.time() - t0
+    threads = max([q.get("num_threads", 1) for q in threadpool_info()] + [1])
+    step_s = dt * cfg.layers * cfg.num_microbatches + dt_opt * shard_elems / n
+    tokps = cfg.tokens * cfg.num_microbatches / step_s
     return {"value": tokps, "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": f"1 of {cfg.layers} layers x 1 of {cfg.num_microbatches} microbatches ({sample.tokens} tokens) at full "
-                      f"shape, fwd+bwd in fp64 numpy: {dt:.1f} s; value = tokens / (time x layers), AdamW not included"}
+                      f"shape, fwd+bwd in fp64 numpy: {dt:.1f} s; AdamW on 2^24 of {shard_elems} shard elements: {dt_opt:.2f} s; "
+                      f"value = step tokens / (layer time x layers x microbatches + AdamW time x shard / sample) "
+                      f"= an extrapolated step of {step_s:.0f} s"}
 
 
 def traffic_probe(cfg):
@@ -275,7 +285,7 @@ def main():
         out["adamw_hbm_frac"] = kernels["adamw"].get("gbs", 0.0) / PEAK_HBM_GBS
     stage.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg)
+        out["cpu_baseline"] = cpu_baseline(cfg, e - b)
     print(json.dumps(out))
 
 

@@ -79,16 +79,21 @@ typedef struct {
   int64_t shard_begin, shard_end; /* [begin, end) in flat parameter index space: the optimizer's range */
   float norm_eps, rope_base;
   float lr, beta1, beta2, adam_eps, weight_decay;
-  float reserved1;
+  int32_t offload_acts;      /* 1 (needs recompute = 1): the layer-boundary activations of the forwarded microbatches
+                                live in pinned host memory (stage_attach_host_stash); the device keeps two microbatch
+                                slots, the one in use and the one being prefetched (Section 4.1.3, Section 5.4) */
 } stage_config;
 
 /* Bytes per term of the paper's memory model, plus the library's transient scratch.
  * activations: what is held between a microbatch's forward and its backward, for
  * max_microbatches microbatches.  With recompute=1 and an interior stage this is exactly
  * max_microbatches * layers * (microbatch*seq*hidden*sizeof(elem)) (Section 4.1.3).
+ * With offload_acts = 1 the device term shrinks to 2 * layers * (...) (current + prefetched microbatch) and
+ * host_stash = max_microbatches * layers * (...) bytes move to the host.
  * scratch: buffers live only inside one call.  workspace = activations + scratch, rounded up. */
 typedef struct {
   int64_t params, grads, optim, activations, scratch, workspace;
+  int64_t host_stash;  /* offload_acts: bytes of pinned host memory for the boundary activations, else 0 */
 } stage_memory;
 
 typedef struct {
@@ -115,13 +120,30 @@ int stage_layout(const stage_config* cfg, stage_segment* out, int32_t n_segments
 int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* master, float* grad_acc,
                float* adam_m, float* adam_v, void* workspace, int64_t workspace_bytes, stage_t** out);
 
+/* offload_acts = 1 only (else STAGE_ERR_ARG): hands the library the pinned host buffer that holds the
+ * layer-boundary activations between a microbatch's forward and its backward (Section 4.1.3: with offloading
+ * only the current and the next, prefetched, microbatch stay on the GPU).  Must be called once, before the
+ * first stage_forward.
+ *   host_pinned  HOST pointer, page-locked (hipHostMalloc), at least mem.host_stash bytes; owned by the
+ *                caller, must outlive the stage
+ * The library creates one extra stream of default priority for the copies and orders it against the stage's
+ * stream with events (Section 5.4: separate streams, nothing blocks the compute stream unless data is
+ * missing).  After each stage_forward the microbatch's boundary activations are copied to the host; a
+ * stage_backward whose microbatch is no longer on the device loads it back, and every stage_backward(mb)
+ * starts the load of microbatch mb-1 (the next one in the reverse order of Section 4.1.1) before it enqueues
+ * its own kernels.  Any call order that is legal without offloading stays legal and gives the same bits.
+ * Calls made in this mode must not be captured into a HIP graph.
+ * STAGE_ERR_ARG if the buffer is NULL, too small or not page-locked; STAGE_ERR_STATE if called twice. */
+int stage_attach_host_stash(stage_t* s, void* host_pinned, int64_t bytes);
+
 /* Forward of microbatch slot mb in [0, max_microbatches).
  *   x_or_ids  elem[T,H] stage input, or int32[T] token ids when has_embed
  *   y_out     elem[T,H] stage output; may be NULL when has_head
  *   targets   int32[T] (has_head only, else NULL); read again by stage_backward, so it must stay valid
  *   loss_out  device float: the microbatch's mean cross entropy (has_head only, else NULL)
- * STAGE_ERR_STATE if slot mb already holds a forward that has not been backpropagated, or if a
- * backward of this step is still waiting for its stage_accumulate. */
+ * STAGE_ERR_STATE if slot mb already holds a forward that has not been backpropagated, if a
+ * backward of this step is still waiting for its stage_accumulate, or if offload_acts = 1 and no host
+ * buffer was attached. */
 int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, const int32_t* targets,
                   float* loss_out);
 

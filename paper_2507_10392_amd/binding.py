@@ -31,11 +31,11 @@ class StageConfigC(C.Structure):
                 ("has_head", C.c_int32), ("recompute", C.c_int32), ("pair_wgrad", C.c_int32),
                 ("act_budget_bytes", C.c_int64), ("shard_begin", C.c_int64), ("shard_end", C.c_int64),
                 ("norm_eps", C.c_float), ("rope_base", C.c_float), ("lr", C.c_float), ("beta1", C.c_float),
-                ("beta2", C.c_float), ("adam_eps", C.c_float), ("weight_decay", C.c_float), ("reserved1", C.c_float)]
+                ("beta2", C.c_float), ("adam_eps", C.c_float), ("weight_decay", C.c_float), ("offload_acts", C.c_int32)]
 
 
 class StageMemoryC(C.Structure):
-    _fields_ = [(n, C.c_int64) for n in ("params", "grads", "optim", "activations", "scratch", "workspace")]
+    _fields_ = [(n, C.c_int64) for n in ("params", "grads", "optim", "activations", "scratch", "workspace", "host_stash")]
 
 
 class StageSegmentC(C.Structure):
@@ -62,6 +62,7 @@ def lib():
         L.stage_query.argtypes = [C.POINTER(StageConfigC), C.POINTER(i64), C.POINTER(StageMemoryC), C.POINTER(i32)]
         L.stage_layout.argtypes = [C.POINTER(StageConfigC), C.POINTER(StageSegmentC), i32]
         L.stage_init.argtypes = [C.POINTER(StageConfigC), vp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(vp)]
+        L.stage_attach_host_stash.argtypes = [vp, vp, i64]
         L.stage_forward.argtypes = [vp, i32, vp, vp, vp, vp]
         L.stage_backward.argtypes = [vp, i32, vp, vp, f32]
         L.stage_accumulate.argtypes = [vp, i32]
@@ -101,7 +102,8 @@ def make_config(cfg, shard=None, max_microbatches=None) -> StageConfigC:
                         cfg.num_microbatches if max_microbatches is None else max_microbatches, cfg.vocab,
                         cfg.has_embed, cfg.has_head, cfg.recompute, int(getattr(cfg, "pair_wgrad", 0)), cfg.act_budget_bytes, b, e,
                         cfg.norm_eps,
-                        cfg.rope_base, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay, 0.0)
+                        cfg.rope_base, cfg.lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay,
+                        int(getattr(cfg, "offload_acts", 0)))
 
 
 def _check(code, handle=None):
@@ -140,6 +142,11 @@ class Stage:
                                 _ptr(grad_acc), _ptr(adam_m), _ptr(adam_v), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), C.byref(h)))
         self.h = h
+
+    def attach_host_stash(self, host):
+        """host: a pinned CPU tensor (torch.empty(..., pin_memory=True)) of at least mem['host_stash'] bytes."""
+        self._keep = self._keep + (host,)
+        _check(lib().stage_attach_host_stash(self.h, _ptr(host), host.numel() * host.element_size()), self.h)
 
     def forward(self, mb, x_or_ids, y_out=None, targets=None, loss_out=None):
         _check(lib().stage_forward(self.h, mb, _ptr(x_or_ids), _ptr(y_out), _ptr(targets), _ptr(loss_out)), self.h)

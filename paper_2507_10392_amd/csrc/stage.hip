@@ -22,7 +22,7 @@ struct Seg { std::string name; int64_t off, rows, cols; };
 
 struct Shape {
   int arch, L, H, nh, d, F, S, mb, T, M, V;
-  bool bf, embed, head, recompute, pair;
+  bool bf, embed, head, recompute, pair, offload;
   int64_t E;  // bytes per element
 };
 
@@ -32,6 +32,7 @@ Shape shape_of(const stage_config& c) {
   s.F = c.ffn; s.S = c.seq; s.mb = c.microbatch; s.T = c.seq * c.microbatch; s.M = c.max_microbatches;
   s.V = c.vocab; s.bf = c.dtype == STAGE_DTYPE_BF16; s.embed = c.has_embed != 0; s.head = c.has_head != 0;
   s.recompute = c.recompute != 0; s.E = s.bf ? 2 : 4;
+  s.offload = c.offload_acts != 0;
   // weight gradients of two microbatches in one product: needs the first one's activations to stay (no
   // recompute), a second microbatch to pair with, and the part boundary on a K slab of the MFMA kernel
   s.pair = c.pair_wgrad != 0 && !s.recompute && s.M >= 2 && s.T % 64 == 0;
@@ -85,6 +86,8 @@ int validate(const stage_config* c, std::string& err) {
     if (c->vocab < 8 || c->vocab % 8) return bad("vocab must be a positive multiple of 8 when has_embed or has_head");
   }
   if (c->recompute != 0 && c->recompute != 1) return bad("recompute must be 0 or 1");
+  if (c->offload_acts != 0 && c->offload_acts != 1) return bad("offload_acts must be 0 or 1");
+  if (c->offload_acts && !c->recompute) return bad("offload_acts needs recompute = 1 (only layer-boundary activations are offloaded)");
   if (c->act_budget_bytes < 0) return bad("act_budget_bytes must be >= 0");
   const int64_t P = count_params(*c);
   if (c->shard_begin < 0 || c->shard_end < c->shard_begin || c->shard_end > P) return bad("shard range outside [0, n_params]");
@@ -118,9 +121,11 @@ struct Bump {
 constexpr int MAX_NBLK = 128;
 struct Plan {
   std::vector<LayerActs> acts;      // recompute ? 1 : M*L   (index mb*L + l)
-  std::vector<char*> stash;         // recompute: M*L layer inputs
+  std::vector<char*> stash;         // recompute: M*L layer inputs; offload: 2*L (index device_slot*L + l)
   std::vector<HeadActs> hacts;      // head: recompute ? 1 : M
-  std::vector<char*> hstash;        // head && recompute: M inputs of the final norm
+  std::vector<char*> hstash;        // head && recompute: M inputs of the final norm; offload: 2
+  int dev_slots = 0;                // offload: microbatches resident on the device at a time
+  int64_t slot_bytes = 0, host_stash_bytes = 0;   // offload: one microbatch's boundary activations; all of them
   std::vector<int32_t*> ids, targets;  // per slot copies
   // scratch
   char *gA, *gB, *gN, *gO, *gQKV, *gF1, *ytmp;
@@ -169,7 +174,22 @@ void make_plan(const stage_config& c, char* base, Plan& p) {
   const int64_t TH = (int64_t)s.T * s.H * s.E;
   Bump b(base);
   // ---- activations held between forward and backward
-  if (s.recompute) {
+  if (s.offload) {
+    // Section 4.1.3 with offloading: the microbatch in use and the one being prefetched stay on the device.  One
+    // microbatch's tensors (L layer inputs, then the final norm's input of a head stage) are contiguous, so a
+    // microbatch moves in one copy.
+    p.dev_slots = s.M < 2 ? s.M : 2;
+    p.slot_bytes = (s.L + (s.head ? 1 : 0)) * TH;
+    p.host_stash_bytes = (int64_t)s.M * p.slot_bytes;
+    p.stash.resize((size_t)p.dev_slots * s.L);
+    if (s.head) p.hstash.resize(p.dev_slots);
+    char* blockp = b.take((int64_t)p.dev_slots * p.slot_bytes);
+    for (int k = 0; k < p.dev_slots; ++k) {
+      char* q = blockp ? blockp + (int64_t)k * p.slot_bytes : nullptr;
+      for (int l = 0; l < s.L; ++l) p.stash[(size_t)k * s.L + l] = q ? q + (int64_t)l * TH : nullptr;
+      if (s.head) p.hstash[k] = q ? q + (int64_t)s.L * TH : nullptr;
+    }
+  } else if (s.recompute) {
     p.stash.resize((size_t)s.M * s.L);
     // exactly M*L tensors of T*H elements, packed (Section 4.1.3's formula); TH is a multiple of 16 bytes
     char* blockp = b.take((int64_t)s.M * s.L * TH);
@@ -221,6 +241,7 @@ void memory_of(const stage_config& c, const Plan& p, stage_memory& m) {
   m.activations = p.act_bytes;
   m.scratch = p.scratch_bytes;
   m.workspace = p.total;
+  m.host_stash = p.host_stash_bytes;
 }
 
 // ---- profiling -------------------------------------------------------------------------------
@@ -242,6 +263,20 @@ struct stage {
   std::vector<ReduceJob> jobs_host;
   int njobs = 0, max_job_width = 0;
   std::string err;
+  // offload_acts: boundary activations in pinned host memory, two device slots, one copy stream
+  struct DevSlot {
+    int owner = -1;            // microbatch whose boundary activations the slot holds (valid or being loaded)
+    bool loaded = false;       // the slot's content arrived by a host-to-device copy (readers wait for copy_done)
+    bool copied = false, computed = false;   // the events below have been recorded at least once
+    hipEvent_t copy_done = nullptr;      // copy stream: last copy from or into the slot has finished
+    hipEvent_t compute_done = nullptr;   // stage stream: last forward or backward that used the slot has finished
+    int64_t tick = 0;          // last use, for the choice of a victim
+  };
+  char* host_stash = nullptr;
+  hipStream_t copy_st = nullptr;
+  DevSlot dslot[2];
+  std::vector<int> where;      // per microbatch: device slot that holds its boundary activations, or -1
+  int64_t clock = 0;
   // profiling
   bool prof = false;
   std::vector<std::string> cls_names;
@@ -271,14 +306,81 @@ hipEvent_t next_event(stage_t* s) {
   return s->ev_pool[s->ev_used++];
 }
 
-// Runs one launcher, optionally bracketed by events; returns false (and sets the error) on failure.
-template <typename F> bool run(stage_t* s, const char* cls, double flops, double bytes, F&& f) {
+// Runs one launcher on a stream, optionally bracketed by events; returns false (and sets the error) on failure.
+template <typename F> bool run_on(stage_t* s, hipStream_t st, const char* cls, double flops, double bytes, F&& f) {
   hipEvent_t a = nullptr, b = nullptr;
-  if (s->prof) { a = next_event(s); b = next_event(s); (void)hipEventRecord(a, s->st); }
+  if (s->prof) { a = next_event(s); b = next_event(s); (void)hipEventRecord(a, st); }
   const hipError_t e = f();
-  if (s->prof) { (void)hipEventRecord(b, s->st); s->recs.push_back({cls_id(s, cls), a, b, flops, bytes}); }
+  if (s->prof) { (void)hipEventRecord(b, st); s->recs.push_back({cls_id(s, cls), a, b, flops, bytes}); }
   if (e != hipSuccess) { s->err = std::string(cls) + ": " + hipGetErrorString(e); return false; }
   return true;
+}
+template <typename F> bool run(stage_t* s, const char* cls, double flops, double bytes, F&& f) {
+  return run_on(s, s->st, cls, flops, bytes, f);
+}
+
+// ---- offload_acts: the device slots and the copies between them and the host stash ------------------
+// Ordering rules.  The copy stream is in order, so a load of a microbatch always follows its store.  Before a
+// copy touches a device slot the copy stream waits for compute_done of that slot (recorded on the stage's
+// stream after every forward or backward that used it); before the stage's stream writes a slot, or reads one
+// that was filled by a load, it waits for the slot's copy_done.
+bool hip_ok(stage_t* s, hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  s->err = std::string(what) + ": " + hipGetErrorString(e);
+  return false;
+}
+
+void evict(stage_t* s, int k) {
+  stage::DevSlot& d = s->dslot[k];
+  if (d.owner >= 0 && s->where[d.owner] == k) s->where[d.owner] = -1;
+  d.owner = -1;
+}
+
+// A slot whose microbatch is no longer waiting for its backward first, else the least recently used one (its
+// microbatch stays valid on the host).
+int pick_slot(stage_t* s) {
+  int best = -1;
+  for (int k = 0; k < s->plan.dev_slots; ++k) {
+    const stage::DevSlot& d = s->dslot[k];
+    if (d.owner < 0 || s->slot[d.owner] != 1) return k;
+    if (best < 0 || d.tick < s->dslot[best].tick) best = k;
+  }
+  return best;
+}
+
+bool mark_computed(stage_t* s, int k) {
+  stage::DevSlot& d = s->dslot[k];
+  d.computed = true;
+  return hip_ok(s, hipEventRecord(d.compute_done, s->st), "offload: event record");
+}
+
+// After forward(mb) wrote slot k: copy it to the host.
+bool offload_store(stage_t* s, int k, int mb) {
+  stage::DevSlot& d = s->dslot[k];
+  if (!mark_computed(s, k)) return false;
+  if (!hip_ok(s, hipStreamWaitEvent(s->copy_st, d.compute_done, 0), "offload: stream wait")) return false;
+  const int64_t n = s->plan.slot_bytes;
+  if (!run_on(s, s->copy_st, "offload_d2h", 0, (double)n, [&] {
+        return hipMemcpyAsync(s->host_stash + (int64_t)mb * n, s->plan.stash[(size_t)k * s->sh.L], n, hipMemcpyDeviceToHost,
+                              s->copy_st); }))
+    return false;
+  d.copied = true;
+  return hip_ok(s, hipEventRecord(d.copy_done, s->copy_st), "offload: event record");
+}
+
+// Brings microbatch mb from the host into slot k (whose previous content is given up).
+bool offload_load(stage_t* s, int k, int mb) {
+  evict(s, k);
+  stage::DevSlot& d = s->dslot[k];
+  if (d.computed && !hip_ok(s, hipStreamWaitEvent(s->copy_st, d.compute_done, 0), "offload: stream wait")) return false;
+  const int64_t n = s->plan.slot_bytes;
+  if (!run_on(s, s->copy_st, "offload_h2d", 0, (double)n, [&] {
+        return hipMemcpyAsync(s->plan.stash[(size_t)k * s->sh.L], s->host_stash + (int64_t)mb * n, n, hipMemcpyHostToDevice,
+                              s->copy_st); }))
+    return false;
+  d.owner = mb; d.loaded = true; d.copied = true; d.tick = ++s->clock;
+  s->where[mb] = k;
+  return hip_ok(s, hipEventRecord(d.copy_done, s->copy_st), "offload: event record");
 }
 
 DType dt_of(const stage_t* s) { return s->sh.bf ? BF16 : F32; }
@@ -596,6 +698,7 @@ int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* m
   s->layout = make_layout(*cfg);
   make_plan(*cfg, (char*)workspace, s->plan);
   s->slot.assign(s->sh.M, 0);
+  s->where.assign(s->sh.M, -1);
 
   // reduction jobs of the vector parameters, partial buffers carved in layout order
   float* pp = s->plan.partials;
@@ -621,6 +724,31 @@ int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* m
   return STAGE_OK;
 }
 
+int stage_attach_host_stash(stage_t* s, void* host_pinned, int64_t bytes) {
+  if (!s) return STAGE_ERR_ARG;
+  if (!s->sh.offload) return fail(s, STAGE_ERR_ARG, "the stage was not configured with offload_acts = 1");
+  if (s->host_stash) return fail(s, STAGE_ERR_STATE, "a host buffer is already attached");
+  if (!host_pinned) return fail(s, STAGE_ERR_ARG, "host_pinned is NULL");
+  if (bytes < s->plan.host_stash_bytes)
+    return fail(s, STAGE_ERR_ARG, "host buffer has " + std::to_string(bytes) + " bytes, " +
+                                      std::to_string(s->plan.host_stash_bytes) + " needed");
+  hipPointerAttribute_t at;
+  if (hipPointerGetAttributes(&at, host_pinned) != hipSuccess) {
+    (void)hipGetLastError();   // the query of an unknown pointer leaves an error behind
+    return fail(s, STAGE_ERR_ARG, "host buffer is not page-locked (allocate it with hipHostMalloc)");
+  }
+  if (at.type != hipMemoryTypeHost)
+    return fail(s, STAGE_ERR_ARG, "host buffer is not page-locked host memory (allocate it with hipHostMalloc)");
+  hipError_t e = hipStreamCreateWithFlags(&s->copy_st, hipStreamNonBlocking);   // default priority
+  for (int k = 0; k < 2 && e == hipSuccess; ++k) {
+    e = hipEventCreateWithFlags(&s->dslot[k].copy_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->dslot[k].compute_done, hipEventDisableTiming);
+  }
+  if (e != hipSuccess) return fail(s, STAGE_ERR_DEVICE, std::string("stage_attach_host_stash: ") + hipGetErrorString(e));
+  s->host_stash = (char*)host_pinned;
+  return STAGE_OK;
+}
+
 int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, const int32_t* targets, float* loss_out) {
   if (!s) return STAGE_ERR_ARG;
   const Shape& h = s->sh;
@@ -635,7 +763,18 @@ int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, con
   const DType dt = dt_of(s);
   const int64_t TH = (int64_t)h.T * h.H * h.E;
 
-  auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)mb * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
+  int k = mb;   // index of the microbatch's boundary activations on the device
+  if (h.offload) {
+    if (!s->host_stash) return fail(s, STAGE_ERR_STATE, "offload_acts = 1 but stage_attach_host_stash was not called");
+    if (s->where[mb] >= 0) evict(s, s->where[mb]);   // left over from this slot's previous round
+    k = pick_slot(s);
+    evict(s, k);
+    stage::DevSlot& d = s->dslot[k];
+    if (d.copied && !hip_ok(s, hipStreamWaitEvent(s->st, d.copy_done, 0), "offload: stream wait")) return STAGE_ERR_DEVICE;
+    d.owner = mb; d.loaded = false; d.tick = ++s->clock;
+    s->where[mb] = k;
+  }
+  auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)k * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
   char* x0 = in_of(0);
   if (h.embed) {
     if (!run(s, "copy", 0, 8.0 * h.T, [&] { return copy_bytes(s->st, pl.ids[mb], x_or_ids, 4ll * h.T); })) return STAGE_ERR_DEVICE;
@@ -646,7 +785,7 @@ int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, con
     return STAGE_ERR_DEVICE;
   }
   char* final_y = nullptr;
-  if (h.head) final_y = h.recompute ? pl.hstash[mb] : pl.hacts[mb].y;
+  if (h.head) final_y = h.recompute ? pl.hstash[k] : pl.hacts[mb].y;
   for (int l = 0; l < h.L; ++l) {
     LayerActs& A = h.recompute ? pl.acts[0] : pl.acts[(size_t)mb * h.L + l];
     char* y = l + 1 < h.L ? in_of(l + 1) : (h.head ? final_y : (char*)y_out);
@@ -658,6 +797,7 @@ int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, con
     if (!head_forward(s, final_y, HA, pl.targets[mb], loss_out)) return STAGE_ERR_DEVICE;
     if (y_out && !run(s, "copy", 0, 2.0 * TH, [&] { return copy_bytes(s->st, y_out, final_y, TH); })) return STAGE_ERR_DEVICE;
   }
+  if (h.offload && !offload_store(s, k, mb)) return STAGE_ERR_DEVICE;
   s->slot[mb] = 1;
   s->outstanding++;
   return STAGE_OK;
@@ -674,7 +814,22 @@ int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float l
   Plan& pl = s->plan;
   const int64_t TH = (int64_t)h.T * h.H * h.E;
 
-  auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)mb * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
+  int k = mb;   // index of the microbatch's boundary activations on the device
+  if (h.offload) {
+    k = s->where[mb];
+    if (k < 0) {   // not on the device (any more): load it now, the kernels below wait for it
+      k = pick_slot(s);
+      if (!offload_load(s, k, mb)) return STAGE_ERR_DEVICE;
+    }
+    stage::DevSlot& d = s->dslot[k];
+    d.tick = ++s->clock;
+    if (d.loaded && !hip_ok(s, hipStreamWaitEvent(s->st, d.copy_done, 0), "offload: stream wait")) return STAGE_ERR_DEVICE;
+    // the next microbatch of the reverse order travels to the other slot while this one computes
+    const int nx = mb - 1;
+    if (pl.dev_slots > 1 && nx >= 0 && s->slot[nx] == 1 && s->where[nx] < 0 && !offload_load(s, 1 - k, nx))
+      return STAGE_ERR_DEVICE;
+  }
+  auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)k * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
   // pair_wgrad: a backward with further backwards to come leaves its weight-gradient products to the next
   // one and keeps their dY operands in per-layer buffers; the next one multiplies for both.
   const bool fuse = h.pair && s->deferred >= 0;
@@ -685,7 +840,7 @@ int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float l
   char* bufs[2] = {pl.gB, pl.gA};
   int bi = 0;
   if (h.head) {
-    char* final_y = h.recompute ? pl.hstash[mb] : pl.hacts[mb].y;
+    char* final_y = h.recompute ? pl.hstash[k] : pl.hacts[mb].y;
     HeadActs& HA = h.recompute ? pl.hacts[0] : pl.hacts[mb];
     if (h.recompute && !head_forward(s, final_y, HA, pl.targets[mb], pl.lossdump)) return STAGE_ERR_DEVICE;
     if (!head_backward(s, final_y, HA, pl.targets[mb], loss_scale, top)) return STAGE_ERR_DEVICE;
@@ -716,6 +871,7 @@ int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float l
           return embed_bwd(s->st, dt_of(s), h.T, h.H, h.V, pl.ids[mb], cur, s->G(s->seg_off("embed.E"))); }))
       return STAGE_ERR_DEVICE;
   }
+  if (h.offload && !mark_computed(s, k)) return STAGE_ERR_DEVICE;
   s->slot[mb] = 2;
   s->pending = mb;
   return STAGE_OK;
@@ -738,6 +894,7 @@ int stage_accumulate(stage_t* s, int32_t mb) {
 int stage_graph_replayed(stage_t* s, int32_t n_microbatches) {
   if (!s) return STAGE_ERR_ARG;
   if (n_microbatches < 1 || n_microbatches > s->sh.M) return fail(s, STAGE_ERR_ARG, "n_microbatches must be in 1..max_microbatches");
+  if (s->sh.offload) return fail(s, STAGE_ERR_ARG, "calls of a stage with offload_acts = 1 cannot be captured");
   if (s->pending >= 0 || s->outstanding != 0)
     return fail(s, STAGE_ERR_STATE, "microbatches are still outstanding (forward without backward+accumulate)");
   s->accumulated += n_microbatches;
@@ -803,6 +960,12 @@ const char* stage_last_error(const stage_t* s) { return s ? s->err.c_str() : g_e
 
 void stage_destroy(stage_t* s) {
   if (!s) return;
+  if (s->copy_st) (void)hipStreamSynchronize(s->copy_st);   // no copy may outlive the caller's buffers
+  for (auto& d : s->dslot) {
+    if (d.copy_done) (void)hipEventDestroy(d.copy_done);
+    if (d.compute_done) (void)hipEventDestroy(d.compute_done);
+  }
+  if (s->copy_st) (void)hipStreamDestroy(s->copy_st);
   for (auto e : s->ev_pool) (void)hipEventDestroy(e);
   delete s;
 }

@@ -73,6 +73,10 @@ class GpuStage:
         self.ws = torch.empty(mem["workspace"], dtype=torch.uint8, device="cuda")
         self.mem = mem
         self.stage = zs.Stage(self.cc, self.params, self.master, self.grad, self.m, self.v, self.ws)
+        self.host = None
+        if getattr(cfg, "offload_acts", 0):
+            self.host = torch.empty(mem["host_stash"], dtype=torch.uint8, pin_memory=True)
+            self.stage.attach_host_stash(self.host)
 
     def run_microbatches(self, inp, M=None, loss_scale=None, order=None):
         cfg = self.cfg

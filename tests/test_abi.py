@@ -57,6 +57,31 @@ def test_recompute_stash_is_exactly_the_papers_formula():
     assert rc["activations"] == 16 * 8 * 4096 * 4096 * 2 and full["activations"] > 10 * rc["activations"]
 
 
+def test_offload_keeps_two_microbatches_on_the_device():
+    """Section 4.1.3: with the boundary activations offloaded, only the microbatch in use and the one being
+    prefetched stay on the GPU; all B x L tensors of S x H x D bytes live on the host."""
+    for name in ("C4b", "C4bt", "C5"):
+        cfg = get_config(name).with_(recompute=1)
+        one = cfg.tokens * cfg.hidden * 2
+        per_mb = (cfg.layers + cfg.has_head) * one      # a head stage also keeps the final norm's input
+        _, res, _ = zs.query(zs.make_config(cfg))
+        _, off, _ = zs.query(zs.make_config(cfg.with_(offload_acts=1)))
+        small = 4 * cfg.tokens * (cfg.has_embed + cfg.has_head) * cfg.num_microbatches   # ids / targets stay on the device
+        assert res["host_stash"] == 0 and off["host_stash"] == cfg.num_microbatches * per_mb
+        assert abs(res["activations"] - (cfg.num_microbatches * per_mb + small)) <= 512 * cfg.num_microbatches
+        assert abs(off["activations"] - (2 * per_mb + small)) <= 512 * cfg.num_microbatches
+        assert off["scratch"] == res["scratch"]
+    # an activation budget that the resident stash breaks is met with offloading
+    c4b = get_config("C4b")
+    with pytest.raises(zs.StageError) as ei:
+        zs.query(zs.make_config(c4b.with_(act_budget_bytes=3 * 10**9)))
+    assert ei.value.code == zs.STAGE_ERR_BUDGET
+    zs.query(zs.make_config(c4b.with_(act_budget_bytes=3 * 10**9, offload_acts=1)))
+    with pytest.raises(zs.StageError) as ei:             # only boundary activations are offloaded
+        zs.query(zs.make_config(c4b.with_(recompute=0, offload_acts=1)))
+    assert ei.value.code == zs.STAGE_ERR_ARG
+
+
 def test_bad_configs_are_rejected_on_the_host():
     cfg = get_config("C1")
     for kw in (dict(heads=3), dict(hidden=250, heads=5), dict(layers=0), dict(arch=2), dict(dtype=3),

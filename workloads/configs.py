@@ -34,7 +34,8 @@ class StageConfig:
     has_embed: int = 0
     has_head: int = 0
     recompute: int = 0
-    pair_wgrad: int = 0          # library option: fold every other backward's weight gradients into the next one's
+    pair_wgrad: int = 0            # library option: fold every other backward's weight gradients into the next one's
+    offload_acts: int = 0          # library option (with recompute): boundary activations kept in pinned host memory
     act_budget_bytes: int = 0
     shard_num: int = 1      # the shard is the first shard_num/shard_den of the flat parameters
     shard_den: int = 1
