@@ -132,6 +132,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture the microbatch loop of a step in a HIP graph and replay it (for launch-bound stages); "
                          "per-kernel events are off in this mode")
+    ap.add_argument("--recompute", action="store_true", help="run the workload with per-layer recompute (stage_config.recompute = 1)")
+    ap.add_argument("--offload", action="store_true",
+                    help="keep the boundary activations in pinned host memory (stage_config.offload_acts = 1; implies --recompute)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a 1 GiB copy and the workload's weight-gradient GEMMs only (for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -148,6 +151,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     cfg = get_config(args.workload).with_(pair_wgrad=0 if args.no_pair_wgrad else 1)
+    if args.recompute or args.offload:
+        cfg = cfg.with_(recompute=1, offload_acts=1 if args.offload else 0)
+    if args.offload and args.graph:
+        print("bench.py: --offload cannot be combined with --graph", file=sys.stderr)
+        sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.traffic_probe:
@@ -178,6 +186,8 @@ def main():
     ys = [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
     dxs = [None] * M if cfg.has_embed else [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
     stage = zs.Stage(cc, params, master, grad, m, v, ws)
+    if cfg.offload_acts:
+        stage.attach_host_stash(torch.empty(mem["host_stash"], dtype=torch.uint8, pin_memory=True))
 
     def microbatches():
         for i in range(M):
@@ -274,12 +284,13 @@ def main():
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers, hidden {cfg.hidden}, heads {cfg.heads}, ffn {cfg.ffn}, "
                                f"seq {cfg.seq}, microbatch {cfg.microbatch} x {M} microbatches, "
                                f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {e - b} of {P} params, "
-                               f"recompute {cfg.recompute}, pair_wgrad {cfg.pair_wgrad}",
+                               f"recompute {cfg.recompute}, pair_wgrad {cfg.pair_wgrad}, offload_acts {cfg.offload_acts}",
                    "tokens_per_step": tokens, "shard_elems": e - b},
         "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
         "mfu_model_flops": mfu, "hfu_executed_flops": mfu * (4.0 / 3.0 if cfg.recompute else 1.0),
         "model_tflop_per_step": mflops / 1e12, "finite": finite,
         "roofline": roofline, "kernels": kernels, "hip_graph": bool(args.graph),
+        "memory_bytes": mem,
     }
     if "adamw" in kernels:
         out["adamw_hbm_frac"] = kernels["adamw"].get("gbs", 0.0) / PEAK_HBM_GBS

@@ -354,6 +354,9 @@ bool mark_computed(stage_t* s, int k) {
   return hip_ok(s, hipEventRecord(d.compute_done, s->st), "offload: event record");
 }
 
+// The copies are left to the runtime's copy path (hipMemcpyAsync on the copy stream).  A copy kernel of this
+// library reached the full link rate (55 GB/s each way) but cost 13-19 % of the step: the GEMM grids fill the
+// 256 compute units exactly, so every unit held by a resident copy workgroup adds a round to each of them.
 // After forward(mb) wrote slot k: copy it to the host.
 bool offload_store(stage_t* s, int k, int mb) {
   stage::DevSlot& d = s->dslot[k];
