@@ -38,6 +38,16 @@ class StageMemoryC(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("params", "grads", "optim", "activations", "scratch", "workspace", "host_stash")]
 
 
+class MinistagesConfigC(C.Structure):
+    _fields_ = [("stage", StageConfigC), ("n_ministages", C.c_int32), ("reserved", C.c_int32)]
+
+
+class MinistagesMemoryC(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("per_stage_host", "host_bytes", "off_params", "off_master", "off_m", "off_v",
+                                         "param_slot", "state_slot", "grad", "workspace_each", "device_bytes",
+                                         "resident_bytes")]
+
+
 class StageSegmentC(C.Structure):
     _fields_ = [("name", C.c_char * 32), ("offset", C.c_int64), ("rows", C.c_int64), ("cols", C.c_int64)]
 
@@ -74,6 +84,19 @@ def lib():
         L.stage_last_error.restype = C.c_char_p
         L.stage_destroy.argtypes = [vp]
         L.stage_destroy.restype = None
+        L.ministages_query.argtypes = [C.POINTER(MinistagesConfigC), C.POINTER(MinistagesMemoryC)]
+        L.ministages_init.argtypes = [C.POINTER(MinistagesConfigC), vp, vp, i64, vp, i64, C.POINTER(vp)]
+        L.ministages_forward.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.ministages_backward.argtypes = [vp, i32, i32, vp, vp, f32]
+        L.ministages_accumulate.argtypes = [vp, i32, i32]
+        L.ministages_optimizer_step.argtypes = [vp, i32, i64, f32]
+        L.ministages_stage.argtypes = [vp, i32]
+        L.ministages_stage.restype = vp
+        L.ministages_traffic.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
+        L.ministages_last_error.argtypes = [vp]
+        L.ministages_last_error.restype = C.c_char_p
+        L.ministages_destroy.argtypes = [vp]
+        L.ministages_destroy.restype = None
         L.stage_op_gemm.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, i32,
                                     i64, i64, i64, i64, i32, i64, i32]
         L.stage_op_gemm_rope.argtypes = L.stage_op_gemm.argtypes + [vp, i32, i32, i32]
@@ -177,6 +200,75 @@ class Stage:
     def close(self):
         if self.h:
             lib().stage_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def ministages_query(cc: StageConfigC, n_ministages: int):
+    """-> dict of the sizes and offsets of include/ministages.h's ministages_memory."""
+    mc, mem = MinistagesConfigC(cc, n_ministages, 0), MinistagesMemoryC()
+    code = lib().ministages_query(C.byref(mc), C.byref(mem))
+    if code != STAGE_OK:
+        raise StageError(code, (lib().ministages_last_error(None) or b"").decode())
+    return {k: getattr(mem, k) for k, _ in MinistagesMemoryC._fields_}
+
+
+class Ministages:
+    """K ministages of one shape sharing two parameter slots on the device (include/ministages.h).
+    host: pinned CPU uint8 tensor (the host block, filled by the caller); arena: device uint8 tensor."""
+
+    def __init__(self, cc: StageConfigC, n_ministages, host, arena, stream=None):
+        import torch
+        self.mc = MinistagesConfigC(cc, n_ministages, 0)
+        self._keep = (host, arena)
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = C.c_void_p()
+        code = lib().ministages_init(C.byref(self.mc), C.c_void_p(self.stream.cuda_stream), _ptr(host), host.numel(),
+                                     _ptr(arena), arena.numel(), C.byref(h))
+        if code != STAGE_OK:
+            raise StageError(code, (lib().ministages_last_error(None) or b"").decode())
+        self.h = h
+
+    def _check(self, code):
+        if code != STAGE_OK:
+            raise StageError(code, (lib().ministages_last_error(self.h) or b"").decode())
+
+    def forward(self, k, mb, x_or_ids, y_out=None, targets=None, loss_out=None):
+        self._check(lib().ministages_forward(self.h, k, mb, _ptr(x_or_ids), _ptr(y_out), _ptr(targets), _ptr(loss_out)))
+
+    def backward(self, k, mb, dy=None, dx_out=None, loss_scale=1.0):
+        self._check(lib().ministages_backward(self.h, k, mb, _ptr(dy), _ptr(dx_out), loss_scale))
+
+    def accumulate(self, k, mb):
+        self._check(lib().ministages_accumulate(self.h, k, mb))
+
+    def optimizer_step(self, k, t, grad_scale=1.0):
+        self._check(lib().ministages_optimizer_step(self.h, k, t, grad_scale))
+
+    def traffic(self):
+        a, b = C.c_int64(), C.c_int64()
+        self._check(lib().ministages_traffic(self.h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def stage_profile(self, k, enable):
+        _check(lib().stage_profile(lib().ministages_stage(self.h, k), 1 if enable else 0))
+
+    def stage_profile_read(self, k):
+        out = (StageKernelStatC * 64)()
+        n = lib().stage_profile_read(lib().ministages_stage(self.h, k), out, 64)
+        if n < 0:
+            raise StageError(-n, "stage_profile_read failed")
+        return {out[i].name.decode(): dict(launches=out[i].launches, ms=out[i].ms, flops=out[i].flops,
+                                           bytes=out[i].bytes) for i in range(n)}
+
+    def close(self):
+        if self.h:
+            lib().ministages_destroy(self.h)
             self.h = None
 
     def __del__(self):

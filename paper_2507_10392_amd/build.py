@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstage.so")
-SOURCES = ["stage.hip", "ops_api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "gemm_mfma_256x256.hip",
+SOURCES = ["stage.hip", "ministages.hip", "ops_api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "gemm_mfma_256x256.hip",
            "gemm_mfma_128x128.hip",
            "attention_simple.hip", "attention_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -15,10 +15,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def declared_symbols():
     names = []
-    for h in ("stage.h", "stage_ops.h"):
+    for h in ("stage.h", "stage_ops.h", "ministages.h"):
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names += re.findall(r"\b(stage_[a-z_0-9]+)\s*\(", text)
+        names += re.findall(r"\b((?:stage|ministages)_[a-z_0-9]+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -79,6 +79,30 @@ def test_offload_keeps_two_microbatches_on_the_device():
     zs.query(zs.make_config(c4b.with_(act_budget_bytes=3 * 10**9, offload_acts=1)))
     with pytest.raises(zs.StageError) as ei:             # only boundary activations are offloaded
         zs.query(zs.make_config(c4b.with_(recompute=0, offload_acts=1)))
+    assert ei.value.code == zs.STAGE_ERR_ARG
+
+
+def test_ministages_memory_report():
+    """Section 4.1.1: two ministages' parameters on the GPU instead of all K; Section 4.1.2: one gradient buffer,
+    freed by each ministage's optimizer step."""
+    cfg = get_config("C3").with_(layers=2)
+    cc = zs.make_config(cfg)
+    P, mem, _ = zs.query(cc)
+    sh = cc.shard_end - cc.shard_begin
+    for K in (1, 2, 4, 9):
+        m = zs.ministages_query(cc, K)
+        up = lambda n: (n + 255) // 256 * 256
+        assert m["off_params"] == 0 and m["off_master"] == up(2 * P) and m["off_m"] == m["off_master"] + up(4 * sh)
+        assert m["per_stage_host"] == up(2 * P) + 3 * up(4 * sh) and m["host_bytes"] == K * m["per_stage_host"]
+        slots = min(K, 2)
+        assert m["device_bytes"] == slots * (up(2 * P) + 3 * up(4 * sh)) + up(4 * P) + K * up(mem["workspace"])
+        assert m["resident_bytes"] == K * (mem["params"] + mem["grads"] + mem["optim"] + mem["workspace"])
+    assert "ministages_forward" in declared_symbols() and "ministages_destroy" in declared_symbols()
+    with pytest.raises(zs.StageError) as ei:
+        zs.ministages_query(cc, 0)
+    assert ei.value.code == zs.STAGE_ERR_ARG
+    with pytest.raises(zs.StageError) as ei:
+        zs.ministages_query(zs.make_config(cfg.with_(recompute=1, offload_acts=1)), 2)
     assert ei.value.code == zs.STAGE_ERR_ARG
 
 
