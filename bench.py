@@ -90,6 +90,72 @@ def cpu_baseline(cfg, shard_elems):
                       f"= an extrapolated step of {step_s:.0f} s"}
 
 
+class MinistageRunner:
+    """The workload's layers cut into K ministages of equal depth that share two parameter slots on the GPU
+    (include/ministages.h); a step runs them in the paper's order: all forwards ministage by ministage, then the
+    backwards in reverse with each ministage's optimizer step right after its own backward."""
+
+    def __init__(self, torch, zs, cfg, K, xs, dys):
+        self.torch, self.K, self.M = torch, K, cfg.num_microbatches
+        sub = cfg.with_(layers=cfg.layers // K)
+        self.cc = zs.make_config(sub)
+        self.P, _, _ = zs.query(self.cc)
+        self.mem = mem = zs.ministages_query(self.cc, K)
+        b, e = self.cc.shard_begin, self.cc.shard_end
+        self.shard_elems = K * (e - b)
+        td = torch.bfloat16 if cfg.dtype == 1 else torch.float32
+        E = 2 if cfg.dtype == 1 else 4
+        self.host = torch.empty(mem["host_bytes"], dtype=torch.uint8, pin_memory=True)
+        self.host.zero_()
+        tmp = torch.empty(self.P, dtype=td, device="cuda")
+        for k in range(K):
+            fill_params(sub, tmp, torch)
+            o = k * mem["per_stage_host"]
+            self.host[o + mem["off_params"]:o + mem["off_params"] + E * self.P].view(td).copy_(tmp)
+            if mem["off_master"] >= 0:
+                self.host[o + mem["off_master"]:o + mem["off_master"] + 4 * (e - b)].view(torch.float32).copy_(tmp[b:e].float())
+        self.probe = self.host[mem["off_params"]:mem["off_params"] + E * (e - b)].view(td)   # ministage 0's shard
+        del tmp
+        self.arena = torch.empty(mem["device_bytes"], dtype=torch.uint8, device="cuda")
+        self.ms = zs.Ministages(self.cc, K, self.host, self.arena)
+        self.xs, self.dys = xs, dys
+        T, H = cfg.tokens, cfg.hidden
+        self.bufs = [[torch.empty(T, H, dtype=td, device="cuda") for _ in range(self.M)] for _ in range(2)]
+
+    def step(self, t):
+        ms, M = self.ms, self.M
+        cur = self.xs
+        for k in range(self.K):
+            nxt = self.bufs[k % 2]
+            for i in range(M):
+                ms.forward(k, i, cur[i], nxt[i])
+            cur = nxt
+        g = self.dys
+        for k in reversed(range(self.K)):
+            nxt = self.bufs[k % 2]
+            for i in reversed(range(M)):
+                ms.backward(k, i, g[i], nxt[i], 1.0 / M)
+                ms.accumulate(k, i)
+            ms.optimizer_step(k, t)
+            g = nxt
+
+    def profile(self, on):
+        for k in range(self.K):
+            self.ms.stage_profile(k, on)
+
+    def profile_read(self):
+        tot = {}
+        for k in range(self.K):
+            for name, st in self.ms.stage_profile_read(k).items():
+                d = tot.setdefault(name, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
+                for key in d:
+                    d[key] += st[key]
+        return tot
+
+    def close(self):
+        self.ms.close()
+
+
 def traffic_probe(cfg):
     """For rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: launches a plain copy of known size (1 GiB read,
     1 GiB written, torch's elementwise copy kernel) and then the weight-gradient GEMMs of one decoder
@@ -135,6 +201,9 @@ def main():
     ap.add_argument("--recompute", action="store_true", help="run the workload with per-layer recompute (stage_config.recompute = 1)")
     ap.add_argument("--offload", action="store_true",
                     help="keep the boundary activations in pinned host memory (stage_config.offload_acts = 1; implies --recompute)")
+    ap.add_argument("--ministages", type=int, default=0, metavar="K",
+                    help="cut the workload's layers into K ministages that share two parameter slots on the GPU, the rest "
+                         "waiting in pinned host memory (include/ministages.h); interior stages only")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a 1 GiB copy and the workload's weight-gradient GEMMs only (for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -156,6 +225,10 @@ def main():
     if args.offload and args.graph:
         print("bench.py: --offload cannot be combined with --graph", file=sys.stderr)
         sys.exit(2)
+    if args.ministages and (args.graph or args.offload or cfg.has_embed or cfg.has_head or cfg.layers % args.ministages):
+        print("bench.py: --ministages K needs an interior stage whose layer count K divides, and neither --graph nor --offload",
+              file=sys.stderr)
+        sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.traffic_probe:
@@ -169,13 +242,14 @@ def main():
     td = torch.bfloat16 if bf else torch.float32
     M, T, H = cfg.num_microbatches, cfg.tokens, cfg.hidden
 
-    params = torch.empty(P, dtype=td, device=dev)
-    fill_params(cfg, params, torch)
-    master = params[b:e].float() if bf else None
-    grad = torch.zeros(P, dtype=torch.float32, device=dev)
-    m = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
-    v = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
-    ws = torch.empty(mem["workspace"], dtype=torch.uint8, device=dev)
+    if not args.ministages:
+        params = torch.empty(P, dtype=td, device=dev)
+        fill_params(cfg, params, torch)
+        master = params[b:e].float() if bf else None
+        grad = torch.zeros(P, dtype=torch.float32, device=dev)
+        m = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
+        v = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
+        ws = torch.empty(mem["workspace"], dtype=torch.uint8, device=dev)
     if cfg.has_embed:
         xs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)]
     else:
@@ -185,7 +259,12 @@ def main():
     dys = [None] * M if cfg.has_head else [(torch.randn(T, H, device=dev) * 0.01).to(td) for _ in range(M)]
     ys = [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
     dxs = [None] * M if cfg.has_embed else [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
-    stage = zs.Stage(cc, params, master, grad, m, v, ws)
+    if args.ministages:
+        stage = MinistageRunner(torch, zs, cfg, args.ministages, xs, dys)
+        params, mem, shard_elems = stage.probe, stage.mem, stage.shard_elems
+    else:
+        stage = zs.Stage(cc, params, master, grad, m, v, ws)
+        shard_elems = e - b
     if cfg.offload_acts:
         stage.attach_host_stash(torch.empty(mem["host_stash"], dtype=torch.uint8, pin_memory=True))
 
@@ -199,6 +278,8 @@ def main():
     graph = None
 
     def step(t):
+        if args.ministages:
+            return stage.step(t)
         if graph is not None:
             graph.replay()
             stage.graph_replayed(M)
@@ -232,16 +313,20 @@ def main():
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the stage's stream
     t0 = time.perf_counter()
     marks[0].record()
+    enqueue_ms = []          # host time to enqueue each step (no synchronisation inside): must stay below the step time
     for i in range(args.steps):
         t += 1
         if i == args.steps - 1 and not args.no_kernel_events:
             stage.profile(True)
+        h0 = time.perf_counter()
         step(t)
+        enqueue_ms.append((time.perf_counter() - h0) * 1e3)
         marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof_steps = 1
-    per_step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    in_order_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+    per_step_ms = sorted(in_order_ms)
     stats = stage.profile_read() if not args.no_kernel_events else {}
     stage.profile(False)
     finite = bool(torch.isfinite(params.float().sum()).item())
@@ -283,10 +368,12 @@ def main():
         "dtype": "bf16" if bf else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers, hidden {cfg.hidden}, heads {cfg.heads}, ffn {cfg.ffn}, "
                                f"seq {cfg.seq}, microbatch {cfg.microbatch} x {M} microbatches, "
-                               f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {e - b} of {P} params, "
-                               f"recompute {cfg.recompute}, pair_wgrad {cfg.pair_wgrad}, offload_acts {cfg.offload_acts}",
-                   "tokens_per_step": tokens, "shard_elems": e - b},
-        "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
+                               f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {shard_elems} of {P} params, "
+                               f"recompute {cfg.recompute}, pair_wgrad {cfg.pair_wgrad}, offload_acts {cfg.offload_acts}"
+                               + (f", {args.ministages} ministages of {cfg.layers // args.ministages} layers time-multiplexed"
+                                  if args.ministages else ""),
+                   "tokens_per_step": tokens, "shard_elems": shard_elems},
+        "ms_each_step": [round(x, 2) for x in in_order_ms], "enqueue_ms_each_step": [round(x, 2) for x in enqueue_ms], "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
         "mfu_model_flops": mfu, "hfu_executed_flops": mfu * (4.0 / 3.0 if cfg.recompute else 1.0),
         "model_tflop_per_step": mflops / 1e12, "finite": finite,
         "roofline": roofline, "kernels": kernels, "hip_graph": bool(args.graph),
@@ -294,9 +381,14 @@ def main():
     }
     if "adamw" in kernels:
         out["adamw_hbm_frac"] = kernels["adamw"].get("gbs", 0.0) / PEAK_HBM_GBS
+    if args.ministages:
+        h2d, d2h = stage.ms.traffic()
+        nsteps = args.steps + args.warmup
+        out["ministages"] = {"K": args.ministages, "device_arena_bytes": mem["device_bytes"], "resident_bytes": mem["resident_bytes"],
+                             "host_bytes": mem["host_bytes"], "h2d_bytes_per_step": h2d / nsteps, "d2h_bytes_per_step": d2h / nsteps}
     stage.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, e - b)
+        out["cpu_baseline"] = cpu_baseline(cfg, shard_elems)
     print(json.dumps(out))
 
 

@@ -13,11 +13,12 @@
  * (include/stage.h) and moves their state between a caller-owned page-locked host block, where all of it
  * lives between uses, and a caller-owned device arena that holds
  *     2 parameter slots            (working parameters of the running and of the prefetched ministage),
- *     2 optimizer-state slots      (fp32 master, m, v of the shard: the one in use, the one in flight),
+ *     3 optimizer-state slots      (fp32 master, m, v of the shard: the one in use, the one whose store is
+ *                                   still in flight, the one being loaded),
  *     1 fp32 gradient buffer       (shared: a ministage's gradients are dropped by its optimizer step
  *                                   before the next ministage's backward starts),
  *     K workspaces                 (each ministage's activations wait for its backward).
- * Ministage k uses parameter slot and optimizer-state slot k mod 2.
+ * Ministage k uses parameter slot k mod 2 and optimizer-state slot k mod 3 (fewer slots when K is smaller).
  *
  * Host block layout: ministage k occupies [k * per_stage_host, (k+1) * per_stage_host); inside it, at the
  * offsets ministages_query reports, the working parameters elem[P], then for the shard the fp32 master
@@ -25,8 +26,9 @@
  * ministage's optimizer step and a synchronisation of the device it holds the updated shard (working
  * parameters in [shard_begin, shard_end), master, m, v).  Parameters outside the shard are never written.
  *
- * All calls only enqueue work: kernels on the stream given to ministages_init, copies on one extra stream
- * of default priority that the library creates; the two are ordered with events, nothing synchronises with
+ * All calls only enqueue work: kernels on the stream given to ministages_init, copies on two extra streams
+ * of default priority that the library creates (one for loads, one for stores, so that a slow store never
+ * holds up the load the next kernels wait for); the three are ordered with events, nothing synchronises with
  * the host.  Calls must not be captured into a HIP graph.  Return values are the STAGE_* codes.
  */
 #ifndef MINISTAGES_H
@@ -53,7 +55,7 @@ typedef struct {
   int64_t host_bytes;                            /* K * per_stage_host */
   int64_t off_params, off_master, off_m, off_v;  /* offsets inside one ministage's host block; off_master = -1 for dtype 0 */
   int64_t param_slot, state_slot, grad, workspace_each;   /* bytes of one slot / buffer on the device */
-  int64_t device_bytes;                          /* arena: 2 param slots + 2 state slots + grad + K workspaces */
+  int64_t device_bytes;                          /* arena: min(K,2) param slots + min(K,3) state slots + grad + K workspaces */
   int64_t resident_bytes;                        /* what the same K ministages need when all stay on the GPU:
                                                     K * (params + grads + optimizer state + workspace) */
 } ministages_memory;
@@ -95,7 +97,7 @@ int ministages_traffic(const ministages_t* ms, int64_t* h2d_bytes, int64_t* d2h_
 /* host string, valid until the next call on ms; ms may be NULL for errors of query/init */
 const char* ministages_last_error(const ministages_t* ms);
 
-/* Waits for the copy stream, then frees the K stages and the object (not the caller's buffers). */
+/* Waits for the copy streams, then frees the K stages and the object (not the caller's buffers). */
 void ministages_destroy(ministages_t* ms);
 
 #ifdef __cplusplus

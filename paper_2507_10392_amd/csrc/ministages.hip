@@ -16,6 +16,11 @@ thread_local std::string g_ms_err;
 
 int64_t up256(int64_t n) { return (n + 255) & ~(int64_t)255; }
 
+// Parameters: the ministage that computes and the one being prefetched.  Optimizer state: the one in use, the one
+// whose store is still in flight and the one being loaded, so that a slow store delays nobody.
+int param_slots(int K) { return K < 2 ? K : 2; }
+int state_slots(int K) { return K < 3 ? K : 3; }
+
 struct Sizes {
   int64_t P = 0, shard = 0, E = 0;
   stage_memory smem{};
@@ -49,8 +54,7 @@ int sizes_of(const ministages_config* c, Sizes& z, std::string& err) {
   m.state_slot = s;
   m.grad = up256(z.P * 4);
   m.workspace_each = up256(z.smem.workspace);
-  const int slots = K < 2 ? 1 : 2;
-  m.device_bytes = slots * (m.param_slot + m.state_slot) + m.grad + (int64_t)K * m.workspace_each;
+  m.device_bytes = param_slots(K) * m.param_slot + state_slots(K) * m.state_slot + m.grad + (int64_t)K * m.workspace_each;
   m.resident_bytes = (int64_t)K * (z.smem.params + z.smem.grads + z.smem.optim + z.smem.workspace);
   return STAGE_OK;
 }
@@ -58,9 +62,11 @@ int sizes_of(const ministages_config* c, Sizes& z, std::string& err) {
 struct Slot {
   int owner = -1;
   bool fresh = false;        // filled by a load that the stage's stream has not waited for yet
-  bool stored = false;       // a store reads the slot: the stage's stream must wait before it writes the slot again
+  bool stored = false;       // a store read the slot: whoever writes the slot next (a load, the optimizer) waits for store_done
   bool computed = false;     // compute_done has been recorded
-  hipEvent_t copy_done = nullptr, compute_done = nullptr;
+  hipEvent_t copy_done = nullptr;      // load stream: the last load into the slot has finished
+  hipEvent_t store_done = nullptr;     // store stream: the last store from the slot has finished
+  hipEvent_t compute_done = nullptr;   // stage's stream: the last call that used the slot has finished
 };
 
 }  // namespace
@@ -68,14 +74,17 @@ struct Slot {
 struct ministages {
   ministages_config cfg;
   Sizes z;
-  int K = 0, nslots = 0;
-  hipStream_t st = nullptr, copy_st = nullptr;
+  int K = 0, np = 0, ns = 0;   // ministages, parameter slots, optimizer-state slots
+  hipStream_t st = nullptr;
+  // Host-to-device and device-to-host copies run side by side.  (A third stream for the small stores of the
+  // updated working parameters was tried: with three copy kernels in flight the compute kernels lost 20 %.)
+  hipStream_t load_st = nullptr, store_st = nullptr;
   char* host = nullptr;
   char* pslot[2] = {nullptr, nullptr};
-  char* sslot[2] = {nullptr, nullptr};
+  char* sslot[3] = {nullptr, nullptr, nullptr};
   float* grad = nullptr;
   std::vector<stage_t*> stages;
-  Slot ps[2], ss[2];
+  Slot ps[2], ss[3];
   int grad_owner = -1;       // ministage whose gradients sit in the shared buffer
   int64_t h2d = 0, d2h = 0;
   std::string err;
@@ -91,51 +100,59 @@ bool ok(ministages_t* ms, hipError_t e, const char* what) {
   return false;
 }
 
+hipError_t d2h(ministages_t* ms, void* dst, const void* src, int64_t n) {
+  return hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToHost, ms->store_st);
+}
+
 char* host_of(ministages_t* ms, int k, int64_t off) { return ms->host + (int64_t)k * ms->z.m.per_stage_host + off; }
 
-// Before a copy writes a slot, everything the stage's stream did with it must be over.
-bool copy_waits_for_compute(ministages_t* ms, Slot& s) {
-  return !s.computed || ok(ms, hipStreamWaitEvent(ms->copy_st, s.compute_done, 0), "stream wait");
+// Before a load overwrites a slot, everything the stage's stream did with it must be over, and so must the
+// store that copies its old content (or an older version of the incoming data) to the host.
+bool load_waits(ministages_t* ms, Slot& s) {
+  if (s.computed && !ok(ms, hipStreamWaitEvent(ms->load_st, s.compute_done, 0), "stream wait")) return false;
+  if (s.stored && !ok(ms, hipStreamWaitEvent(ms->load_st, s.store_done, 0), "stream wait")) return false;
+  return true;
 }
 
 bool load_params(ministages_t* ms, int k) {
-  Slot& s = ms->ps[k % ms->nslots];
+  Slot& s = ms->ps[k % ms->np];
   if (s.owner == k) return true;
-  if (!copy_waits_for_compute(ms, s)) return false;
+  if (!load_waits(ms, s)) return false;
   const int64_t n = ms->z.P * ms->z.E;
-  if (!ok(ms, hipMemcpyAsync(ms->pslot[k % ms->nslots], host_of(ms, k, ms->z.m.off_params), n, hipMemcpyHostToDevice, ms->copy_st),
+  if (!ok(ms, hipMemcpyAsync(ms->pslot[k % ms->np], host_of(ms, k, ms->z.m.off_params), n, hipMemcpyHostToDevice, ms->load_st),
           "parameter load"))
     return false;
   ms->h2d += n;
   s.owner = k; s.fresh = true;
-  return ok(ms, hipEventRecord(s.copy_done, ms->copy_st), "event record");
+  return ok(ms, hipEventRecord(s.copy_done, ms->load_st), "event record");
 }
 
 bool load_state(ministages_t* ms, int k) {
-  Slot& s = ms->ss[k % ms->nslots];
+  Slot& s = ms->ss[k % ms->ns];
   if (s.owner == k || ms->z.shard == 0) return true;
-  if (!copy_waits_for_compute(ms, s)) return false;
+  if (!load_waits(ms, s)) return false;
   const Sizes& z = ms->z;
-  char* d = ms->sslot[k % ms->nslots];
+  char* d = ms->sslot[k % ms->ns];
   const int64_t n = z.shard * 4;
   if (z.st_master >= 0 &&
-      !ok(ms, hipMemcpyAsync(d + z.st_master, host_of(ms, k, z.m.off_master), n, hipMemcpyHostToDevice, ms->copy_st), "state load"))
+      !ok(ms, hipMemcpyAsync(d + z.st_master, host_of(ms, k, z.m.off_master), n, hipMemcpyHostToDevice, ms->load_st), "state load"))
     return false;
-  if (!ok(ms, hipMemcpyAsync(d + z.st_m, host_of(ms, k, z.m.off_m), n, hipMemcpyHostToDevice, ms->copy_st), "state load")) return false;
-  if (!ok(ms, hipMemcpyAsync(d + z.st_v, host_of(ms, k, z.m.off_v), n, hipMemcpyHostToDevice, ms->copy_st), "state load")) return false;
+  if (!ok(ms, hipMemcpyAsync(d + z.st_m, host_of(ms, k, z.m.off_m), n, hipMemcpyHostToDevice, ms->load_st), "state load")) return false;
+  if (!ok(ms, hipMemcpyAsync(d + z.st_v, host_of(ms, k, z.m.off_v), n, hipMemcpyHostToDevice, ms->load_st), "state load")) return false;
   ms->h2d += n * (z.st_master >= 0 ? 3 : 2);
   s.owner = k; s.fresh = true;
-  return ok(ms, hipEventRecord(s.copy_done, ms->copy_st), "event record");
+  return ok(ms, hipEventRecord(s.copy_done, ms->load_st), "event record");
 }
 
 // The stage's stream is about to use the slot: wait for a load it has not seen yet and, before writing, for a
-// store that may still be reading it.  copy_done is recorded after every copy of the slot on the in-order copy
-// stream, so its latest record covers all of them.
+// store that may still be reading it.
 bool compute_waits_for_copy(ministages_t* ms, Slot& s, bool will_write) {
-  const bool wait = s.fresh || (will_write && s.stored);
-  s.fresh = false;
-  if (will_write) s.stored = false;
-  return !wait || ok(ms, hipStreamWaitEvent(ms->st, s.copy_done, 0), "stream wait");
+  if (s.fresh) {
+    s.fresh = false;
+    if (!ok(ms, hipStreamWaitEvent(ms->st, s.copy_done, 0), "stream wait")) return false;
+  }
+  if (will_write && s.stored && !ok(ms, hipStreamWaitEvent(ms->st, s.store_done, 0), "stream wait")) return false;
+  return true;
 }
 
 bool mark_computed(ministages_t* ms, Slot& s) {
@@ -147,25 +164,26 @@ bool mark_computed(ministages_t* ms, Slot& s) {
 bool store_shard(ministages_t* ms, int k) {
   const Sizes& z = ms->z;
   if (z.shard == 0) return true;
-  Slot& p = ms->ps[k % ms->nslots];
-  Slot& s = ms->ss[k % ms->nslots];
-  if (!ok(ms, hipStreamWaitEvent(ms->copy_st, s.compute_done, 0), "stream wait")) return false;   // recorded after the step
+  Slot& p = ms->ps[k % ms->np];
+  Slot& s = ms->ss[k % ms->ns];
+  // s.compute_done was recorded after the step
+  if (!ok(ms, hipStreamWaitEvent(ms->store_st, s.compute_done, 0), "stream wait")) return false;
   const int64_t b = ms->cfg.stage.shard_begin, n4 = z.shard * 4, ne = z.shard * z.E;
-  char* d = ms->sslot[k % ms->nslots];
-  if (!ok(ms, hipMemcpyAsync(host_of(ms, k, z.m.off_params) + b * z.E, ms->pslot[k % ms->nslots] + b * z.E, ne, hipMemcpyDeviceToHost,
-                             ms->copy_st), "parameter store"))
+  char* d = ms->sslot[k % ms->ns];
+  if (!ok(ms, d2h(ms, host_of(ms, k, z.m.off_params) + b * z.E, ms->pslot[k % ms->np] + b * z.E, ne), "parameter store"))
     return false;
+  // The parameter slot is free for the next load as soon as its shard has left; the optimizer-state slot (and
+  // the host block's state) only when the three larger copies are through.  Whoever writes a slot next (a load,
+  // the ministage's next optimizer step) waits for its store_done.
+  if (!ok(ms, hipEventRecord(p.store_done, ms->store_st), "event record")) return false;
   if (z.st_master >= 0 &&
-      !ok(ms, hipMemcpyAsync(host_of(ms, k, z.m.off_master), d + z.st_master, n4, hipMemcpyDeviceToHost, ms->copy_st), "state store"))
+      !ok(ms, d2h(ms, host_of(ms, k, z.m.off_master), d + z.st_master, n4), "state store"))
     return false;
-  if (!ok(ms, hipMemcpyAsync(host_of(ms, k, z.m.off_m), d + z.st_m, n4, hipMemcpyDeviceToHost, ms->copy_st), "state store")) return false;
-  if (!ok(ms, hipMemcpyAsync(host_of(ms, k, z.m.off_v), d + z.st_v, n4, hipMemcpyDeviceToHost, ms->copy_st), "state store")) return false;
+  if (!ok(ms, d2h(ms, host_of(ms, k, z.m.off_m), d + z.st_m, n4), "state store")) return false;
+  if (!ok(ms, d2h(ms, host_of(ms, k, z.m.off_v), d + z.st_v, n4), "state store")) return false;
   ms->d2h += ne + n4 * (z.st_master >= 0 ? 3 : 2);
-  // Later loads into these slots follow on the same in-order copy stream.  The stage's stream must not write
-  // the slots again (the ministage's next optimizer step) before the store has read them.
   p.stored = s.stored = true;
-  return ok(ms, hipEventRecord(p.copy_done, ms->copy_st), "event record") &&
-         ok(ms, hipEventRecord(s.copy_done, ms->copy_st), "event record");
+  return ok(ms, hipEventRecord(s.store_done, ms->store_st), "event record");
 }
 
 bool check_k(ministages_t* ms, int k) { return k >= 0 && k < ms->K; }
@@ -209,30 +227,30 @@ int ministages_init(const ministages_config* cfg, void* hip_stream, void* host_s
   if (at.type != hipMemoryTypeHost) return fail(nullptr, STAGE_ERR_ARG, "host_state is not page-locked host memory");
 
   ministages_t* ms = new ministages();
-  ms->cfg = *cfg; ms->z = z; ms->K = cfg->n_ministages; ms->nslots = ms->K < 2 ? 1 : 2;
+  ms->cfg = *cfg; ms->z = z; ms->K = cfg->n_ministages; ms->np = param_slots(ms->K); ms->ns = state_slots(ms->K);
   ms->st = (hipStream_t)hip_stream;
   ms->host = (char*)host_state;
   char* p = (char*)device_arena;
-  for (int i = 0; i < ms->nslots; ++i) { ms->pslot[i] = p; p += z.m.param_slot; }
-  for (int i = 0; i < ms->nslots; ++i) { ms->sslot[i] = p; p += z.m.state_slot; }
+  for (int i = 0; i < ms->np; ++i) { ms->pslot[i] = p; p += z.m.param_slot; }
+  for (int i = 0; i < ms->ns; ++i) { ms->sslot[i] = p; p += z.m.state_slot; }
   ms->grad = (float*)p; p += z.m.grad;
   auto bail = [&](int code, const std::string& msg) {
     ministages_destroy(ms);
     return fail(nullptr, code, msg);
   };
-  hipError_t e = hipStreamCreateWithFlags(&ms->copy_st, hipStreamNonBlocking);   // default priority
-  for (int i = 0; i < 2 && e == hipSuccess; ++i) {
-    for (Slot* s : {&ms->ps[i], &ms->ss[i]}) {
-      if (e == hipSuccess) e = hipEventCreateWithFlags(&s->copy_done, hipEventDisableTiming);
-      if (e == hipSuccess) e = hipEventCreateWithFlags(&s->compute_done, hipEventDisableTiming);
-    }
+  hipError_t e = hipStreamCreateWithFlags(&ms->load_st, hipStreamNonBlocking);   // default priority, both
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&ms->store_st, hipStreamNonBlocking);
+  for (Slot* s : {&ms->ps[0], &ms->ps[1], &ms->ss[0], &ms->ss[1], &ms->ss[2]}) {
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->copy_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->store_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s->compute_done, hipEventDisableTiming);
   }
   if (e == hipSuccess) e = hipMemsetAsync(ms->grad, 0, z.P * 4, ms->st);
   if (e != hipSuccess) return bail(STAGE_ERR_DEVICE, std::string("ministages_init: ") + hipGetErrorString(e));
   for (int k = 0; k < ms->K; ++k) {
-    char* sd = ms->sslot[k % ms->nslots];
+    char* sd = ms->sslot[k % ms->ns];
     stage_t* s = nullptr;
-    rc = stage_init(&cfg->stage, hip_stream, ms->pslot[k % ms->nslots], z.st_master >= 0 && z.shard > 0 ? (float*)(sd + z.st_master) : nullptr,
+    rc = stage_init(&cfg->stage, hip_stream, ms->pslot[k % ms->np], z.st_master >= 0 && z.shard > 0 ? (float*)(sd + z.st_master) : nullptr,
                     ms->grad, z.shard > 0 ? (float*)(sd + z.st_m) : nullptr, z.shard > 0 ? (float*)(sd + z.st_v) : nullptr, p,
                     z.m.workspace_each, &s);
     if (rc != STAGE_OK) return bail(rc, std::string("stage_init of ministage ") + std::to_string(k) + ": " + stage_last_error(nullptr));
@@ -248,7 +266,7 @@ int ministages_forward(ministages_t* ms, int32_t k, int32_t mb, const void* x_or
                        float* loss_out) {
   if (!ms) return STAGE_ERR_ARG;
   if (!check_k(ms, k)) return fail(ms, STAGE_ERR_ARG, "ministage index out of range");
-  Slot& s = ms->ps[k % ms->nslots];
+  Slot& s = ms->ps[k % ms->np];
   if (!load_params(ms, k) || !compute_waits_for_copy(ms, s, false)) return STAGE_ERR_DEVICE;
   const int rc = stage_forward(ms->stages[k], mb, x_or_ids, y_out, targets, loss_out);
   if (!mark_computed(ms, s)) return STAGE_ERR_DEVICE;
@@ -263,7 +281,7 @@ int ministages_backward(ministages_t* ms, int32_t k, int32_t mb, const void* dy,
   if (ms->grad_owner >= 0 && ms->grad_owner != k)
     return fail(ms, STAGE_ERR_STATE, "the gradient buffer still holds ministage " + std::to_string(ms->grad_owner) +
                                          "'s gradients: run its optimizer step first");
-  Slot& s = ms->ps[k % ms->nslots];
+  Slot& s = ms->ps[k % ms->np];
   if (!load_params(ms, k) || !compute_waits_for_copy(ms, s, false)) return STAGE_ERR_DEVICE;
   const int rc = stage_backward(ms->stages[k], mb, dy, dx_out, loss_scale);
   if (!mark_computed(ms, s)) return STAGE_ERR_DEVICE;
@@ -287,8 +305,8 @@ int ministages_optimizer_step(ministages_t* ms, int32_t k, int64_t t, float grad
   if (!check_k(ms, k)) return fail(ms, STAGE_ERR_ARG, "ministage index out of range");
   if (ms->grad_owner >= 0 && ms->grad_owner != k)
     return fail(ms, STAGE_ERR_STATE, "the gradient buffer holds ministage " + std::to_string(ms->grad_owner) + "'s gradients");
-  Slot& p = ms->ps[k % ms->nslots];
-  Slot& s = ms->ss[k % ms->nslots];
+  Slot& p = ms->ps[k % ms->np];
+  Slot& s = ms->ss[k % ms->ns];
   if (!load_params(ms, k) || !load_state(ms, k)) return STAGE_ERR_DEVICE;
   if (!compute_waits_for_copy(ms, p, true) || !compute_waits_for_copy(ms, s, true)) return STAGE_ERR_DEVICE;
   const int rc = stage_optimizer_step(ms->stages[k], t, grad_scale);
@@ -312,14 +330,16 @@ const char* ministages_last_error(const ministages_t* ms) { return ms ? ms->err.
 
 void ministages_destroy(ministages_t* ms) {
   if (!ms) return;
-  if (ms->copy_st) (void)hipStreamSynchronize(ms->copy_st);   // no copy may outlive the caller's buffers
+  for (hipStream_t c : {ms->load_st, ms->store_st})
+    if (c) (void)hipStreamSynchronize(c);   // no copy may outlive the caller's buffers
   for (stage_t* s : ms->stages) stage_destroy(s);
-  for (int i = 0; i < 2; ++i)
-    for (Slot* s : {&ms->ps[i], &ms->ss[i]}) {
-      if (s->copy_done) (void)hipEventDestroy(s->copy_done);
-      if (s->compute_done) (void)hipEventDestroy(s->compute_done);
-    }
-  if (ms->copy_st) (void)hipStreamDestroy(ms->copy_st);
+  for (Slot* s : {&ms->ps[0], &ms->ps[1], &ms->ss[0], &ms->ss[1], &ms->ss[2]}) {
+    if (s->copy_done) (void)hipEventDestroy(s->copy_done);
+    if (s->store_done) (void)hipEventDestroy(s->store_done);
+    if (s->compute_done) (void)hipEventDestroy(s->compute_done);
+  }
+  for (hipStream_t c : {ms->load_st, ms->store_st})
+    if (c) (void)hipStreamDestroy(c);
   delete ms;
 }
 

@@ -94,8 +94,7 @@ def test_ministages_memory_report():
         up = lambda n: (n + 255) // 256 * 256
         assert m["off_params"] == 0 and m["off_master"] == up(2 * P) and m["off_m"] == m["off_master"] + up(4 * sh)
         assert m["per_stage_host"] == up(2 * P) + 3 * up(4 * sh) and m["host_bytes"] == K * m["per_stage_host"]
-        slots = min(K, 2)
-        assert m["device_bytes"] == slots * (up(2 * P) + 3 * up(4 * sh)) + up(4 * P) + K * up(mem["workspace"])
+        assert m["device_bytes"] == min(K, 2) * up(2 * P) + min(K, 3) * 3 * up(4 * sh) + up(4 * P) + K * up(mem["workspace"])
         assert m["resident_bytes"] == K * (mem["params"] + mem["grads"] + mem["optim"] + mem["workspace"])
     assert "ministages_forward" in declared_symbols() and "ministages_destroy" in declared_symbols()
     with pytest.raises(zs.StageError) as ei:

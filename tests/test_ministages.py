@@ -34,8 +34,7 @@ class Group:
                 self.state(k, "master").copy_(torch.from_numpy(inp_full.master[k * self.P + self.b:k * self.P + self.e]))
         self.arena = torch.empty(m["device_bytes"], dtype=torch.uint8, device="cuda")
         self.ms = zs.Ministages(self.cc, K, self.host, self.arena)
-        slots = min(K, 2)
-        g0 = slots * (m["param_slot"] + m["state_slot"])
+        g0 = min(K, 2) * m["param_slot"] + min(K, 3) * m["state_slot"]
         self.grad = self.arena[g0:g0 + 4 * self.P].view(torch.float32)     # the shared gradient buffer (test only)
 
     def params(self, k):
