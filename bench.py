@@ -156,6 +156,49 @@ class MinistageRunner:
         self.ms.close()
 
 
+def planner_profile(cfg):
+    """What the paper's planner takes from a GPU (Section 4.3, "Profiling" and "Memory Model"): the stage timed at
+    small microbatch sizes with stage_time_layers, the library's least-squares line per pass, the line's
+    prediction against a measurement at larger sizes, and the four memory terms of stage_query."""
+    import torch
+    import paper_2507_10392_amd as zs
+    dev = torch.device("cuda:0")
+    td = torch.bfloat16 if cfg.dtype == 1 else torch.float32
+    base = cfg.with_(layers=min(cfg.layers, 2), num_microbatches=1, has_embed=0, has_head=0, vocab=0, recompute=0, offload_acts=0)
+    fit_sizes, held_out = [1, 2, 3, 4], [6, 8]
+    points = {}
+    for mb in fit_sizes + held_out:
+        c = base.with_(microbatch=mb * cfg.microbatch)
+        cc = zs.make_config(c)
+        P, mem, _ = zs.query(cc)
+        b, e = cc.shard_begin, cc.shard_end
+        params = torch.empty(P, dtype=td, device=dev)
+        fill_params(c, params, torch)
+        master = params[b:e].float() if cfg.dtype == 1 else None
+        grad = torch.zeros(P, dtype=torch.float32, device=dev)
+        m, v = torch.zeros(max(e - b, 1), device=dev), torch.zeros(max(e - b, 1), device=dev)
+        ws = torch.empty(mem["workspace"], dtype=torch.uint8, device=dev)
+        x = torch.randn(c.tokens, c.hidden, device=dev).to(td)
+        dy = (torch.randn(c.tokens, c.hidden, device=dev) * 0.01).to(td)
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        st = zs.Stage(cc, params, master, grad, m, v, ws)
+        f, bw = st.time_layers(x, y, dy, dx, reps=3)
+        st.close()
+        points[mb] = (f / base.layers, bw / base.layers)
+        del params, master, grad, m, v, ws, x, dy, y, dx
+    out = {"workload": f"{cfg.name}: one layer, microbatch sizes in units of {cfg.microbatch} x {cfg.seq} tokens",
+           "ms_per_layer": {str(k): {"fwd": round(p[0], 4), "bwd": round(p[1], 4)} for k, p in points.items()}}
+    for i, name in enumerate(("fwd", "bwd")):
+        a, sl, r2 = zs.fit_linear([float(k) for k in fit_sizes], [points[k][i] for k in fit_sizes])
+        out[name] = {"intercept_ms": a, "slope_ms_per_unit": sl, "r2": r2, "fitted_on": fit_sizes,
+                     "held_out": {str(k): {"predicted": a + sl * k, "measured": points[k][i],
+                                            "error": (a + sl * k) / points[k][i] - 1.0} for k in held_out}}
+    _, mem, _ = zs.query(zs.make_config(cfg))
+    out["memory_model_bytes"] = {k: mem[k] for k in ("params", "grads", "optim", "activations")}
+    out["memory_model_bytes"]["total"] = sum(out["memory_model_bytes"].values())
+    print(json.dumps({"planner_profile": out}))
+
+
 def traffic_probe(cfg):
     """For rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: launches a plain copy of known size (1 GiB read,
     1 GiB written, torch's elementwise copy kernel) and then the weight-gradient GEMMs of one decoder
@@ -204,6 +247,8 @@ def main():
     ap.add_argument("--ministages", type=int, default=0, metavar="K",
                     help="cut the workload's layers into K ministages that share two parameter slots on the GPU, the rest "
                          "waiting in pinned host memory (include/ministages.h); interior stages only")
+    ap.add_argument("--planner-profile", action="store_true",
+                    help="time one layer at small microbatch sizes, fit the runtime lines and print them with the memory terms")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a 1 GiB copy and the workload's weight-gradient GEMMs only (for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -233,6 +278,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.traffic_probe:
         traffic_probe(cfg)
+        return
+    if args.planner_profile:
+        planner_profile(cfg)
         return
     torch.manual_seed(cfg.seed)
     cc = zs.make_config(cfg)

@@ -190,6 +190,28 @@ typedef struct {
 int stage_profile(stage_t* s, int32_t enable);
 int stage_profile_read(stage_t* s, stage_kernel_stat* out, int32_t n);
 
+/* Runtime profile for a planner (Section 4.3, "Profiling": layer runtimes are measured at small batch sizes
+ * and a linear model predicts the sizes that were not measured; together with the four memory terms of
+ * stage_query this is what the paper's planner consumes).
+ *
+ * stage_time_layers measures this stage at its configured microbatch size: one untimed and then reps timed
+ * rounds of stage_forward + stage_backward + stage_accumulate on slot 0, bracketed by HIP events on the stage's
+ * stream.  Arguments as for stage_forward / stage_backward (caller-owned device buffers).  Writes the mean
+ * milliseconds of one forward and of one backward (+accumulate) of the whole stage; divide by the layer count
+ * for a per-layer figure.  Legal only on a stage with nothing outstanding and nothing accumulated
+ * (STAGE_ERR_STATE otherwise); SYNCHRONISES the stream; leaves grad_acc all zero and the schedule state as it
+ * found it.
+ *
+ * stage_fit_linear is host-only: ordinary least squares y = intercept + slope * x over n >= 2 points with at
+ * least two distinct x (STAGE_ERR_ARG otherwise); r2 is the coefficient of determination (1 when all y are
+ * equal). */
+typedef struct {
+  double intercept, slope, r2;
+} stage_linear_fit;
+int stage_time_layers(stage_t* s, const void* x_or_ids, void* y_out, const void* dy, void* dx_out, const int32_t* targets,
+                      float* loss_out, int32_t reps, double* fwd_ms, double* bwd_ms);
+int stage_fit_linear(const double* x, const double* y, int32_t n, stage_linear_fit* out);
+
 /* host string, valid until the next call on s; s may be NULL for errors of stage_query/init */
 const char* stage_last_error(const stage_t* s);
 

@@ -411,3 +411,23 @@ def stage_step(cfg, compute_params, xs, dys=None, targets=None, loss_scale=1.0):
         caches[i] = None
     key = "loss" if cfg.has_head else "y"
     return {key: outs, "dx": dxs, "grad": grad}
+
+
+# --------------------------------------------------------------------------
+# runtime model for the planner
+# --------------------------------------------------------------------------
+
+
+def linear_fit(x, y):
+    """Ordinary least squares y = a + b*x (the paper's Section 4.3, "Profiling": a linear model fitted to
+    runtimes measured at small batch sizes predicts the others).  The textbook definition: b = cov(x, y) /
+    var(x), a = mean(y) - b*mean(x); r2 = 1 - SS_res / SS_tot (1 when all y are equal).
+    Returns (a, b, r2)."""
+    x = np.asarray(x, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    xb, yb = x.mean(), y.mean()
+    b = ((x - xb) * (y - yb)).sum() / ((x - xb) ** 2).sum()
+    a = yb - b * xb
+    ss_res = ((y - (a + b * x)) ** 2).sum()
+    ss_tot = ((y - yb) ** 2).sum()
+    return float(a), float(b), float(1.0 - ss_res / ss_tot) if ss_tot > 0 else 1.0

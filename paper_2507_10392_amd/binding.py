@@ -48,6 +48,10 @@ class MinistagesMemoryC(C.Structure):
                                          "resident_bytes")]
 
 
+class StageLinearFitC(C.Structure):
+    _fields_ = [("intercept", C.c_double), ("slope", C.c_double), ("r2", C.c_double)]
+
+
 class StageSegmentC(C.Structure):
     _fields_ = [("name", C.c_char * 32), ("offset", C.c_int64), ("rows", C.c_int64), ("cols", C.c_int64)]
 
@@ -80,6 +84,8 @@ def lib():
         L.stage_graph_replayed.argtypes = [vp, i32]
         L.stage_profile.argtypes = [vp, i32]
         L.stage_profile_read.argtypes = [vp, C.POINTER(StageKernelStatC), i32]
+        L.stage_time_layers.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.stage_fit_linear.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), i32, C.POINTER(StageLinearFitC)]
         L.stage_last_error.argtypes = [vp]
         L.stage_last_error.restype = C.c_char_p
         L.stage_destroy.argtypes = [vp]
@@ -141,6 +147,14 @@ def query(cc: StageConfigC):
     return n.value, {k: getattr(mem, k) for k, _ in StageMemoryC._fields_}, ns.value
 
 
+def fit_linear(x, y):
+    """Least-squares line through (x, y) by the library (stage_fit_linear) -> (intercept, slope, r2)."""
+    n = len(x)
+    xa, ya, out = (C.c_double * n)(*x), (C.c_double * n)(*y), StageLinearFitC()
+    _check(lib().stage_fit_linear(xa, ya, n, C.byref(out)))
+    return out.intercept, out.slope, out.r2
+
+
 def layout(cc: StageConfigC):
     _, _, ns = query(cc)
     segs = (StageSegmentC * ns)()
@@ -188,6 +202,13 @@ class Stage:
 
     def profile(self, enable):
         _check(lib().stage_profile(self.h, 1 if enable else 0), self.h)
+
+    def time_layers(self, x_or_ids, y_out, dy, dx_out, targets=None, loss_out=None, reps=3):
+        """-> (forward ms, backward ms) of one microbatch through the whole stage (stage_time_layers)."""
+        f, b = C.c_double(), C.c_double()
+        _check(lib().stage_time_layers(self.h, _ptr(x_or_ids), _ptr(y_out), _ptr(dy), _ptr(dx_out), _ptr(targets),
+                                       _ptr(loss_out), reps, C.byref(f), C.byref(b)), self.h)
+        return f.value, b.value
 
     def profile_read(self):
         out = (StageKernelStatC * 64)()

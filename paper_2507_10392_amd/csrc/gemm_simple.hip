@@ -3,6 +3,8 @@
 // dimensions).  64x64x16 tiles, 256 threads, 4x4 outputs per thread, every access bounds-checked.
 #include "kernels.h"
 
+#include <vector>
+
 namespace zs {
 
 template <typename T, int TA, int TB>
@@ -107,7 +109,11 @@ int gemm_select(DType dt, const Gemm& g, int force) {
   return gemm_mfma_supported(dt, g) ? GEMM_MFMA : GEMM_SIMPLE;
 }
 
-hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
+namespace {
+
+// One launch: the MFMA kernel when it takes the arguments, else the plain kernel (with the rotation and the
+// two-part K range done in extra passes).
+hipError_t gemm_one(hipStream_t st, DType dt, const Gemm& g, int force) {
   if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, g);   // rotation fused into its epilogue
   if (g.A2) {   // two-part K range: one plain product per part
     Gemm a = g, b = g;
@@ -121,6 +127,85 @@ hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
   for (int z = 0; e == hipSuccess && g.rope && z < g.rope_batches && z < g.batch; ++z)
     e = rope_apply(st, dt, g.M, g.rope_S, g.N, g.rope_d, (char*)g.C + (int64_t)z * g.sC * elem, g.ldc, g.rope, 1.0f);
   return e;
+}
+
+// The MFMA kernel addresses each operand with 32-bit byte offsets below 2^30.  A bf16 product whose token-sized
+// operand is larger (microbatches of more than about 24 k tokens at a 2 x 11008-wide activation) is cut into
+// launches that each stay below the limit, instead of falling to the plain kernel:
+//   A stored [M, K] (tokens = rows): ranges of rows of A, C and the residual (a multiple of the tile height and,
+//     with a fused rotation, of the sequence length, so that row mod S is unchanged);
+//   the accumulating product with A stored [K, M] and B [K, N] (tokens = K): ranges of K, each added into C.
+// Returns false when the arguments are not of that kind; the caller then runs them as one launch.
+constexpr int64_t OPERAND_LIMIT = 1ll << 30;
+
+bool split_rows(const Gemm& g, std::vector<Gemm>& parts) {
+  if (g.transA || g.A2 || g.lda <= 0) return false;
+  if ((int64_t)g.M * g.lda * 2 < OPERAND_LIMIT) return false;
+  int64_t unit = 256;
+  if (g.rope) {   // least common multiple of the tile height and the sequence length
+    int64_t a = unit, b = g.rope_S;
+    while (b) { const int64_t t = a % b; a = b; b = t; }
+    unit = unit / a * g.rope_S;
+  }
+  int64_t rows = (OPERAND_LIMIT - 1 - (int64_t)g.K * 2) / (g.lda * 2) / unit * unit;
+  if (rows <= 0) return false;
+  for (int64_t r0 = 0; r0 < g.M; r0 += rows) {
+    Gemm p = g;
+    p.M = (int)(g.M - r0 < rows ? g.M - r0 : rows);
+    p.A = (const char*)g.A + r0 * g.lda * 2;
+    p.C = (char*)g.C + r0 * g.ldc * (g.c_f32_accum ? 4 : 2);
+    if (g.resid) p.resid = (const char*)g.resid + r0 * g.ldr * 2;
+    parts.push_back(p);
+  }
+  return true;
+}
+
+bool split_k(const Gemm& g, std::vector<Gemm>& parts) {
+  if (!g.transA || g.transB || !g.c_f32_accum || g.kseg || g.A2 || g.lda <= 0 || g.ldb <= 0) return false;
+  const int64_t ld = g.lda > g.ldb ? g.lda : g.ldb;
+  if ((int64_t)g.K * ld * 2 < OPERAND_LIMIT) return false;
+  const int64_t kc = (OPERAND_LIMIT - 1) / (ld * 2) / 64 * 64;
+  if (kc <= 0) return false;
+  for (int64_t k0 = 0; k0 < g.K; k0 += kc) {
+    Gemm p = g;
+    p.K = (int)(g.K - k0 < kc ? g.K - k0 : kc);
+    p.A = (const char*)g.A + k0 * g.lda * 2;
+    p.B = (const char*)g.B + k0 * g.ldb * 2;
+    parts.push_back(p);
+  }
+  return true;
+}
+
+}  // namespace
+
+bool gemm_splits(DType dt, const Gemm& g) {
+  if (dt != BF16 || gemm_mfma_supported(dt, g)) return false;
+  std::vector<Gemm> parts;
+  if (!(split_rows(g, parts) || split_k(g, parts))) return false;
+  for (const Gemm& p : parts)
+    if (!gemm_mfma_supported(dt, p)) return false;
+  return true;
+}
+
+hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
+  if (dt == BF16 && force != GEMM_SIMPLE && !gemm_mfma_supported(dt, g)) {
+    std::vector<Gemm> parts;
+    if (g.A2) {   // the two parts of a paired weight gradient on their own, each cut further if it has to be
+      Gemm a = g, b = g;
+      a.A2 = a.B2 = nullptr; a.K = g.kseg; a.kseg = 0;
+      b.A = g.A2; b.B = g.B2; b.A2 = b.B2 = nullptr; b.K = g.K - g.kseg; b.kseg = 0;
+      const hipError_t e = gemm(st, dt, a, force);
+      return e != hipSuccess ? e : gemm(st, dt, b, force);
+    }
+    if (split_rows(g, parts) || split_k(g, parts)) {
+      for (const Gemm& p : parts) {
+        const hipError_t e = gemm_one(st, dt, p, force);
+        if (e != hipSuccess) return e;
+      }
+      return hipSuccess;
+    }
+  }
+  return gemm_one(st, dt, g, force);
 }
 
 }  // namespace zs

@@ -36,6 +36,8 @@ enum GemmImpl { GEMM_AUTO = 0, GEMM_SIMPLE = 1, GEMM_MFMA = 2 };
 // Returns which implementation a call with these arguments runs (GEMM_SIMPLE or GEMM_MFMA).
 int gemm_select(DType dt, const Gemm& g, int force);
 hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force);
+// True when gemm() runs the call as several MFMA launches because an operand exceeds the kernel's 2^30-byte range.
+bool gemm_splits(DType dt, const Gemm& g);
 hipError_t gemm_simple(hipStream_t st, DType dt, const Gemm& g);
 bool gemm_mfma_supported(DType dt, const Gemm& g);
 hipError_t gemm_mfma(hipStream_t st, const Gemm& g);

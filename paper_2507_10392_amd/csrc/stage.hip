@@ -392,7 +392,7 @@ bool do_gemm(stage_t* s, const Gemm& g) {
   const int impl = gemm_select(dt_of(s), g, GEMM_AUTO);
   static const char* names[2][4] = {{"gemm_simple_nn", "gemm_simple_nt", "gemm_simple_tn", "gemm_simple_tt"},
                                     {"gemm_mfma_nn", "gemm_mfma_nt", "gemm_mfma_tn", "gemm_mfma_tt"}};
-  const char* cls = names[impl == GEMM_MFMA][g.transA * 2 + g.transB];
+  const char* cls = names[impl == GEMM_MFMA || gemm_splits(dt_of(s), g)][g.transA * 2 + g.transB];
   const double flops = 2.0 * g.M * g.N * g.K * g.batch;
   return run(s, cls, flops, 0.0, [&] { return gemm(s->st, dt_of(s), g, GEMM_AUTO); });
 }
@@ -957,6 +957,62 @@ int stage_profile_read(stage_t* s, stage_kernel_stat* out, int32_t n) {
   s->recs.clear();
   s->ev_used = 0;
   return nc;
+}
+
+int stage_time_layers(stage_t* s, const void* x_or_ids, void* y_out, const void* dy, void* dx_out, const int32_t* targets,
+                      float* loss_out, int32_t reps, double* fwd_ms, double* bwd_ms) {
+  if (!s) return STAGE_ERR_ARG;
+  if (reps < 1 || reps > 1000 || !fwd_ms || !bwd_ms) return fail(s, STAGE_ERR_ARG, "reps must be in 1..1000 and the outputs not NULL");
+  if (s->pending >= 0 || s->outstanding != 0 || s->accumulated != 0)
+    return fail(s, STAGE_ERR_STATE, "stage_time_layers needs a stage with nothing outstanding and nothing accumulated");
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+  for (auto& e : ev)
+    if (hipEventCreate(&e) != hipSuccess) return fail(s, STAGE_ERR_DEVICE, "hipEventCreate failed");
+  auto done = [&](int rc) {
+    for (auto e : ev) (void)hipEventDestroy(e);
+    return rc;
+  };
+  double f = 0.0, b = 0.0;
+  const float scale = 1.0f;
+  for (int r = -1; r < reps; ++r) {   // round -1 is the warm-up
+    if (hipEventRecord(ev[0], s->st) != hipSuccess) return done(fail(s, STAGE_ERR_DEVICE, "hipEventRecord failed"));
+    int rc = stage_forward(s, 0, x_or_ids, y_out, targets, loss_out);
+    if (rc != STAGE_OK) return done(rc);
+    (void)hipEventRecord(ev[1], s->st);
+    rc = stage_backward(s, 0, dy, dx_out, scale);
+    if (rc == STAGE_OK) rc = stage_accumulate(s, 0);
+    if (rc != STAGE_OK) return done(rc);
+    (void)hipEventRecord(ev[2], s->st);
+    if (hipEventSynchronize(ev[2]) != hipSuccess) return done(fail(s, STAGE_ERR_DEVICE, "hipEventSynchronize failed"));
+    float m0 = 0.f, m1 = 0.f;
+    if (hipEventElapsedTime(&m0, ev[0], ev[1]) != hipSuccess || hipEventElapsedTime(&m1, ev[1], ev[2]) != hipSuccess)
+      return done(fail(s, STAGE_ERR_DEVICE, "hipEventElapsedTime failed"));
+    if (r >= 0) { f += m0; b += m1; }
+  }
+  // give the stage back as it was found: no accumulated microbatch, gradients zero
+  if (!flush_deferred(s)) return done(STAGE_ERR_DEVICE);
+  s->accumulated = 0;
+  if (fill_zero(s->st, s->grad, count_params(s->cfg)) != hipSuccess || hipStreamSynchronize(s->st) != hipSuccess)
+    return done(fail(s, STAGE_ERR_DEVICE, "clearing grad_acc failed"));
+  *fwd_ms = f / reps;
+  *bwd_ms = b / reps;
+  return done(STAGE_OK);
+}
+
+int stage_fit_linear(const double* x, const double* y, int32_t n, stage_linear_fit* out) {
+  if (!x || !y || !out || n < 2) return fail(nullptr, STAGE_ERR_ARG, "stage_fit_linear needs n >= 2 points");
+  double xb = 0.0, yb = 0.0;
+  for (int i = 0; i < n; ++i) { xb += x[i]; yb += y[i]; }
+  xb /= n; yb /= n;
+  double sxx = 0.0, sxy = 0.0, syy = 0.0;
+  for (int i = 0; i < n; ++i) { sxx += (x[i] - xb) * (x[i] - xb); sxy += (x[i] - xb) * (y[i] - yb); syy += (y[i] - yb) * (y[i] - yb); }
+  if (!(sxx > 0.0)) return fail(nullptr, STAGE_ERR_ARG, "stage_fit_linear needs at least two distinct x");
+  out->slope = sxy / sxx;
+  out->intercept = yb - out->slope * xb;
+  double res = 0.0;
+  for (int i = 0; i < n; ++i) { const double d = y[i] - (out->intercept + out->slope * x[i]); res += d * d; }
+  out->r2 = syy > 0.0 ? 1.0 - res / syy : 1.0;
+  return STAGE_OK;
 }
 
 const char* stage_last_error(const stage_t* s) { return s ? s->err.c_str() : g_err.c_str(); }

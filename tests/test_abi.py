@@ -105,6 +105,23 @@ def test_ministages_memory_report():
     assert ei.value.code == zs.STAGE_ERR_ARG
 
 
+def test_library_line_fit_matches_oracle():
+    """stage_fit_linear is host-only arithmetic, so its parity with the oracle runs without a GPU."""
+    import numpy as np
+    rng = np.random.default_rng(11)
+    for n in (2, 3, 5, 40):
+        x = np.sort(rng.uniform(1.0, 64.0, n))
+        y = 0.3 + 1.7 * x + rng.standard_normal(n) * 0.5
+        a, b, r2 = zs.fit_linear(list(x), list(y))
+        oa, ob, or2 = so.linear_fit(x, y)
+        assert abs(a - oa) <= 1e-9 * max(1.0, abs(oa)) and abs(b - ob) <= 1e-9 * abs(ob) and abs(r2 - or2) <= 1e-9
+    assert zs.fit_linear([1.0, 2.0], [5.0, 5.0]) == (5.0, 0.0, 1.0)
+    for bad in (([1.0], [2.0]), ([3.0, 3.0, 3.0], [1.0, 2.0, 3.0])):
+        with pytest.raises(zs.StageError) as ei:
+            zs.fit_linear(*bad)
+        assert ei.value.code == zs.STAGE_ERR_ARG
+
+
 def test_bad_configs_are_rejected_on_the_host():
     cfg = get_config("C1")
     for kw in (dict(heads=3), dict(hidden=250, heads=5), dict(layers=0), dict(arch=2), dict(dtype=3),

@@ -136,6 +136,61 @@ def test_gemm_full_shape_sampled_outputs(gpu_device):
     assert ey <= 1e-2 and eda <= 1e-2 and edw <= 1e-4
 
 
+def test_gemm_with_operands_beyond_the_kernels_offset_range(gpu_device):
+    """Token-sized operands of more than 2^30 bytes (26 624 tokens x 22 016 columns of bf16): the dispatcher cuts
+    the product into launches of the MFMA kernel over row ranges (forward and input-gradient products, also
+    with the fused rotation) or over ranges of K (weight gradient).  256 sampled outputs each against float64
+    dot products, and the samples include rows and K ranges on both sides of every cut."""
+    rng = np.random.default_rng(17)
+    T, F2, N, S, d = 26624, 22016, 512, 2048, 128
+    g = torch.Generator(device="cuda").manual_seed(9)
+    big = torch.randn(T, F2, device="cuda", generator=g).to(torch.bfloat16)
+    assert big.numel() * 2 > 2 ** 30
+    W = (torch.randn(N, F2, device="cuda", generator=g) * 0.02).to(torch.bfloat16)       # [N, K]: two K segments of F2/2
+    Wn = (torch.randn(F2, N, device="cuda", generator=g) * 0.02).to(torch.bfloat16)      # [K, N]
+    x = torch.randn(T, N, device="cuda", generator=g).to(torch.bfloat16)
+    res = torch.randn(T, N, device="cuda", generator=g).to(torch.bfloat16)
+    big64 = None
+    ii = np.concatenate([rng.integers(0, T, 250), [0, T - 1, 24319, 24320, 22527, 22528]])
+    jj = rng.integers(0, N, ii.size)
+
+    print("[case] gemm big operand NT segmented", flush=True)
+    c = torch.empty(T, N, dtype=torch.bfloat16, device="cuda")
+    zs.ops.gemm(st(), 1, 0, 1, T, N, F2, big, F2, W, F2, c, N, 0, None, res, N, 1, 0, 0, 0, 0, F2 // 2, F2 // 2, 0)
+    torch.cuda.synchronize()
+    A = big[torch.from_numpy(ii).cuda()].float().cpu().numpy().astype(np.float64)
+    want = np.einsum("sk,sk->s", A, W.float().cpu().numpy().astype(np.float64)[jj]) + res.float().cpu().numpy()[ii, jj]
+    got = c.float().cpu().numpy()[ii, jj]
+    assert np.abs(got - want).max() / np.abs(want).max() <= 1e-2
+
+    print("[case] gemm big operand NN with fused rotation", flush=True)
+    table = torch.empty(S * d, dtype=torch.float32, device="cuda")
+    zs.ops.rope_table(st(), S, d, 10000.0, table)
+    c2 = torch.empty(T, N, dtype=torch.bfloat16, device="cuda")
+    zs.ops.gemm_rope(st(), 1, 0, 0, T, N, F2, big, F2, Wn, N, c2, N, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0, table, S, d, 1)
+    torch.cuda.synchronize()
+    Wn64 = Wn.float().cpu().numpy().astype(np.float64)
+    pair = jj // 2 * 2
+    u0 = np.einsum("sk,ks->s", A, Wn64[:, pair])
+    u1 = np.einsum("sk,ks->s", A, Wn64[:, pair + 1])
+    ang = (ii % S) * 10000.0 ** (-2.0 * ((pair % d) // 2) / d)
+    want = np.where(jj % 2 == 0, u0 * np.cos(ang) - u1 * np.sin(ang), u0 * np.sin(ang) + u1 * np.cos(ang))
+    got = c2.float().cpu().numpy()[ii, jj]
+    assert np.abs(got - want).max() / np.abs(want).max() <= 1e-2
+
+    print("[case] gemm big operand TN", flush=True)
+    dW = torch.zeros(2 * N * (F2 // 2), dtype=torch.float32, device="cuda")
+    zs.ops.gemm(st(), 1, 1, 0, N, F2 // 2, T, x, N, big, F2, dW, F2 // 2, 1, None, None, 0, 2, 0, F2 // 2, N * (F2 // 2), 0, 0, 0, 0)
+    torch.cuda.synchronize()
+    rows, cols = rng.integers(0, N, 64), rng.integers(0, F2, 64)
+    x64 = x.float().cpu().numpy().astype(np.float64)
+    B = big[:, torch.from_numpy(cols).cuda()].float().cpu().numpy().astype(np.float64)
+    want = np.einsum("ks,ks->s", x64[:, rows], B)
+    dWh = dW.cpu().numpy().reshape(2, N, F2 // 2)
+    got = dWh[cols // (F2 // 2), rows, cols % (F2 // 2)]
+    assert np.abs(got - want).max() / np.abs(want).max() <= 1e-4
+
+
 # ----------------------------------------------------------------------------- norms
 
 

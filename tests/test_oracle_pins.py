@@ -440,3 +440,25 @@ def test_oracle_has_not_drifted_from_stored_summary():
             elif isinstance(v, dict):
                 for kk, vv in v.items():
                     assert abs(now[k][kk] - vv) <= 1e-9 * max(abs(vv), 1e-12), (rec["config"], k, kk)
+
+
+# ---------------------------------------------------------------- runtime model
+
+
+def test_linear_fit_recovers_lines_and_matches_library_least_squares():
+    """Pins of the oracle's least-squares line: exact recovery of a line, numpy's polynomial fit and its
+    correlation coefficient on noisy data, invariance of r2 under shifts and scalings, the two-point case."""
+    rng = np.random.default_rng(5)
+    x = np.array([1.0, 2.0, 3.0, 4.0, 6.0, 8.0])
+    a, b, r2 = so.linear_fit(x, 0.75 + 2.5 * x)
+    assert abs(a - 0.75) < 1e-12 and abs(b - 2.5) < 1e-12 and abs(r2 - 1.0) < 1e-12
+    y = 3.0 - 0.4 * x + rng.standard_normal(x.size) * 0.3
+    a, b, r2 = so.linear_fit(x, y)
+    pb, pa = np.polyfit(x, y, 1)
+    assert abs(a - pa) < 1e-10 and abs(b - pb) < 1e-10
+    assert abs(r2 - np.corrcoef(x, y)[0, 1] ** 2) < 1e-10
+    a2, b2, r22 = so.linear_fit(10.0 * x - 3.0, 2.0 * y + 7.0)
+    assert abs(r22 - r2) < 1e-10 and abs(b2 - 2.0 * b / 10.0) < 1e-10
+    a, b, r2 = so.linear_fit([2.0, 5.0], [1.0, 7.0])              # two points: the line through them
+    assert abs(b - 2.0) < 1e-12 and abs(a + 3.0) < 1e-12 and abs(r2 - 1.0) < 1e-12
+    assert so.linear_fit([1.0, 2.0, 3.0], [4.0, 4.0, 4.0]) == (4.0, 0.0, 1.0)
