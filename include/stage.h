@@ -36,6 +36,12 @@
  *  - Activations are row-major [T, H] with T = microbatch*seq tokens, token
  *    t = b*seq + s.  dtype 0: float everywhere.  dtype 1: bf16 activations and
  *    working parameters, fp32 master weights, gradients and Adam moments.
+ *    dtype 2: the same with IEEE half (fp16) in place of bf16, the mixed precision the
+ *    paper trains in (Section 6.1); meant to be used with loss scaling, which stays
+ *    with the caller: interior stages receive dy already scaled, the head stage's
+ *    loss_scale carries the scale, grad_scale of the optimizer step takes it out
+ *    again, stage_set_overflow_flag finds the steps to skip and
+ *    stage_loss_scale_update is the usual rule for adapting the scale.
  */
 #ifndef STAGE_H
 #define STAGE_H
@@ -58,7 +64,7 @@ enum {
 };
 
 enum { STAGE_ARCH_GPT = 0, STAGE_ARCH_LLAMA = 1 };
-enum { STAGE_DTYPE_F32 = 0, STAGE_DTYPE_BF16 = 1 };
+enum { STAGE_DTYPE_F32 = 0, STAGE_DTYPE_BF16 = 1, STAGE_DTYPE_F16 = 2 };
 
 typedef struct {
   int32_t arch;              /* STAGE_ARCH_* */
@@ -176,6 +182,18 @@ int stage_graph_replayed(stage_t* stage, int32_t n_microbatches);
  * data-parallel peers).  Then grad_acc is set to zero everywhere.  Legal only when at least
  * one microbatch was accumulated and none is outstanding; otherwise STAGE_ERR_STATE. */
 int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale);
+
+/* Loss-scaled training (dtype 2).  Once a device flag is set (NULL = off again), every stage_optimizer_step
+ * first tests the shard's accumulated gradients and ORs 1 into *device_flag (int32, caller-owned, cleared by the
+ * caller) if any of them is inf or nan; the update kernel reads the flag and, when it is non-zero, leaves
+ * parameters, master copy and moments untouched (the gradients are still dropped).  The caller reads the flag
+ * after the step, and may OR flags of several stages or ranks into one before the step.
+ * stage_loss_scale_update is host-only: the usual dynamic rule - a step that overflowed multiplies the scale by
+ * backoff (0 < backoff < 1) and restarts the count; growth_interval steps in a row without overflow multiply it
+ * by growth (> 1). */
+int stage_set_overflow_flag(stage_t* s, int32_t* device_flag);
+int stage_loss_scale_update(float* scale, int32_t* good_steps, int32_t found_inf, float backoff, float growth,
+                            int32_t growth_interval);
 
 /* Per-kernel-class timing with HIP events on the stage's stream.  stage_profile(s, 1) starts
  * bracketing every launch with events, stage_profile(s, 0) stops.  stage_profile_read

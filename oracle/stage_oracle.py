@@ -431,3 +431,28 @@ def linear_fit(x, y):
     ss_res = ((y - (a + b * x)) ** 2).sum()
     ss_tot = ((y - yb) ** 2).sum()
     return float(a), float(b), float(1.0 - ss_res / ss_tot) if ss_tot > 0 else 1.0
+
+
+
+# --------------------------------------------------------------------------
+# dynamic loss scaling (fp16 mixed precision)
+# --------------------------------------------------------------------------
+
+
+def loss_scale_update(scale, good_steps, found_inf, backoff=0.5, growth=2.0, growth_interval=2000):
+    """The usual dynamic loss-scaling rule for fp16 mixed precision (the precision the paper trains in,
+    Section 6.1; the paper does not spell the rule out): a step whose gradients overflowed is skipped and
+    multiplies the scale by backoff; growth_interval consecutive good steps multiply it by growth.
+    Returns the new (scale, good_steps)."""
+    if found_inf:
+        return scale * backoff, 0
+    good_steps += 1
+    if good_steps >= growth_interval:
+        return scale * growth, 0
+    return scale, good_steps
+
+
+def gradients_overflow_fp16(dy_scaled_max):
+    """Whether an upstream gradient of that magnitude is representable in IEEE half (largest finite value
+    65504): the seed itself becomes inf when it is not, and every gradient downstream of it non-finite."""
+    return not (dy_scaled_max <= 65504.0)

@@ -84,6 +84,8 @@ def lib():
         L.stage_graph_replayed.argtypes = [vp, i32]
         L.stage_profile.argtypes = [vp, i32]
         L.stage_profile_read.argtypes = [vp, C.POINTER(StageKernelStatC), i32]
+        L.stage_set_overflow_flag.argtypes = [vp, vp]
+        L.stage_loss_scale_update.argtypes = [C.POINTER(f32), C.POINTER(i32), i32, f32, f32, i32]
         L.stage_time_layers.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.stage_fit_linear.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), i32, C.POINTER(StageLinearFitC)]
         L.stage_last_error.argtypes = [vp]
@@ -153,6 +155,13 @@ def fit_linear(x, y):
     xa, ya, out = (C.c_double * n)(*x), (C.c_double * n)(*y), StageLinearFitC()
     _check(lib().stage_fit_linear(xa, ya, n, C.byref(out)))
     return out.intercept, out.slope, out.r2
+
+
+def loss_scale_update(scale, good_steps, found_inf, backoff=0.5, growth=2.0, growth_interval=2000):
+    """The library's dynamic loss-scaling rule (stage_loss_scale_update) -> (scale, good_steps)."""
+    sc, gd = C.c_float(scale), C.c_int32(good_steps)
+    _check(lib().stage_loss_scale_update(C.byref(sc), C.byref(gd), int(bool(found_inf)), backoff, growth, growth_interval))
+    return sc.value, gd.value
 
 
 def layout(cc: StageConfigC):

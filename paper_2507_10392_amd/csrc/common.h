@@ -9,24 +9,30 @@ typedef __bf16 bf16;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-enum DType { F32 = 0, BF16 = 1 };
+enum DType { F32 = 0, BF16 = 1, F16 = 2 };   // F16: IEEE half (the precision the paper trains in, Section 6.1)
 
 constexpr int WAVE = 64;
 
 __device__ __forceinline__ float to_f(float x) { return x; }
 __device__ __forceinline__ float to_f(bf16 x) { return (float)x; }
+__device__ __forceinline__ float to_f(f16 x) { return (float)x; }
 template <typename T> __device__ __forceinline__ T from_f(float x);
 template <> __device__ __forceinline__ float from_f<float>(float x) { return x; }
 template <> __device__ __forceinline__ bf16 from_f<bf16>(float x) { return (bf16)x; }  // round-to-nearest-even
+template <> __device__ __forceinline__ f16 from_f<f16>(float x) { return (f16)x; }     // round-to-nearest-even, overflow to inf
 
 // Elements moved per 16-byte access.
 template <typename T> struct Vec;
 template <> struct Vec<float> { static constexpr int N = 4; typedef f32x4 type; };
 template <> struct Vec<bf16> { static constexpr int N = 8; typedef bf16x8 type; };
+template <> struct Vec<f16> { static constexpr int N = 8; typedef f16x8 type; };
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

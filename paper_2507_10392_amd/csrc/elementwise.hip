@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void norm_fwd_reg_kernel(int Trows, const T* _
 
 // J (row = 64 x V x J elements) for which the register-resident norm kernels are instantiated, else 0.
 static int reg_chunks(DType dt, int H) {
-  const int per = 64 * (dt == F32 ? 4 : 8);
+  const int per = 64 * (dt == F32 ? 4 : 8);   // both 16-bit types move 8 elements per access
   if (H % per) return 0;
   const int J = H / per;
   return (J == 1 || J == 2 || J == 4 || J == 8 || J == 10) ? J : 0;
@@ -134,10 +134,12 @@ hipError_t norm_fwd(hipStream_t st, DType dt, int kind, int T, int H, const void
   hipLaunchKernelGGL((norm_fwd_kernel<TT, KK>), grid, blk, 0, st, T, H, (const TT*)x, (const TT*)g, (const TT*)b, eps, (TT*)n, rstd, mean)
   if (J) {
     if (dt == F32) { if (kind == 0) { LJ(float, 0) } else { LJ(float, 1) } }
-    else { if (kind == 0) { LJ(bf16, 0) } else { LJ(bf16, 1) } }
+    else if (dt == BF16) { if (kind == 0) { LJ(bf16, 0) } else { LJ(bf16, 1) } }
+    else { if (kind == 0) { LJ(f16, 0) } else { LJ(f16, 1) } }
   } else {
     if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
-    else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+    else if (dt == BF16) { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+    else { if (kind == 0) L(f16, 0); else L(f16, 1); }
   }
 #undef L
 #undef LJ
@@ -250,10 +252,12 @@ hipError_t norm_bwd(hipStream_t st, DType dt, int kind, int T, int H, const void
   hipLaunchKernelGGL((norm_bwd_kernel<TT, KK>), grid, blk, 0, st, T, H, (const TT*)dn, (const TT*)x, (const TT*)g, rstd, mean, (const TT*)dres, (TT*)dx)
   if (J) {
     if (dt == F32) { if (kind == 0) { LJ(float, 0) } else { LJ(float, 1) } }
-    else { if (kind == 0) { LJ(bf16, 0) } else { LJ(bf16, 1) } }
+    else if (dt == BF16) { if (kind == 0) { LJ(bf16, 0) } else { LJ(bf16, 1) } }
+    else { if (kind == 0) { LJ(f16, 0) } else { LJ(f16, 1) } }
   } else {
     if (dt == F32) { if (kind == 0) L(float, 0); else L(float, 1); }
-    else { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+    else if (dt == BF16) { if (kind == 0) L(bf16, 0); else L(bf16, 1); }
+    else { if (kind == 0) L(f16, 0); else L(f16, 1); }
   }
 #undef L
 #undef LJ
@@ -327,8 +331,10 @@ hipError_t colsum_partial(hipStream_t st, DType dt, int T, int N, const void* a,
   dim3 grid((unsigned)cdiv(N, 64 * V), (unsigned)nblk), blk(256);
   if (dt == F32)
     hipLaunchKernelGGL(colsum_kernel<float>, grid, blk, 0, st, T, N, (const float*)a, lda, (const float*)x, ldx, rstd, mean, part, rows_per_blk);
-  else
+  else if (dt == BF16)
     hipLaunchKernelGGL(colsum_kernel<bf16>, grid, blk, 0, st, T, N, (const bf16*)a, lda, (const bf16*)x, ldx, rstd, mean, part, rows_per_blk);
+  else
+    hipLaunchKernelGGL(colsum_kernel<f16>, grid, blk, 0, st, T, N, (const f16*)a, lda, (const f16*)x, ldx, rstd, mean, part, rows_per_blk);
   return hipGetLastError();
 }
 
@@ -409,7 +415,8 @@ hipError_t rope_apply(hipStream_t st, DType dt, int T, int S, int ncols, int d, 
   const int64_t n = (int64_t)T * (ncols / V);
   dim3 grid((unsigned)cdiv(n, 256)), blk(256);
   if (dt == F32) hipLaunchKernelGGL(rope_kernel<float>, grid, blk, 0, st, T, S, ncols, d, (float*)a, ld, table, sign);
-  else hipLaunchKernelGGL(rope_kernel<bf16>, grid, blk, 0, st, T, S, ncols, d, (bf16*)a, ld, table, sign);
+  else if (dt == BF16) hipLaunchKernelGGL(rope_kernel<bf16>, grid, blk, 0, st, T, S, ncols, d, (bf16*)a, ld, table, sign);
+  else hipLaunchKernelGGL(rope_kernel<f16>, grid, blk, 0, st, T, S, ncols, d, (f16*)a, ld, table, sign);
   return hipGetLastError();
 }
 
@@ -439,14 +446,16 @@ hipError_t gelu_fwd(hipStream_t st, DType dt, int64_t n, const void* z, void* a)
   const int V = dt == F32 ? 4 : 8;
   dim3 grid((unsigned)cdiv(n / V, 256)), blk(256);
   if (dt == F32) hipLaunchKernelGGL((gelu_kernel<float, 0>), grid, blk, 0, st, n / V, (const float*)z, (const float*)nullptr, (float*)a);
-  else hipLaunchKernelGGL((gelu_kernel<bf16, 0>), grid, blk, 0, st, n / V, (const bf16*)z, (const bf16*)nullptr, (bf16*)a);
+  else if (dt == BF16) hipLaunchKernelGGL((gelu_kernel<bf16, 0>), grid, blk, 0, st, n / V, (const bf16*)z, (const bf16*)nullptr, (bf16*)a);
+  else hipLaunchKernelGGL((gelu_kernel<f16, 0>), grid, blk, 0, st, n / V, (const f16*)z, (const f16*)nullptr, (f16*)a);
   return hipGetLastError();
 }
 hipError_t gelu_bwd(hipStream_t st, DType dt, int64_t n, const void* z, const void* da, void* dz) {
   const int V = dt == F32 ? 4 : 8;
   dim3 grid((unsigned)cdiv(n / V, 256)), blk(256);
   if (dt == F32) hipLaunchKernelGGL((gelu_kernel<float, 1>), grid, blk, 0, st, n / V, (const float*)z, (const float*)da, (float*)dz);
-  else hipLaunchKernelGGL((gelu_kernel<bf16, 1>), grid, blk, 0, st, n / V, (const bf16*)z, (const bf16*)da, (bf16*)dz);
+  else if (dt == BF16) hipLaunchKernelGGL((gelu_kernel<bf16, 1>), grid, blk, 0, st, n / V, (const bf16*)z, (const bf16*)da, (bf16*)dz);
+  else hipLaunchKernelGGL((gelu_kernel<f16, 1>), grid, blk, 0, st, n / V, (const f16*)z, (const f16*)da, (f16*)dz);
   return hipGetLastError();
 }
 
@@ -483,14 +492,16 @@ hipError_t swiglu_fwd(hipStream_t st, DType dt, int T, int F, const void* gu, vo
   const int V = dt == F32 ? 4 : 8;
   dim3 grid((unsigned)cdiv((int64_t)T * (F / V), 256)), blk(256);
   if (dt == F32) hipLaunchKernelGGL((swiglu_kernel<float, 0>), grid, blk, 0, st, T, F, (const float*)gu, (const float*)nullptr, (float*)a);
-  else hipLaunchKernelGGL((swiglu_kernel<bf16, 0>), grid, blk, 0, st, T, F, (const bf16*)gu, (const bf16*)nullptr, (bf16*)a);
+  else if (dt == BF16) hipLaunchKernelGGL((swiglu_kernel<bf16, 0>), grid, blk, 0, st, T, F, (const bf16*)gu, (const bf16*)nullptr, (bf16*)a);
+  else hipLaunchKernelGGL((swiglu_kernel<f16, 0>), grid, blk, 0, st, T, F, (const f16*)gu, (const f16*)nullptr, (f16*)a);
   return hipGetLastError();
 }
 hipError_t swiglu_bwd(hipStream_t st, DType dt, int T, int F, const void* gu, const void* da, void* dgu) {
   const int V = dt == F32 ? 4 : 8;
   dim3 grid((unsigned)cdiv((int64_t)T * (F / V), 256)), blk(256);
   if (dt == F32) hipLaunchKernelGGL((swiglu_kernel<float, 1>), grid, blk, 0, st, T, F, (const float*)gu, (const float*)da, (float*)dgu);
-  else hipLaunchKernelGGL((swiglu_kernel<bf16, 1>), grid, blk, 0, st, T, F, (const bf16*)gu, (const bf16*)da, (bf16*)dgu);
+  else if (dt == BF16) hipLaunchKernelGGL((swiglu_kernel<bf16, 1>), grid, blk, 0, st, T, F, (const bf16*)gu, (const bf16*)da, (bf16*)dgu);
+  else hipLaunchKernelGGL((swiglu_kernel<f16, 1>), grid, blk, 0, st, T, F, (const f16*)gu, (const f16*)da, (f16*)dgu);
   return hipGetLastError();
 }
 
@@ -515,7 +526,8 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(int H, int V, const int3
 }
 hipError_t embed_fwd(hipStream_t st, DType dt, int T, int H, int V, const int32_t* ids, const void* E, void* x) {
   if (dt == F32) hipLaunchKernelGGL(embed_fwd_kernel<float>, dim3(T), dim3(256), 0, st, H, V, ids, (const float*)E, (float*)x);
-  else hipLaunchKernelGGL(embed_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, H, V, ids, (const bf16*)E, (bf16*)x);
+  else if (dt == BF16) hipLaunchKernelGGL(embed_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, H, V, ids, (const bf16*)E, (bf16*)x);
+  else hipLaunchKernelGGL(embed_fwd_kernel<f16>, dim3(T), dim3(256), 0, st, H, V, ids, (const f16*)E, (f16*)x);
   return hipGetLastError();
 }
 
@@ -548,7 +560,8 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(int Trows, int H, int V,
 }
 hipError_t embed_bwd(hipStream_t st, DType dt, int T, int H, int V, const int32_t* ids, const void* dx, float* dE) {
   if (dt == F32) hipLaunchKernelGGL(embed_bwd_kernel<float>, dim3(T), dim3(256), 0, st, T, H, V, ids, (const float*)dx, dE);
-  else hipLaunchKernelGGL(embed_bwd_kernel<bf16>, dim3(T), dim3(256), 0, st, T, H, V, ids, (const bf16*)dx, dE);
+  else if (dt == BF16) hipLaunchKernelGGL(embed_bwd_kernel<bf16>, dim3(T), dim3(256), 0, st, T, H, V, ids, (const bf16*)dx, dE);
+  else hipLaunchKernelGGL(embed_bwd_kernel<f16>, dim3(T), dim3(256), 0, st, T, H, V, ids, (const f16*)dx, dE);
   return hipGetLastError();
 }
 
@@ -586,7 +599,8 @@ __global__ __launch_bounds__(256) void mean_kernel(int n, const float* __restric
 hipError_t ce_fwd(hipStream_t st, DType dt, int T, int V, const void* z, int64_t ldz, const int32_t* targets,
                   float* lse, float* rowloss, float* loss) {
   if (dt == F32) hipLaunchKernelGGL(ce_fwd_kernel<float>, dim3(T), dim3(256), 0, st, V, (const float*)z, ldz, targets, lse, rowloss);
-  else hipLaunchKernelGGL(ce_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, V, (const bf16*)z, ldz, targets, lse, rowloss);
+  else if (dt == BF16) hipLaunchKernelGGL(ce_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, V, (const bf16*)z, ldz, targets, lse, rowloss);
+  else hipLaunchKernelGGL(ce_fwd_kernel<f16>, dim3(T), dim3(256), 0, st, V, (const f16*)z, ldz, targets, lse, rowloss);
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st, T, rowloss, loss);
   return hipGetLastError();
 }
@@ -604,7 +618,8 @@ hipError_t ce_bwd(hipStream_t st, DType dt, int T, int V, void* z, int64_t ldz, 
                   const float* lse, float scale) {
   dim3 grid((unsigned)cdiv(V, 256), (unsigned)T), blk(256);
   if (dt == F32) hipLaunchKernelGGL(ce_bwd_kernel<float>, grid, blk, 0, st, V, (float*)z, ldz, targets, lse, scale);
-  else hipLaunchKernelGGL(ce_bwd_kernel<bf16>, grid, blk, 0, st, V, (bf16*)z, ldz, targets, lse, scale);
+  else if (dt == BF16) hipLaunchKernelGGL(ce_bwd_kernel<bf16>, grid, blk, 0, st, V, (bf16*)z, ldz, targets, lse, scale);
+  else hipLaunchKernelGGL(ce_bwd_kernel<f16>, grid, blk, 0, st, V, (f16*)z, ldz, targets, lse, scale);
   return hipGetLastError();
 }
 
@@ -618,15 +633,25 @@ __device__ __forceinline__ float adamw_one(float p, float g, float& m, float& v,
   return p - h.lr * (mhat / (sqrtf(vhat) + h.eps) + h.wd * p);
 }
 
-// One float4 of p, g, m, v per lane; reads 16 B/element, writes 12 B (+2 B bf16 copy, +4 B zeroed grad).
+// One float4 of p, g, m, v per lane; reads 16 B/element, writes 12 B (+2 B 16-bit copy, +4 B zeroed grad).
 // VEC=false is the scalar variant for ranges that are not 16-byte aligned and for the tail.
-template <bool BF, bool VEC>
+// W is the element type of the working copy (float: params itself is the master).  With h.skip set and *h.skip
+// non-zero (a non-finite gradient was found, loss-scaled fp16 training) nothing but the zeroing of grad happens.
+template <typename W, bool VEC>
 __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, void* params, float* master,
                                                     float* grad, float* m, float* v, AdamW h) {
+  constexpr bool LOW = sizeof(W) == 2;
+  typedef W W4 __attribute__((ext_vector_type(4)));
   const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * (VEC ? 4 : 1);
   if (i >= n) return;
-  float* pm = BF ? master + i : (float*)params + begin + i;
+  const bool skip = h.skip != nullptr && *h.skip != 0;
+  float* pm = LOW ? master + i : (float*)params + begin + i;
   if (VEC) {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    if (skip) {
+      __builtin_nontemporal_store(zero, (f32x4*)(grad + begin + i));
+      return;
+    }
     // every byte is touched once per step: non-temporal accesses keep the streams out of the caches
     f32x4 p4 = __builtin_nontemporal_load((f32x4*)pm), g4 = __builtin_nontemporal_load((f32x4*)(grad + begin + i)),
           m4 = __builtin_nontemporal_load((f32x4*)(m + i)), v4 = __builtin_nontemporal_load((f32x4*)(v + i));
@@ -640,22 +665,36 @@ __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, vo
     __builtin_nontemporal_store(p4, (f32x4*)pm);
     __builtin_nontemporal_store(m4, (f32x4*)(m + i));
     __builtin_nontemporal_store(v4, (f32x4*)(v + i));
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     __builtin_nontemporal_store(zero, (f32x4*)(grad + begin + i));
-    if (BF) {
-      bf16x4 b;
+    if (LOW) {
+      // The working copy is the rounding of the STORED fp32 value.  Without the barrier the compiler folds the
+      // update's last fused multiply-add and the conversion into one mixed-precision instruction that rounds the
+      // exact result once, which differs from half(master) whenever the fp32 value lands on a tie.
+      W4 b;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) b[k] = (bf16)p4[k];
-      __builtin_nontemporal_store(b, (bf16x4*)((bf16*)params + begin + i));
+      for (int k = 0; k < 4; ++k) {
+        float q = p4[k];
+        asm volatile("" : "+v"(q));
+        b[k] = (W)q;
+      }
+      __builtin_nontemporal_store(b, (W4*)((W*)params + begin + i));
     }
   } else {
+    if (skip) {
+      grad[begin + i] = 0.f;
+      return;
+    }
     float mm = m[i], vv = v[i];
     const float pn = adamw_one(*pm, grad[begin + i], mm, vv, h);
     *pm = pn;
     m[i] = mm;
     v[i] = vv;
     grad[begin + i] = 0.f;
-    if (BF) ((bf16*)params)[begin + i] = (bf16)pn;
+    if (LOW) {
+      float q = pn;
+      asm volatile("" : "+v"(q));   // as above: round the stored value
+      ((W*)params)[begin + i] = (W)q;
+    }
   }
 }
 
@@ -666,17 +705,37 @@ hipError_t adamw(hipStream_t st, DType dt, int64_t n, int64_t begin, void* param
   const int64_t nv = aligned ? (n / 4) * 4 : 0;
   if (nv > 0) {
     dim3 grid((unsigned)cdiv(nv / 4, 256)), blk(256);
-    if (dt == BF16) hipLaunchKernelGGL((adamw_kernel<true, true>), grid, blk, 0, st, nv, begin, params, master, grad, m, v, h);
-    else hipLaunchKernelGGL((adamw_kernel<false, true>), grid, blk, 0, st, nv, begin, params, master, grad, m, v, h);
+    if (dt == BF16) hipLaunchKernelGGL((adamw_kernel<bf16, true>), grid, blk, 0, st, nv, begin, params, master, grad, m, v, h);
+    else if (dt == F16) hipLaunchKernelGGL((adamw_kernel<f16, true>), grid, blk, 0, st, nv, begin, params, master, grad, m, v, h);
+    else hipLaunchKernelGGL((adamw_kernel<float, true>), grid, blk, 0, st, nv, begin, params, master, grad, m, v, h);
   }
   if (n > nv) {
     const int64_t r = n - nv;
     dim3 grid((unsigned)cdiv(r, 256)), blk(256);
     if (dt == BF16)
-      hipLaunchKernelGGL((adamw_kernel<true, false>), grid, blk, 0, st, r, begin + nv, params, master + nv, grad, m + nv, v + nv, h);
+      hipLaunchKernelGGL((adamw_kernel<bf16, false>), grid, blk, 0, st, r, begin + nv, params, master + nv, grad, m + nv, v + nv, h);
+    else if (dt == F16)
+      hipLaunchKernelGGL((adamw_kernel<f16, false>), grid, blk, 0, st, r, begin + nv, params, master + nv, grad, m + nv, v + nv, h);
     else
-      hipLaunchKernelGGL((adamw_kernel<false, false>), grid, blk, 0, st, r, begin + nv, params, (float*)nullptr, grad, m + nv, v + nv, h);
+      hipLaunchKernelGGL((adamw_kernel<float, false>), grid, blk, 0, st, r, begin + nv, params, (float*)nullptr, grad, m + nv, v + nv, h);
   }
+  return hipGetLastError();
+}
+
+// Sets *flag to 1 when any of g[0..n) is not finite (never clears it): the overflow test of loss-scaled training.
+__global__ __launch_bounds__(256) void nonfinite_kernel(const float* __restrict__ g, int64_t n, int* __restrict__ flag) {
+  bool bad = false;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const float x = g[i];
+    bad |= !(fabsf(x) <= 3.402823466e38f);   // false for inf and for nan
+  }
+  if (__any(bad) && (threadIdx.x & 63) == 0) atomicOr(flag, 1);
+}
+hipError_t nonfinite_check(hipStream_t st, const float* g, int64_t n, int* flag) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = cdiv(n, 256 * 8);
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(nonfinite_kernel, dim3((unsigned)blocks), dim3(256), 0, st, g, n, flag);
   return hipGetLastError();
 }
 

@@ -101,7 +101,7 @@ template <typename T> static hipError_t launch_simple(hipStream_t st, const Gemm
 
 hipError_t gemm_simple(hipStream_t st, DType dt, const Gemm& g) {
   if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
-  return dt == F32 ? launch_simple<float>(st, g) : launch_simple<bf16>(st, g);
+  return dt == F32 ? launch_simple<float>(st, g) : dt == BF16 ? launch_simple<bf16>(st, g) : launch_simple<f16>(st, g);
 }
 
 int gemm_select(DType dt, const Gemm& g, int force) {

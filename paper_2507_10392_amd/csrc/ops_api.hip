@@ -9,7 +9,7 @@ using namespace zs;
 
 namespace {
 int rc(hipError_t e) { return e == hipSuccess ? STAGE_OK : STAGE_ERR_DEVICE; }
-bool dt_ok(int d) { return d == 0 || d == 1; }
+bool dt_ok(int d) { return d == 0 || d == 1 || d == 2; }
 int vec_of(int d) { return d == 0 ? 4 : 8; }
 }  // namespace
 
@@ -164,7 +164,7 @@ int stage_op_adamw(void* stream, int32_t dtype, int64_t n, int64_t begin, void* 
   if (!dt_ok(dtype) || n < 0 || begin < 0 || t < 1) return STAGE_ERR_ARG;
   if (n == 0) return STAGE_OK;
   if (!params || !grad || !m || !v) return STAGE_ERR_ARG;
-  if ((dtype == 1) != (master != nullptr)) return STAGE_ERR_ARG;
+  if ((dtype != 0) != (master != nullptr)) return STAGE_ERR_ARG;
   AdamW h;
   h.lr = lr; h.beta1 = beta1; h.beta2 = beta2; h.eps = eps; h.wd = wd;
   h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)beta1, (double)t)));

@@ -21,8 +21,8 @@ thread_local std::string g_err;  // errors raised before a stage exists
 struct Seg { std::string name; int64_t off, rows, cols; };
 
 struct Shape {
-  int arch, L, H, nh, d, F, S, mb, T, M, V;
-  bool bf, embed, head, recompute, pair, offload;
+  int arch, L, H, nh, d, F, S, mb, T, M, V, dtype;
+  bool bf /* 16-bit elements (bf16 or fp16) with an fp32 master copy */, embed, head, recompute, pair, offload;
   int64_t E;  // bytes per element
 };
 
@@ -30,7 +30,7 @@ Shape shape_of(const stage_config& c) {
   Shape s;
   s.arch = c.arch; s.L = c.layers; s.H = c.hidden; s.nh = c.heads; s.d = c.heads ? c.hidden / c.heads : 0;
   s.F = c.ffn; s.S = c.seq; s.mb = c.microbatch; s.T = c.seq * c.microbatch; s.M = c.max_microbatches;
-  s.V = c.vocab; s.bf = c.dtype == STAGE_DTYPE_BF16; s.embed = c.has_embed != 0; s.head = c.has_head != 0;
+  s.V = c.vocab; s.dtype = c.dtype; s.bf = c.dtype != STAGE_DTYPE_F32; s.embed = c.has_embed != 0; s.head = c.has_head != 0;
   s.recompute = c.recompute != 0; s.E = s.bf ? 2 : 4;
   s.offload = c.offload_acts != 0;
   // weight gradients of two microbatches in one product: needs the first one's activations to stay (no
@@ -73,7 +73,8 @@ int validate(const stage_config* c, std::string& err) {
   if (!c) { err = "config is NULL"; return STAGE_ERR_ARG; }
   auto bad = [&](const char* m) { err = m; return STAGE_ERR_ARG; };
   if (c->arch != STAGE_ARCH_GPT && c->arch != STAGE_ARCH_LLAMA) return bad("arch must be 0 (GPT) or 1 (Llama)");
-  if (c->dtype != STAGE_DTYPE_F32 && c->dtype != STAGE_DTYPE_BF16) return bad("dtype must be 0 (fp32) or 1 (bf16)");
+  if (c->dtype != STAGE_DTYPE_F32 && c->dtype != STAGE_DTYPE_BF16 && c->dtype != STAGE_DTYPE_F16)
+    return bad("dtype must be 0 (fp32), 1 (bf16) or 2 (fp16)");
   if (c->layers < 1 || c->hidden < 8 || c->heads < 1 || c->ffn < 8 || c->seq < 1 || c->microbatch < 1)
     return bad("layers, heads, seq, microbatch must be >= 1 and hidden, ffn >= 8");
   if (c->max_microbatches < 1) return bad("max_microbatches must be >= 1");
@@ -260,6 +261,7 @@ struct stage {
   int pending = -1;          // slot whose backward waits for stage_accumulate
   int outstanding = 0, accumulated = 0;
   int deferred = -1;         // pair_wgrad: slot whose weight-gradient products wait for the next backward
+  int* overflow = nullptr;   // device flag of loss-scaled training (stage_set_overflow_flag), or NULL
   std::vector<ReduceJob> jobs_host;
   int njobs = 0, max_job_width = 0;
   std::string err;
@@ -386,7 +388,7 @@ bool offload_load(stage_t* s, int k, int mb) {
   return hip_ok(s, hipEventRecord(d.copy_done, s->copy_st), "offload: event record");
 }
 
-DType dt_of(const stage_t* s) { return s->sh.bf ? BF16 : F32; }
+DType dt_of(const stage_t* s) { return s->sh.dtype == STAGE_DTYPE_F16 ? F16 : s->sh.bf ? BF16 : F32; }
 
 bool do_gemm(stage_t* s, const Gemm& g) {
   const int impl = gemm_select(dt_of(s), g, GEMM_AUTO);
@@ -685,7 +687,7 @@ int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* m
   const int64_t sh = cfg->shard_end - cfg->shard_begin;
   if (!params || !grad_acc) return fail(nullptr, STAGE_ERR_ARG, "params and grad_acc must not be NULL");
   if (sh > 0 && (!adam_m || !adam_v)) return fail(nullptr, STAGE_ERR_ARG, "adam_m and adam_v must not be NULL");
-  if (cfg->dtype == STAGE_DTYPE_BF16 && sh > 0 && !master) return fail(nullptr, STAGE_ERR_ARG, "master must not be NULL for dtype 1");
+  if (cfg->dtype != STAGE_DTYPE_F32 && sh > 0 && !master) return fail(nullptr, STAGE_ERR_ARG, "master must not be NULL for dtypes 1 and 2");
   if (cfg->dtype == STAGE_DTYPE_F32 && master) return fail(nullptr, STAGE_ERR_ARG, "master must be NULL for dtype 0");
   if (((uintptr_t)params | (uintptr_t)grad_acc | (uintptr_t)master | (uintptr_t)adam_m | (uintptr_t)adam_v) & 15)
     return fail(nullptr, STAGE_ERR_ARG, "params, master, grad_acc, adam_m, adam_v must be 16-byte aligned");
@@ -917,7 +919,12 @@ int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale) {
   h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)c.beta1, (double)t)));
   h.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)c.beta2, (double)t)));
   h.grad_scale = grad_scale;
+  h.skip = s->overflow;
   const int64_t P = count_params(c), b = c.shard_begin, e = c.shard_end, n = e - b;
+  // loss-scaled training: a non-finite gradient anywhere in the shard raises the flag, and the update that reads
+  // the flag then leaves parameters and moments alone
+  if (s->overflow && n > 0 && !run(s, "overflow_check", 0, 4.0 * n, [&] { return nonfinite_check(s->st, s->grad + b, n, s->overflow); }))
+    return STAGE_ERR_DEVICE;
   const double per = s->sh.bf ? 30.0 : 28.0;
   if (!run(s, "adamw", 0, per * n, [&] {
         return adamw(s->st, dt_of(s), n, b, s->params, s->master, s->grad, s->m, s->v, h); }))
@@ -928,6 +935,27 @@ int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale) {
         return er != hipSuccess ? er : fill_zero(s->st, s->grad + e, P - e); }))
     return STAGE_ERR_DEVICE;
   s->accumulated = 0;
+  return STAGE_OK;
+}
+
+int stage_set_overflow_flag(stage_t* s, int32_t* device_flag) {
+  if (!s) return STAGE_ERR_ARG;
+  if ((uintptr_t)device_flag & 3) return fail(s, STAGE_ERR_ARG, "device_flag must be 4-byte aligned");
+  s->overflow = (int*)device_flag;
+  return STAGE_OK;
+}
+
+int stage_loss_scale_update(float* scale, int32_t* good_steps, int32_t found_inf, float backoff, float growth, int32_t growth_interval) {
+  if (!scale || !good_steps || !(*scale > 0.f) || !(backoff > 0.f && backoff < 1.f) || !(growth > 1.f) || growth_interval < 1 ||
+      *good_steps < 0)
+    return fail(nullptr, STAGE_ERR_ARG, "stage_loss_scale_update: scale > 0, 0 < backoff < 1, growth > 1, growth_interval >= 1 required");
+  if (found_inf) {
+    *scale *= backoff;
+    *good_steps = 0;
+  } else if (++*good_steps >= growth_interval) {
+    *scale *= growth;
+    *good_steps = 0;
+  }
   return STAGE_OK;
 }
 

@@ -12,9 +12,9 @@ import torch
 
 import paper_2507_10392_amd as zs
 from oracle import stage_oracle as so
-from workloads.configs import DTYPE_BF16
+from workloads.configs import DTYPE_BF16, DTYPE_F16
 
-TOL = {0: 1e-4, 1: 2e-2}
+TOL = {0: 1e-4, 1: 2e-2, 2: 3e-3}   # fp16 rounds 8 times finer than bf16
 
 
 def rel_err(a, o):
@@ -48,7 +48,7 @@ def hp32(cfg):
 
 
 def tdtype(cfg):
-    return torch.bfloat16 if cfg.dtype == DTYPE_BF16 else torch.float32
+    return torch.bfloat16 if cfg.dtype == DTYPE_BF16 else torch.float16 if cfg.dtype == DTYPE_F16 else torch.float32
 
 
 def dev(a, dtype=None):
@@ -66,7 +66,7 @@ class GpuStage:
         b, e = self.cc.shard_begin, self.cc.shard_end
         self.shard = (b, e)
         self.params = dev(inp.params, tdtype(cfg))
-        self.master = dev(inp.master[b:e]) if cfg.dtype == DTYPE_BF16 else None
+        self.master = dev(inp.master[b:e]) if cfg.dtype != 0 else None
         self.grad = torch.zeros(P, dtype=torch.float32, device="cuda")
         self.m = torch.zeros(max(e - b, 1), dtype=torch.float32, device="cuda")
         self.v = torch.zeros(max(e - b, 1), dtype=torch.float32, device="cuda")
@@ -218,8 +218,8 @@ def compare_optimizer(cfg, inp, shard, gpu_grad, res, ora_grad, tol, t=1):
     par = res["params"].astype(np.float64)
     assert np.array_equal(par[:b], inp.params[:b].astype(np.float64)) and np.array_equal(par[e:], inp.params[e:].astype(np.float64))
     assert not res["grad_after"].any()
-    if cfg.dtype == DTYPE_BF16:
-        want = torch.from_numpy(res["master"]).to(torch.bfloat16)      # round-to-nearest-even, bit exact
+    if cfg.dtype != 0:
+        want = torch.from_numpy(res["master"]).to(tdtype(cfg))          # round-to-nearest-even, bit exact
         got = res["params_raw"][b:e].cpu()
         assert torch.equal(want.view(torch.int16), got.view(torch.int16))
     return frac_masked

@@ -122,6 +122,20 @@ def test_library_line_fit_matches_oracle():
         assert ei.value.code == zs.STAGE_ERR_ARG
 
 
+def test_loss_scale_rule_matches_oracle():
+    """stage_loss_scale_update is host-only: compared with the oracle over a scripted sequence of good and
+    overflowing steps (halving, doubling after an unbroken run, the count restarting after an overflow)."""
+    scale, good, o = 65536.0, 0, (65536.0, 0)
+    for found in (0, 0, 1, 0, 0, 0, 0, 1, 1, 0, 0, 0, 0, 0, 0):
+        scale, good = zs.loss_scale_update(scale, good, found, 0.5, 2.0, 3)
+        o = so.loss_scale_update(o[0], o[1], found, 0.5, 2.0, 3)
+        assert (scale, good) == o
+    assert o == (65536.0, 0)          # /2, x2, /2, /2, x2, x2 with the counts in between
+    for bad in ((0.0, 0, 0, 0.5, 2.0, 3), (1.0, 0, 0, 1.5, 2.0, 3), (1.0, 0, 0, 0.5, 1.0, 3), (1.0, 0, 0, 0.5, 2.0, 0)):
+        with pytest.raises(zs.StageError):
+            zs.loss_scale_update(*bad)
+
+
 def test_bad_configs_are_rejected_on_the_host():
     cfg = get_config("C1")
     for kw in (dict(heads=3), dict(hidden=250, heads=5), dict(layers=0), dict(arch=2), dict(dtype=3),

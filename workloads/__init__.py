@@ -6,4 +6,4 @@ oracle's tests and the HIP path's tests can be fed from it without the two
 sharing any computation.
 """
 from .configs import StageConfig, CONFIGS, get_config  # noqa: F401
-from .inputs import StageInputs, make_inputs, round_bf16  # noqa: F401
+from .inputs import StageInputs, make_inputs, round_bf16, round_f16  # noqa: F401

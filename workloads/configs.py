@@ -16,6 +16,7 @@ ARCH_GPT = 0    # pre-LayerNorm, GELU FFN, biases, no RoPE
 ARCH_LLAMA = 1  # pre-RMSNorm, SwiGLU FFN, RoPE, no biases
 DTYPE_F32 = 0   # fp32 everywhere
 DTYPE_BF16 = 1  # bf16 params/activations, fp32 master weights, grads, moments
+DTYPE_F16 = 2   # the same with IEEE half; used with loss scaling (the mixed precision the paper trains in)
 
 
 @dataclass(frozen=True)
@@ -110,6 +111,13 @@ def _mk() -> dict[str, StageConfig]:
                             shard_num=1, shard_den=3, seed=20250723)
     c["C5t"] = StageConfig("C5t", ARCH_LLAMA, DTYPE_BF16, 2, 512, 4, 1376, 256, 1, 8,
                            vocab=2000, has_embed=1, has_head=1, seed=20250724)
+    # fp16 twins (the paper's mixed precision): same shapes as C3t / C2t / C5t, fewer microbatches
+    c["C3h"] = StageConfig("C3h", ARCH_LLAMA, DTYPE_F16, 2, 512, 4, 1376, 256, 1, 4,
+                           shard_num=1, shard_den=2, seed=20250742)
+    c["C2h"] = StageConfig("C2h", ARCH_GPT, DTYPE_F16, 2, 512, 4, 2048, 256, 1, 3,
+                           shard_num=1, shard_den=4, seed=20250741)
+    c["C5h"] = StageConfig("C5h", ARCH_LLAMA, DTYPE_F16, 2, 512, 4, 1376, 256, 1, 3,
+                           vocab=2000, has_embed=1, has_head=1, seed=20250744)
     # fp32 Llama-style and GPT-with-head minis used to exercise every code path in fp32.
     c["L1"] = StageConfig("L1", ARCH_LLAMA, DTYPE_F32, 2, 256, 4, 688, 128, 2, 4,
                           vocab=1000, has_embed=1, has_head=1, seed=20250731)
