@@ -244,6 +244,9 @@ def main():
     ap.add_argument("--recompute", action="store_true", help="run the workload with per-layer recompute (stage_config.recompute = 1)")
     ap.add_argument("--offload", action="store_true",
                     help="keep the boundary activations in pinned host memory (stage_config.offload_acts = 1; implies --recompute)")
+    ap.add_argument("--fp16", action="store_true",
+                    help="run the workload in fp16 mixed precision (stage_config.dtype = 2) with a loss scale of 1024 on the "
+                         "upstream gradient, taken out again by the optimizer step, and the overflow test switched on")
     ap.add_argument("--ministages", type=int, default=0, metavar="K",
                     help="cut the workload's layers into K ministages that share two parameter slots on the GPU, the rest "
                          "waiting in pinned host memory (include/ministages.h); interior stages only")
@@ -267,6 +270,12 @@ def main():
     cfg = get_config(args.workload).with_(pair_wgrad=0 if args.no_pair_wgrad else 1)
     if args.recompute or args.offload:
         cfg = cfg.with_(recompute=1, offload_acts=1 if args.offload else 0)
+    loss_scale = 1.0
+    if args.fp16:
+        if cfg.dtype != 1 or args.ministages:
+            print("bench.py: --fp16 applies to the bf16 workloads and not to --ministages", file=sys.stderr)
+            sys.exit(2)
+        cfg, loss_scale = cfg.with_(dtype=2), 1024.0
     if args.offload and args.graph:
         print("bench.py: --offload cannot be combined with --graph", file=sys.stderr)
         sys.exit(2)
@@ -286,8 +295,8 @@ def main():
     cc = zs.make_config(cfg)
     P, mem, _ = zs.query(cc)
     b, e = cc.shard_begin, cc.shard_end
-    bf = cfg.dtype == 1
-    td = torch.bfloat16 if bf else torch.float32
+    bf = cfg.dtype != 0
+    td = torch.bfloat16 if cfg.dtype == 1 else torch.float16 if cfg.dtype == 2 else torch.float32
     M, T, H = cfg.num_microbatches, cfg.tokens, cfg.hidden
 
     if not args.ministages:
@@ -304,7 +313,7 @@ def main():
         xs = [torch.randn(T, H, device=dev).to(td) for _ in range(M)]
     tgs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
     losses = [torch.zeros(1, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
-    dys = [None] * M if cfg.has_head else [(torch.randn(T, H, device=dev) * 0.01).to(td) for _ in range(M)]
+    dys = [None] * M if cfg.has_head else [(torch.randn(T, H, device=dev) * (0.01 * loss_scale)).to(td) for _ in range(M)]
     ys = [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
     dxs = [None] * M if cfg.has_embed else [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
     if args.ministages:
@@ -320,10 +329,14 @@ def main():
         for i in range(M):
             stage.forward(i, xs[i], ys[i], tgs[i], losses[i])
         for i in reversed(range(M)):
-            stage.backward(i, dys[i], dxs[i], 1.0 / M)
+            stage.backward(i, dys[i], dxs[i], loss_scale / M)
             stage.accumulate(i)
 
     graph = None
+    overflow = None
+    if args.fp16:
+        overflow = torch.zeros(1, dtype=torch.int32, device=dev)
+        zs.lib().stage_set_overflow_flag(stage.h, overflow.data_ptr())
 
     def step(t):
         if args.ministages:
@@ -333,7 +346,7 @@ def main():
             stage.graph_replayed(M)
         else:
             microbatches()
-        stage.optimizer_step(t)
+        stage.optimizer_step(t, 1.0 / loss_scale)
 
     t = 0
     if args.graph:
@@ -413,7 +426,7 @@ def main():
         "metric": "stage train tokens/s on 1 MI355X (fwd+bwd+AdamW); MFMA util % of bf16 peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if bf else "f32", "data": "synthetic",
+        "dtype": {0: "f32", 1: "bf16", 2: "f16"}[cfg.dtype], "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.layers} layers, hidden {cfg.hidden}, heads {cfg.heads}, ffn {cfg.ffn}, "
                                f"seq {cfg.seq}, microbatch {cfg.microbatch} x {M} microbatches, "
                                f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {shard_elems} of {P} params, "
@@ -427,6 +440,8 @@ def main():
         "roofline": roofline, "kernels": kernels, "hip_graph": bool(args.graph),
         "memory_bytes": mem,
     }
+    if overflow is not None:
+        out["fp16"] = {"loss_scale": loss_scale, "overflow_flag": int(overflow.item())}
     if "adamw" in kernels:
         out["adamw_hbm_frac"] = kernels["adamw"].get("gbs", 0.0) / PEAK_HBM_GBS
     if args.ministages:

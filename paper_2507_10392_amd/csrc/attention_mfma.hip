@@ -15,6 +15,20 @@
 // log-sum-exp.  delta_i = dO_i . O_i is formed by the dQ kernel for its own rows and stored for the other.
 #include "kernels.h"
 
+// This file is compiled twice: as it stands for bf16, and through attention_mfma_f16.hip (which defines
+// ZS_ATTN_F16 and includes it) for IEEE half.  e16 is the 16-bit element type of the build; the two builds
+// differ in the conversions to and from float, the matrix-core instruction and the names they export.
+#ifdef ZS_ATTN_F16
+#define ZS_ATTN_MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16
+#define ZS_ATTN_NAME(x) x##_f16
+namespace zs { typedef f16 e16; typedef f16x8 e16x8; typedef f16x4 e16x4; }
+#else
+#define ZS_ATTN_MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16
+#define ZS_ATTN_NAME(x) x
+namespace zs { typedef bf16 e16; typedef bf16x8 e16x8; typedef bf16x4 e16x4; }
+#endif
+
+
 namespace zs {
 
 namespace {
@@ -32,77 +46,77 @@ constexpr float LN2 = 0.6931471805599453f;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-__device__ __forceinline__ bf16x8 zero8() {
-  bf16x8 z;
+__device__ __forceinline__ e16x8 zero8() {
+  e16x8 z;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) z[i] = (bf16)0.f;
+  for (int i = 0; i < 8; ++i) z[i] = (e16)0.f;
   return z;
 }
 
 // A-operand fragment of a row-major LDS tile: lane (row = lane%32, g = lane/32) gets 8 consecutive columns.
-__device__ __forceinline__ bf16x8 lds_frag(const bf16* tile, int row0, int col0, int lane) {
-  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 31)) * LDT + col0 + 8 * (lane >> 5));
+__device__ __forceinline__ e16x8 lds_frag(const e16* tile, int row0, int col0, int lane) {
+  return *reinterpret_cast<const e16x8*>(tile + (row0 + (lane & 31)) * LDT + col0 + 8 * (lane >> 5));
 }
 
 // A-operand fragment of the TRANSPOSE of a row-major LDS tile M[k][n]: lane (i = lane%32, g = lane/32)
 // gets M[k][n0+i] for the 8 contraction slots  k = k0 + 4g + {0,1,2,3, 8,9,10,11}.  This slot order is
 // the order in which a lane's accumulator registers 8s..8s+7 of a 32-row MFMA block hold rows, so the
 // matching B operand is just those registers.
-__device__ __forceinline__ bf16x8 lds_frag_tr(const bf16* tile, int k0, int n0, int lane) {
+__device__ __forceinline__ e16x8 lds_frag_tr(const e16* tile, int k0, int n0, int lane) {
   const int r = lane & 15, gi = lane >> 4;
-  const bf16* p = tile + (k0 + 4 * (gi >> 1) + (r >> 2)) * LDT + n0 + 16 * (gi & 1) + 4 * (r & 3);
+  const e16* p = tile + (k0 + 4 * (gi >> 1) + (r >> 2)) * LDT + n0 + 16 * (gi & 1) + 4 * (r & 3);
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * LDT));
-  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  union { struct { s16x4 a, b; } s; e16x8 v; } u;
   u.s.a = lo;
   u.s.b = hi;
   return u.v;
 }
 
-__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int s) {
-  bf16x8 o;
+__device__ __forceinline__ e16x8 pack8(const f32x16& a, int s) {
+  e16x8 o;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (bf16)a[8 * s + e];
+  for (int e = 0; e < 8; ++e) o[e] = (e16)a[8 * s + e];
   return o;
 }
 
 // A 64 x 128 tile moves HBM -> registers (fetch, issued before the MFMAs of the current tile so the
 // latency hides behind them) -> LDS (put, after them).  Thread t carries 4 vectors of 16 bytes:
 // vector v = t + 256 i is row v/16, columns 8*(v%16)...
-template <int NT> struct TileRegs { bf16x8 v[1024 / NT]; };   // NT threads share the 1024 vectors of a tile
+template <int NT> struct TileRegs { e16x8 v[1024 / NT]; };   // NT threads share the 1024 vectors of a tile
 // Rows of one (batch, head) are read through a raw buffer descriptor over [first row, last row's 128 columns]:
 // the per-lane offset is one register, the tile's row offset a scalar, and rows at or past nrows fall
 // beyond num_records and read as zero without a branch.  Offsets are 32-bit: nrows * ld * 2 < 2^31.
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const bf16* base, int64_t ld, int nrows) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16*>(base), 0, (int)((((int64_t)nrows - 1) * ld + D) * 2), 0x00020000);
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const e16* base, int64_t ld, int nrows) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<e16*>(base), 0, (int)((((int64_t)nrows - 1) * ld + D) * 2), 0x00020000);
 }
 template <int NT>
 __device__ __forceinline__ void fetch_tile(TileRegs<NT>& x, __amdgpu_buffer_rsrc_t rs, int ld, int row0, int tid) {
   const int voff = ((tid >> 4) * ld + (tid & 15) * 8) * 2;
 #pragma unroll
   for (int i = 0; i < 1024 / NT; ++i) {
-    union { u32x4 u; bf16x8 h; } c;
+    union { u32x4 u; e16x8 h; } c;
     c.u = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, (row0 + (NT / 16) * i) * ld * 2, 0);
     x.v[i] = c.h;
   }
 }
-template <int NT> __device__ __forceinline__ void put_tile(const TileRegs<NT>& x, bf16* tile, int tid) {
+template <int NT> __device__ __forceinline__ void put_tile(const TileRegs<NT>& x, e16* tile, int tid) {
 #pragma unroll
   for (int i = 0; i < 1024 / NT; ++i) {
     const int v = tid + NT * i;
-    *reinterpret_cast<bf16x8*>(tile + (v >> 4) * LDT + (v & 15) * 8) = x.v[i];
+    *reinterpret_cast<e16x8*>(tile + (v >> 4) * LDT + (v & 15) * 8) = x.v[i];
   }
 }
 
 // Row fragments kept in registers for a whole kernel: lane (row = row0 + lane%32, g) holds, for each of the
 // 8 contraction steps over d, 8 consecutive elements.  Rows >= nrows read as zero.
-__device__ __forceinline__ void load_row_frags(bf16x8 (&f)[8], const bf16* __restrict__ src, int64_t ld, int row0,
+__device__ __forceinline__ void load_row_frags(e16x8 (&f)[8], const e16* __restrict__ src, int64_t ld, int row0,
                                                int nrows, int lane) {
   const int row = row0 + (lane & 31);
 #pragma unroll
   for (int s = 0; s < 8; ++s)
-    f[s] = row < nrows ? *reinterpret_cast<const bf16x8*>(src + (int64_t)row * ld + 16 * s + 8 * (lane >> 5)) : zero8();
+    f[s] = row < nrows ? *reinterpret_cast<const e16x8*>(src + (int64_t)row * ld + 16 * s + 8 * (lane >> 5)) : zero8();
 }
 
 // Row index (inside a 32-row MFMA block) held by accumulator register r of this lane.
@@ -134,24 +148,24 @@ __device__ __forceinline__ void unrotate4(float (&x)[4], const float2* __restric
 
 // ------------------------------------------------------------------------------------------ forward
 // grid ceil(S/128)*nh*mb; wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
-                                                       const bf16* __restrict__ v, int64_t ld, bf16* __restrict__ o,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const e16* __restrict__ q, const e16* __restrict__ k,
+                                                       const e16* __restrict__ v, int64_t ld, e16* __restrict__ o,
                                                        int64_t ldo, float* __restrict__ lse, float scale_log2, int nh,
                                                        int mb) {
   extern __shared__ __align__(16) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);            // [2][K tile | V tile]
+  e16* smem = reinterpret_cast<e16*>(smem_raw);            // [2][K tile | V tile]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const BlockId bid = block_id(nh, mb);
   const int qb = (S + 127) / 128 - 1 - bid.rank, h = bid.h, b = bid.b;
   const int64_t tok0 = (int64_t)b * S;
-  const bf16* qh = q + tok0 * ld + h * D;
-  const bf16* kh = k + tok0 * ld + h * D;
-  const bf16* vh = v + tok0 * ld + h * D;
+  const e16* qh = q + tok0 * ld + h * D;
+  const e16* kh = k + tok0 * ld + h * D;
+  const e16* vh = v + tok0 * ld + h * D;
   const __amdgpu_buffer_rsrc_t rsk = head_rsrc(kh, ld, S), rsv = head_rsrc(vh, ld, S);
   const int q0 = qb * 128, wq0 = q0 + wave * 32;
   const int my_q = wq0 + (lane & 31);
 
-  bf16x8 qf[8];
+  e16x8 qf[8];
   load_row_frags(qf, qh, ld, wq0, S, lane);
   f32x16 oacc[4];
 #pragma unroll
@@ -169,8 +183,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
   put_tile(vr, smem + TILE, tid);
   __syncthreads();
   for (int t = 0; t < ntiles; ++t) {
-    const bf16* Kt = smem + (t & 1) * 2 * TILE;
-    const bf16* Vt = Kt + TILE;
+    const e16* Kt = smem + (t & 1) * 2 * TILE;
+    const e16* Vt = Kt + TILE;
     if (t + 1 < ntiles) {
       fetch_tile(kr, rsk, (int)ld, (t + 1) * TR, tid);
       fetch_tile(vr, rsv, (int)ld, (t + 1) * TR, tid);
@@ -184,7 +198,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
         for (int r = 0; r < 16; ++r) sacc[jb][r] = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s)
-          sacc[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Kt, jb * 32, 16 * s, lane), qf[s], sacc[jb], 0, 0, 0);
+          sacc[jb] = ZS_ATTN_MFMA(lds_frag(Kt, jb * 32, 16 * s, lane), qf[s], sacc[jb], 0, 0, 0);
       }
       if (key0 + TR - 1 > wq0) {   // tile touches the diagonal: mask keys in the future of this lane's query
 #pragma unroll
@@ -200,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[jb][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;   // scale > 0, so the maximum commutes with it
       // Lazy rescaling: the reference maximum m only moves when some row's maximum grew by more than 2^8;
-      // until then P is formed against the old reference (values up to 2^8, harmless in bf16/fp32) and the
+      // until then P is formed against the old reference (values up to 2^8, harmless in e16/fp32) and the
       // 64 accumulator registers are left alone.  m, l and O always refer to the same reference, so
       // O/l and m + log2(l) are exact whatever the schedule of updates.
       if (__any(mx > m + 8.0f)) {
@@ -228,10 +242,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 pf = pack8(sacc[jb], s2);
+          const e16x8 pf = pack8(sacc[jb], s2);
 #pragma unroll
           for (int db = 0; db < 4; ++db)
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(Vt, jb * 32 + 16 * s2, db * 32, lane), pf,
+            oacc[db] = ZS_ATTN_MFMA(lds_frag_tr(Vt, jb * 32 + 16 * s2, db * 32, lane), pf,
                                                                oacc[db], 0, 0, 0);
         }
     }
@@ -243,15 +257,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
   }
   if (my_q < S) {
     const float inv = 1.0f / l;
-    bf16* orow = o + (tok0 + my_q) * ldo + h * D;
+    e16* orow = o + (tok0 + my_q) * ldo + h * D;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        bf16x4 w;
+        e16x4 w;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (bf16)(oacc[db][4 * c + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + db * 32 + 8 * c + 4 * (lane >> 5)) = w;
+        for (int e = 0; e < 4; ++e) w[e] = (e16)(oacc[db][4 * c + e] * inv);
+        *reinterpret_cast<e16x4*>(orow + db * 32 + 8 * c + 4 * (lane >> 5)) = w;
       }
     if (lane < 32) lse[((int64_t)b * nh + h) * S + my_q] = (m + log2f(l)) * LN2;
   }
@@ -260,29 +274,29 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const bf16* __r
 // ------------------------------------------------------------------------------------------ dQ
 // grid ceil(S/128)*nh*mb; wave w owns queries q0+32w..; loops over K/V tiles up to the diagonal.
 // dQ^T[d][q] += K^T[d][key] dS^T[key][q],  dS^T = P^T o (dP^T - delta_q),  dP^T = V dO^T.
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
-                                                          const bf16* __restrict__ v, int64_t ld,
-                                                          const bf16* __restrict__ o, const bf16* __restrict__ dout,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const e16* __restrict__ q, const e16* __restrict__ k,
+                                                          const e16* __restrict__ v, int64_t ld,
+                                                          const e16* __restrict__ o, const e16* __restrict__ dout,
                                                           int64_t ldo, const float* __restrict__ lse,
                                                           float* __restrict__ delta,
-                                                          bf16* __restrict__ dq, int64_t ldd, float scale, int nh,
+                                                          e16* __restrict__ dq, int64_t ldd, float scale, int nh,
                                                           int mb, const float2* __restrict__ rope) {
   extern __shared__ __align__(16) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  e16* smem = reinterpret_cast<e16*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const BlockId bid = block_id(nh, mb);
   const int qb = (S + 127) / 128 - 1 - bid.rank, h = bid.h, b = bid.b;
   const int64_t tok0 = (int64_t)b * S;
-  const bf16* qh = q + tok0 * ld + h * D;
-  const bf16* kh = k + tok0 * ld + h * D;
-  const bf16* vh = v + tok0 * ld + h * D;
-  const bf16* doh = dout + tok0 * ldo + h * D;
+  const e16* qh = q + tok0 * ld + h * D;
+  const e16* kh = k + tok0 * ld + h * D;
+  const e16* vh = v + tok0 * ld + h * D;
+  const e16* doh = dout + tok0 * ldo + h * D;
   const __amdgpu_buffer_rsrc_t rsk = head_rsrc(kh, ld, S), rsv = head_rsrc(vh, ld, S);
   const int q0 = qb * 128, wq0 = q0 + wave * 32;
   const int my_q = wq0 + (lane & 31);
   const float scale_log2 = scale * LOG2E;
 
-  bf16x8 qf[8], dof[8];
+  e16x8 qf[8], dof[8];
   load_row_frags(qf, qh, ld, wq0, S, lane);
   load_row_frags(dof, doh, ldo, wq0, S, lane);
   const int64_t stat = ((int64_t)b * nh + h) * S + min(my_q, S - 1);
@@ -291,7 +305,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
   // The value is also stored for the dK/dV kernel, which runs after this one.
   float dlt = 0.f;
   {
-    bf16x8 of[8];
+    e16x8 of[8];
     load_row_frags(of, o + tok0 * ldo + h * D, ldo, wq0, S, lane);
 #pragma unroll
     for (int s = 0; s < 8; ++s)
@@ -315,8 +329,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
   put_tile(vr, smem + TILE, tid);
   __syncthreads();
   for (int t = 0; t < ntiles; ++t) {
-    const bf16* Kt = smem + (t & 1) * 2 * TILE;
-    const bf16* Vt = Kt + TILE;
+    const e16* Kt = smem + (t & 1) * 2 * TILE;
+    const e16* Vt = Kt + TILE;
     if (t + 1 < ntiles) {
       fetch_tile(kr, rsk, (int)ld, (t + 1) * TR, tid);
       fetch_tile(vr, rsv, (int)ld, (t + 1) * TR, tid);
@@ -331,8 +345,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
         for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Kt, jb * 32, 16 * s, lane), qf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Vt, jb * 32, 16 * s, lane), dof[s], pacc, 0, 0, 0);
+          sacc = ZS_ATTN_MFMA(lds_frag(Kt, jb * 32, 16 * s, lane), qf[s], sacc, 0, 0, 0);
+          pacc = ZS_ATTN_MFMA(lds_frag(Vt, jb * 32, 16 * s, lane), dof[s], pacc, 0, 0, 0);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] = __builtin_amdgcn_exp2f(fmaf(sacc[r], scale_log2, -lse2)) * (pacc[r] - dlt);
@@ -343,10 +357,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 dsf = pack8(sacc, s2);
+          const e16x8 dsf = pack8(sacc, s2);
 #pragma unroll
           for (int db = 0; db < 4; ++db)
-            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(Kt, jb * 32 + 16 * s2, db * 32, lane), dsf,
+            acc[db] = ZS_ATTN_MFMA(lds_frag_tr(Kt, jb * 32 + 16 * s2, db * 32, lane), dsf,
                                                               acc[db], 0, 0, 0);
         }
       }
@@ -358,7 +372,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
     __syncthreads();
   }
   if (my_q < S) {
-    bf16* row = dq + (tok0 + my_q) * ldd + h * D;
+    e16* row = dq + (tok0 + my_q) * ldd + h * D;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -367,10 +381,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
 #pragma unroll
         for (int e = 0; e < 4; ++e) x[e] = acc[db][4 * c + e] * scale;
         if (rope) unrotate4(x, rope, my_q, db * 32 + 8 * c + 4 * (lane >> 5));
-        bf16x4 w;
+        e16x4 w;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (bf16)x[e];
-        *reinterpret_cast<bf16x4*>(row + db * 32 + 8 * c + 4 * (lane >> 5)) = w;
+        for (int e = 0; e < 4; ++e) w[e] = (e16)x[e];
+        *reinterpret_cast<e16x4*>(row + db * 32 + 8 * c + 4 * (lane >> 5)) = w;
       }
   }
 }
@@ -382,23 +396,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const bf16* 
 // S[q][key] = Q K^T (lane = key, registers = queries), P = exp2(S c - lse_q), dP = dO V^T,
 // dV^T[d][key] += dO^T[d][q] P[q][key],  dK^T[d][key] += Q^T[d][q] dS[q][key].
 template <int NW>
-__global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16* __restrict__ q, const bf16* __restrict__ k,
-                                                           const bf16* __restrict__ v, int64_t ld,
-                                                           const bf16* __restrict__ dout, int64_t ldo,
+__global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const e16* __restrict__ q, const e16* __restrict__ k,
+                                                           const e16* __restrict__ v, int64_t ld,
+                                                           const e16* __restrict__ dout, int64_t ldo,
                                                            const float* __restrict__ lse, const float* __restrict__ delta,
-                                                           bf16* __restrict__ dk, bf16* __restrict__ dv, int64_t ldd,
+                                                           e16* __restrict__ dk, e16* __restrict__ dv, int64_t ldd,
                                                            float scale, int nh, int mb, const float2* __restrict__ rope) {
   extern __shared__ __align__(16) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);                 // [2][Q tile | dO tile]
+  e16* smem = reinterpret_cast<e16*>(smem_raw);                 // [2][Q tile | dO tile]
   float* stats = reinterpret_cast<float*>(smem + 4 * TILE);       // [2][lse2[64] | delta[64]]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const BlockId bid = block_id(nh, mb);
   const int kb = bid.rank, h = bid.h, b = bid.b;                   // early key blocks (most work) first
   const int64_t tok0 = (int64_t)b * S;
-  const bf16* qh = q + tok0 * ld + h * D;
-  const bf16* kh = k + tok0 * ld + h * D;
-  const bf16* vh = v + tok0 * ld + h * D;
-  const bf16* doh = dout + tok0 * ldo + h * D;
+  const e16* qh = q + tok0 * ld + h * D;
+  const e16* kh = k + tok0 * ld + h * D;
+  const e16* vh = v + tok0 * ld + h * D;
+  const e16* doh = dout + tok0 * ldo + h * D;
   const __amdgpu_buffer_rsrc_t rsq = head_rsrc(qh, ld, S), rsdo = head_rsrc(doh, ldo, S);
   const float* lse_h = lse + ((int64_t)b * nh + h) * S;
   const float* dlt_h = delta + ((int64_t)b * nh + h) * S;
@@ -409,14 +423,14 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
   // K fragments stay in registers; the wave's 32 rows of V go to a private LDS block instead and are
   // read back as B operands (same fragment pattern as the A operands), which keeps the kernel within
   // the register budget of two waves per SIMD.
-  bf16x8 kf[8];
+  e16x8 kf[8];
   load_row_frags(kf, kh, ld, wk0, S, lane);
-  bf16* Vw = reinterpret_cast<bf16*>(stats + 256) + wave * 32 * LDT;
+  e16* Vw = reinterpret_cast<e16*>(stats + 256) + wave * 32 * LDT;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int vv = lane + 64 * i, r = vv >> 4, c = (vv & 15) * 8;
-    *reinterpret_cast<bf16x8*>(Vw + r * LDT + c) =
-        wk0 + r < S ? *reinterpret_cast<const bf16x8*>(vh + (int64_t)(wk0 + r) * ld + c) : zero8();
+    *reinterpret_cast<e16x8*>(Vw + r * LDT + c) =
+        wk0 + r < S ? *reinterpret_cast<const e16x8*>(vh + (int64_t)(wk0 + r) * ld + c) : zero8();
   }
   f32x16 dkacc[4], dvacc[4];
 #pragma unroll
@@ -446,8 +460,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
   __syncthreads();
   for (int t = t_begin; t < t_end; ++t) {
     const int buf = (t - t_begin) & 1;
-    const bf16* Qt = smem + buf * 2 * TILE;
-    const bf16* dOt = Qt + TILE;
+    const e16* Qt = smem + buf * 2 * TILE;
+    const e16* dOt = Qt + TILE;
     const float* st = stats + buf * 128;
     if (t + 1 < t_end) fetch(t + 1);
     const int qrow0 = t * TR;
@@ -460,8 +474,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
         for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Qt, ib * 32, 16 * s, lane), kf[s], sacc, 0, 0, 0);
-          pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(dOt, ib * 32, 16 * s, lane), lds_frag(Vw, 0, 16 * s, lane), pacc,
+          sacc = ZS_ATTN_MFMA(lds_frag(Qt, ib * 32, 16 * s, lane), kf[s], sacc, 0, 0, 0);
+          pacc = ZS_ATTN_MFMA(lds_frag(dOt, ib * 32, 16 * s, lane), lds_frag(Vw, 0, 16 * s, lane), pacc,
                                                          0, 0, 0);
         }
 #pragma unroll
@@ -480,12 +494,12 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 pf = pack8(sacc, s2), dsf = pack8(pacc, s2);
+          const e16x8 pf = pack8(sacc, s2), dsf = pack8(pacc, s2);
 #pragma unroll
           for (int db = 0; db < 4; ++db) {
-            dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(dOt, ib * 32 + 16 * s2, db * 32, lane), pf,
+            dvacc[db] = ZS_ATTN_MFMA(lds_frag_tr(dOt, ib * 32 + 16 * s2, db * 32, lane), pf,
                                                                 dvacc[db], 0, 0, 0);
-            dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_tr(Qt, ib * 32 + 16 * s2, db * 32, lane), dsf,
+            dkacc[db] = ZS_ATTN_MFMA(lds_frag_tr(Qt, ib * 32 + 16 * s2, db * 32, lane), dsf,
                                                                 dkacc[db], 0, 0, 0);
           }
         }
@@ -495,8 +509,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
     __syncthreads();
   }
   if (my_k < S) {
-    bf16* krow = dk + (tok0 + my_k) * ldd + h * D;
-    bf16* vrow = dv + (tok0 + my_k) * ldd + h * D;
+    e16* krow = dk + (tok0 + my_k) * ldd + h * D;
+    e16* vrow = dv + (tok0 + my_k) * ldd + h * D;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -505,20 +519,20 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const bf16
 #pragma unroll
         for (int e = 0; e < 4; ++e) x[e] = dkacc[db][4 * c + e] * scale;
         if (rope) unrotate4(x, rope, my_k, db * 32 + 8 * c + 4 * (lane >> 5));
-        bf16x4 wk, wv;
+        e16x4 wk, wv;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          wk[e] = (bf16)x[e];
-          wv[e] = (bf16)dvacc[db][4 * c + e];
+          wk[e] = (e16)x[e];
+          wv[e] = (e16)dvacc[db][4 * c + e];
         }
-        *reinterpret_cast<bf16x4*>(krow + db * 32 + 8 * c + 4 * (lane >> 5)) = wk;
-        *reinterpret_cast<bf16x4*>(vrow + db * 32 + 8 * c + 4 * (lane >> 5)) = wv;
+        *reinterpret_cast<e16x4*>(krow + db * 32 + 8 * c + 4 * (lane >> 5)) = wk;
+        *reinterpret_cast<e16x4*>(vrow + db * 32 + 8 * c + 4 * (lane >> 5)) = wv;
       }
   }
 }
 
-constexpr size_t SMEM_FWD = 4 * TILE * sizeof(bf16);                    // 77824
-constexpr size_t smem_dkv(int nw) { return 4 * TILE * sizeof(bf16) + 256 * sizeof(float) + (size_t)nw * 32 * LDT * sizeof(bf16); }
+constexpr size_t SMEM_FWD = 4 * TILE * sizeof(e16);                    // 77824
+constexpr size_t smem_dkv(int nw) { return 4 * TILE * sizeof(e16) + 256 * sizeof(float) + (size_t)nw * 32 * LDT * sizeof(e16); }
 
 template <typename K> hipError_t set_smem(K kern, size_t bytes, bool& done) {
   if (done) return hipSuccess;
@@ -529,21 +543,23 @@ template <typename K> hipError_t set_smem(K kern, size_t bytes, bool& done) {
 
 }  // namespace
 
-bool attn_mfma_supported(DType dt, int S, int d) { return dt == BF16 && d == D && S >= 1; }
+#ifndef ZS_ATTN_F16
+bool attn_mfma_supported(DType dt, int S, int d) { return (dt == BF16 || dt == F16) && d == D && S >= 1; }
+#endif
 
-hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
+hipError_t ZS_ATTN_NAME(attn_fwd_mfma)(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, void* o, int64_t ldo, float* lse) {
   if ((int64_t)S * ld * 2 >= (1ll << 31)) return hipErrorInvalidValue;      // 32-bit buffer offsets
   static bool cfg = false;
   hipError_t e = set_smem(attn_fwd_kernel, SMEM_FWD, cfg);
   if (e != hipSuccess) return e;
   dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
-  hipLaunchKernelGGL(attn_fwd_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                     (bf16*)o, ldo, lse, LOG2E / sqrtf((float)d), nh, mb);
+  hipLaunchKernelGGL(attn_fwd_kernel, grid, blk, SMEM_FWD, st, S, (const e16*)q, (const e16*)k, (const e16*)v, ld,
+                     (e16*)o, ldo, lse, LOG2E / sqrtf((float)d), nh, mb);
   return hipGetLastError();
 }
 
-hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
+hipError_t ZS_ATTN_NAME(attn_bwd_mfma)(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
                          void* dq, void* dk, void* dv, int64_t ldd, const float2* rope) {
   if ((int64_t)S * (ld > ldo ? ld : ldo) * 2 >= (1ll << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets
@@ -554,16 +570,16 @@ hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)d);
   dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                     (const bf16*)o, (const bf16*)dout, ldo, lse, delta, (bf16*)dq, ldd, scale, nh, mb, rope);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const e16*)q, (const e16*)k, (const e16*)v, ld,
+                     (const e16*)o, (const e16*)dout, ldo, lse, delta, (e16*)dq, ldd, scale, nh, mb, rope);
   // 256 keys per workgroup when that still gives every CU a workgroup, else 128
   if (cdiv(S, 256) * nh * mb >= 256) {
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), smem_dkv(8), st,
-                       S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld, (const bf16*)dout, ldo, lse, delta, (bf16*)dk,
-                       (bf16*)dv, ldd, scale, nh, mb, rope);
+                       S, (const e16*)q, (const e16*)k, (const e16*)v, ld, (const e16*)dout, ldo, lse, delta, (e16*)dk,
+                       (e16*)dv, ldd, scale, nh, mb, rope);
   } else {
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<4>, grid, blk, smem_dkv(4), st, S, (const bf16*)q, (const bf16*)k, (const bf16*)v, ld,
-                       (const bf16*)dout, ldo, lse, delta, (bf16*)dk, (bf16*)dv, ldd, scale, nh, mb, rope);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<4>, grid, blk, smem_dkv(4), st, S, (const e16*)q, (const e16*)k, (const e16*)v, ld,
+                       (const e16*)dout, ldo, lse, delta, (e16*)dk, (e16*)dv, ldd, scale, nh, mb, rope);
   }
   return hipGetLastError();
 }

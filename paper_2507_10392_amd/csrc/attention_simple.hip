@@ -208,6 +208,11 @@ hipError_t attn_fwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const voi
 hipError_t attn_bwd_mfma(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
                          void* dq, void* dk, void* dv, int64_t ldd, const float2* rope);
+hipError_t attn_fwd_mfma_f16(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
+                             int64_t ld, void* o, int64_t ldo, float* lse);
+hipError_t attn_bwd_mfma_f16(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
+                             int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
+                             void* dq, void* dk, void* dv, int64_t ldd, const float2* rope);
 bool attn_mfma_supported(DType dt, int S, int d);
 
 int attn_select(DType dt, int S, int d, int force) {
@@ -217,7 +222,9 @@ int attn_select(DType dt, int S, int d, int force) {
 
 hipError_t attn_fwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, const void* q, const void* k,
                     const void* v, int64_t ld, void* o, int64_t ldo, float* lse, int force) {
-  if (attn_select(dt, S, d, force) == ATTN_MFMA) return attn_fwd_mfma(st, mb, S, nh, d, q, k, v, ld, o, ldo, lse);
+  if (attn_select(dt, S, d, force) == ATTN_MFMA)
+    return dt == F16 ? attn_fwd_mfma_f16(st, mb, S, nh, d, q, k, v, ld, o, ldo, lse)
+                     : attn_fwd_mfma(st, mb, S, nh, d, q, k, v, ld, o, ldo, lse);
   return dt == F32    ? fwd_simple<float>(st, mb, S, nh, d, q, k, v, ld, o, ldo, lse)
          : dt == BF16 ? fwd_simple<bf16>(st, mb, S, nh, d, q, k, v, ld, o, ldo, lse)
                       : fwd_simple<f16>(st, mb, S, nh, d, q, k, v, ld, o, ldo, lse);
@@ -226,7 +233,8 @@ hipError_t attn_bwd(hipStream_t st, DType dt, int mb, int S, int nh, int d, cons
                     const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse,
                     float* delta, void* dq, void* dk, void* dv, int64_t ldd, const float2* rope, int force) {
   if (attn_select(dt, S, d, force) == ATTN_MFMA)   // rotation fused into the kernels' stores
-    return attn_bwd_mfma(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd, rope);
+    return dt == F16 ? attn_bwd_mfma_f16(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd, rope)
+                     : attn_bwd_mfma(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd, rope);
   hipError_t e = dt == F32    ? bwd_simple<float>(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd)
                  : dt == BF16 ? bwd_simple<bf16>(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd)
                               : bwd_simple<f16>(st, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd);

@@ -1,4 +1,4 @@
-// bf16 MFMA GEMM: argument checks and the choice of workgroup tile.  The kernels live in
+// 16-bit (bf16 / fp16) MFMA GEMM: argument checks and the choice of workgroup tile.  The kernels live in
 // gemm_mfma_impl.h, one translation unit per tile shape.
 #include "kernels.h"
 
@@ -6,6 +6,8 @@ namespace zs {
 
 hipError_t gemm_mfma_256x256(hipStream_t st, const Gemm& g);   // 8 wavefronts
 hipError_t gemm_mfma_128x128(hipStream_t st, const Gemm& g);   // 4 wavefronts, two workgroups per CU
+hipError_t gemm_mfma_256x256_f16(hipStream_t st, const Gemm& g);
+hipError_t gemm_mfma_128x128_f16(hipStream_t st, const Gemm& g);
 
 namespace {
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -16,7 +18,7 @@ int g_force_tile = 0;   // 0 automatic; 1: 256x256, 2: 128x128 (set through gemm
 // every leading dimension, batch stride and segment size a multiple of 8 elements; the extent
 // along each operand's contiguous axis must be a multiple of 8 as well.
 bool gemm_mfma_supported(DType dt, const Gemm& g) {
-  if (dt != BF16) return false;
+  if (dt != BF16 && dt != F16) return false;
   if (g.M < 1 || g.N < 1 || g.K < 1 || g.batch < 1) return false;
   if (!aligned16(g.A) || !aligned16(g.B)) return false;
   if (g.lda % 8 || g.ldb % 8 || g.sA % 8 || g.sB % 8) return false;
@@ -69,8 +71,10 @@ int gemm_mfma_pick_tile(const Gemm& g) {
 
 void gemm_mfma_force_tile(int id) { g_force_tile = id; }
 
-hipError_t gemm_mfma(hipStream_t st, const Gemm& g) {
-  return gemm_mfma_pick_tile(g) == 2 ? gemm_mfma_128x128(st, g) : gemm_mfma_256x256(st, g);
+hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g) {
+  const bool small = gemm_mfma_pick_tile(g) == 2;
+  if (dt == F16) return small ? gemm_mfma_128x128_f16(st, g) : gemm_mfma_256x256_f16(st, g);
+  return small ? gemm_mfma_128x128(st, g) : gemm_mfma_256x256(st, g);
 }
 
 }  // namespace zs

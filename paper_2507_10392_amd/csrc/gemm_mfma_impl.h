@@ -1,4 +1,4 @@
-// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation: the tile kernel,
+// 16-bit (bf16 or IEEE half) GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16 / _f16), fp32 accumulation: the tile kernel,
 // templated on the workgroup tile BM x BN and the number of wavefronts.
 //
 // One workgroup of 4 (2 x 2) or 8 (2 x 4) wavefronts computes a BM x BN tile of C; each wavefront owns
@@ -186,18 +186,28 @@ __device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x16 (&ac
   }
 }
 
-// Epilogue for bf16 output: after staging, ALL threads read rows back 8 columns at a time, add bias and
+// The matrix-core instruction for the element type E; fragments travel as 16-bit containers (bf16x8).
+template <typename E> __device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c);
+template <> __device__ __forceinline__ f32x16 mfma_32x32x16<bf16>(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x16 mfma_32x32x16<f16>(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// Epilogue for 16-bit output (E = bf16 or IEEE half): after staging, ALL threads read rows back 8 columns at a time, add bias and
 // residual in fp32, round once to bf16 and store 16 bytes per lane, consecutive lanes covering
 // consecutive 16-byte pieces of a row of C.
-template <int BM, int BN, int NT, int MI, int NJ>
+template <typename E, int BM, int BN, int NT, int MI, int NJ>
 __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
                                                int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
   static_assert((BM / 2) * LDW * 4 <= 2 * (slab_elems(BM) + slab_elems(BN)) * 2, "staging tile must fit the K-loop buffers");
+  typedef typename Vec<E>::type E8;
   const int lane = tid & 63;
-  const bf16* bias = g.bias ? (const bf16*)g.bias + (int64_t)z * g.sBias : nullptr;
-  const bf16* R = g.resid ? (const bf16*)g.resid + (int64_t)z * g.sC : nullptr;
-  bf16* Cz = (bf16*)g.C + (int64_t)z * g.sC;
+  const E* bias = g.bias ? (const E*)g.bias + (int64_t)z * g.sBias : nullptr;
+  const E* R = g.resid ? (const E*)g.resid + (int64_t)z * g.sC : nullptr;
+  E* Cz = (E*)g.C + (int64_t)z * g.sC;
   const bool rope = g.rope && z < g.rope_batches;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
@@ -216,12 +226,12 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
       float x[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
       if (col + 8 <= g.N) {
         if (bias) {
-          const bf16x8 bb = *reinterpret_cast<const bf16x8*>(bias + col);
+          const E8 bb = *reinterpret_cast<const E8*>(bias + col);
 #pragma unroll
           for (int e = 0; e < 8; ++e) x[e] += (float)bb[e];
         }
         if (R) {
-          const bf16x8 rr = *reinterpret_cast<const bf16x8*>(R + (int64_t)row * g.ldr + col);
+          const E8 rr = *reinterpret_cast<const E8*>(R + (int64_t)row * g.ldr + col);
 #pragma unroll
           for (int e = 0; e < 8; ++e) x[e] += (float)rr[e];
         }
@@ -236,16 +246,16 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
             x[2 * i + 1] = u * s4[i] + w * c4[i];
           }
         }
-        bf16x8 o;
+        E8 o;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (bf16)x[e];
-        *reinterpret_cast<bf16x8*>(Cz + (int64_t)row * g.ldc + col) = o;
+        for (int e = 0; e < 8; ++e) o[e] = (E)x[e];
+        *reinterpret_cast<E8*>(Cz + (int64_t)row * g.ldc + col) = o;
       } else {
         for (int e = 0; e < 8 && col + e < g.N; ++e) {
           float y = x[e];
           if (bias) y += (float)bias[col + e];
           if (R) y += (float)R[(int64_t)row * g.ldr + col + e];
-          Cz[(int64_t)row * g.ldc + col + e] = (bf16)y;
+          Cz[(int64_t)row * g.ldc + col + e] = (E)y;
         }
       }
     }
@@ -254,7 +264,7 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
 
 // NW wavefronts: 4 as a 2 x 2 grid, or 8 as 2 (m) x 4 (n), in which case two waves share each SIMD and one
 // wave's loads, LDS traffic and barrier waits overlap the other's MFMAs.
-template <int BM, int BN, int NW, int TA, int TB, int SEG, int ACC>
+template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG, int ACC>
 __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma_kernel(Gemm g, int tiles_m,
                                                                                                         int tiles_n) {
   constexpr int NT = 64 * NW, WN = NW / 2;               // threads; waves along n (2 along m)
@@ -354,7 +364,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma_32x32x16<E>(b[j], a[i], acc[i][j]);
       stash_a(buf ^ 1, fa, ks * VA / 4, (ks + 1) * VA / 4);
       stash_b(buf ^ 1, fb, ks * VB / 4, (ks + 1) * VB / 4);
     }
@@ -377,13 +387,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   }
 
   if (ACC) epilogue_accum<BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
-  else epilogue_store<BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
+  else epilogue_store<E, BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
 }
 
-template <int BM, int BN, int NW, int TA, int TB, int SEG, int ACC> hipError_t launch2(hipStream_t st, const Gemm& g) {
+template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG, int ACC> hipError_t launch2(hipStream_t st, const Gemm& g) {
   constexpr size_t SMEM_BYTES = 2 * (slab_elems(BM) + slab_elems(BN)) * sizeof(bf16);
   static bool configured = false;
-  auto kern = gemm_mfma_kernel<BM, BN, NW, TA, TB, SEG, ACC>;
+  auto kern = gemm_mfma_kernel<E, BM, BN, NW, TA, TB, SEG, ACC>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
     if (e != hipSuccess) return e;
@@ -395,17 +405,17 @@ template <int BM, int BN, int NW, int TA, int TB, int SEG, int ACC> hipError_t l
   return hipGetLastError();
 }
 
-template <int BM, int BN, int NW, int TA, int TB, int SEG> hipError_t launch(hipStream_t st, const Gemm& g) {
-  return g.c_f32_accum ? launch2<BM, BN, NW, TA, TB, SEG, 1>(st, g) : launch2<BM, BN, NW, TA, TB, SEG, 0>(st, g);
+template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG> hipError_t launch(hipStream_t st, const Gemm& g) {
+  return g.c_f32_accum ? launch2<E, BM, BN, NW, TA, TB, SEG, 1>(st, g) : launch2<E, BM, BN, NW, TA, TB, SEG, 0>(st, g);
 }
 
-template <int BM, int BN, int NW> hipError_t gemm_mfma_tile(hipStream_t st, const Gemm& g) {
-  if (g.A2) return launch<BM, BN, NW, 1, 0, 1>(st, g);
-  if (g.kseg) return g.transA ? launch<BM, BN, NW, 1, 1, 1>(st, g) : launch<BM, BN, NW, 0, 1, 1>(st, g);
-  if (!g.transA && !g.transB) return launch<BM, BN, NW, 0, 0, 0>(st, g);
-  if (!g.transA && g.transB) return launch<BM, BN, NW, 0, 1, 0>(st, g);
-  if (g.transA && !g.transB) return launch<BM, BN, NW, 1, 0, 0>(st, g);
-  return launch<BM, BN, NW, 1, 1, 0>(st, g);
+template <typename E, int BM, int BN, int NW> hipError_t gemm_mfma_tile(hipStream_t st, const Gemm& g) {
+  if (g.A2) return launch<E, BM, BN, NW, 1, 0, 1>(st, g);
+  if (g.kseg) return g.transA ? launch<E, BM, BN, NW, 1, 1, 1>(st, g) : launch<E, BM, BN, NW, 0, 1, 1>(st, g);
+  if (!g.transA && !g.transB) return launch<E, BM, BN, NW, 0, 0, 0>(st, g);
+  if (!g.transA && g.transB) return launch<E, BM, BN, NW, 0, 1, 0>(st, g);
+  if (g.transA && !g.transB) return launch<E, BM, BN, NW, 1, 0, 0>(st, g);
+  return launch<E, BM, BN, NW, 1, 1, 0>(st, g);
 }
 
 }  // namespace gemm_impl

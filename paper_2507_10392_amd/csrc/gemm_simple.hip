@@ -114,7 +114,7 @@ namespace {
 // One launch: the MFMA kernel when it takes the arguments, else the plain kernel (with the rotation and the
 // two-part K range done in extra passes).
 hipError_t gemm_one(hipStream_t st, DType dt, const Gemm& g, int force) {
-  if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, g);   // rotation fused into its epilogue
+  if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, dt, g);   // rotation fused into its epilogue
   if (g.A2) {   // two-part K range: one plain product per part
     Gemm a = g, b = g;
     a.A2 = a.B2 = nullptr; a.K = g.kseg; a.kseg = 0;
@@ -179,7 +179,7 @@ bool split_k(const Gemm& g, std::vector<Gemm>& parts) {
 }  // namespace
 
 bool gemm_splits(DType dt, const Gemm& g) {
-  if (dt != BF16 || gemm_mfma_supported(dt, g)) return false;
+  if (dt == F32 || gemm_mfma_supported(dt, g)) return false;
   std::vector<Gemm> parts;
   if (!(split_rows(g, parts) || split_k(g, parts))) return false;
   for (const Gemm& p : parts)
@@ -188,7 +188,7 @@ bool gemm_splits(DType dt, const Gemm& g) {
 }
 
 hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
-  if (dt == BF16 && force != GEMM_SIMPLE && !gemm_mfma_supported(dt, g)) {
+  if (dt != F32 && force != GEMM_SIMPLE && !gemm_mfma_supported(dt, g)) {
     std::vector<Gemm> parts;
     if (g.A2) {   // the two parts of a paired weight gradient on their own, each cut further if it has to be
       Gemm a = g, b = g;

@@ -40,7 +40,7 @@ hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force);
 bool gemm_splits(DType dt, const Gemm& g);
 hipError_t gemm_simple(hipStream_t st, DType dt, const Gemm& g);
 bool gemm_mfma_supported(DType dt, const Gemm& g);
-hipError_t gemm_mfma(hipStream_t st, const Gemm& g);
+hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g);
 // Workgroup tile the MFMA kernel would use: 1 = 256x256 (8 waves), 2 = 128x128 (4 waves); force_tile(0) = automatic.
 int gemm_mfma_pick_tile(const Gemm& g);
 void gemm_mfma_force_tile(int id);

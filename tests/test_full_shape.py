@@ -18,18 +18,18 @@ from workloads import get_config, make_inputs, round_bf16
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["C3", "C2"])
-def test_one_layer_one_microbatch_at_full_shape(gpu_device, name):
-    cfg = get_config(name).with_(layers=1, num_microbatches=1, shard_num=1, shard_den=1)
-    print(f"[case] full-shape single layer {name}: T={cfg.tokens} H={cfg.hidden} F={cfg.ffn}", flush=True)
-    inp = make_inputs(cfg, perturbed=True)
+@pytest.mark.parametrize("name,dtype", [("C3", 1), ("C2", 1), ("C3", 2)])
+def test_one_layer_one_microbatch_at_full_shape(gpu_device, name, dtype):
+    cfg = get_config(name).with_(layers=1, num_microbatches=1, shard_num=1, shard_den=1, dtype=dtype)
+    print(f"[case] full-shape single layer {name} dtype={dtype}: T={cfg.tokens} H={cfg.hidden} F={cfg.ffn}", flush=True)
+    inp = make_inputs(cfg, perturbed=True, dy_scale=1024.0 if dtype == 2 else 1.0)   # fp16 runs with a loss scale
     g = GpuStage(cfg, inp)
     gpu = g.run_microbatches(inp)
     g.stage.close()
     ora = oracle_step(cfg, inp)
     rep = []
     compare_step(cfg, gpu, ora, TOL[cfg.dtype], rep)
-    log_report(f"full-shape single layer {name}", sorted(rep, key=lambda r: -r[1])[:8])
+    log_report(f"full-shape single layer {name} dtype={dtype}", sorted(rep, key=lambda r: -r[1])[:8])
 
 
 def test_attention_full_size_heads_match_oracle(gpu_device):

@@ -6,17 +6,17 @@ import torch
 import paper_2507_10392_amd as zs
 from harness import dev, log_report, rel_err
 from oracle import stage_oracle as so
-from workloads import round_bf16
+from workloads import round_bf16, round_f16
 
 pytestmark = pytest.mark.gpu
 
-TD = {0: torch.float32, 1: torch.bfloat16}
-TOL = {0: 2e-5, 1: 1e-2}        # single kernels: one rounding step, so tighter than the whole-step bar
+TD = {0: torch.float32, 1: torch.bfloat16, 2: torch.float16}
+TOL = {0: 2e-5, 1: 1e-2, 2: 1.5e-3}   # single kernels: one rounding step, so tighter than the whole-step bar
 
 
 def draw(rng, shape, dtype, scale=1.0):
     a = (rng.standard_normal(shape) * scale).astype(np.float32)
-    return round_bf16(a) if dtype == 1 else a
+    return round_bf16(a) if dtype == 1 else round_f16(a) if dtype == 2 else a
 
 
 def st():
@@ -54,7 +54,7 @@ GEMM_CASES = [
 
 
 @pytest.mark.parametrize("impl", [1, 2, 3, 4])
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 @pytest.mark.parametrize("case", GEMM_CASES, ids=lambda c: "x".join(str(int(v)) for v in c))
 def test_gemm_matches_float64_matmul(gpu_device, case, dtype, impl):
     M, N, K, ta, tb, batch, kseg, use_bias, use_res, accum = case
@@ -103,24 +103,25 @@ def test_gemm_matches_float64_matmul(gpu_device, case, dtype, impl):
     assert err <= tol
 
 
-def test_gemm_full_shape_sampled_outputs(gpu_device):
+@pytest.mark.parametrize("dtype", [1, 2])
+def test_gemm_full_shape_sampled_outputs(gpu_device, dtype):
     """The three products of the 7B-class FFN down projection at full size (T=4096, H=4096, F=11008),
     checked on 256 sampled outputs each, every one recomputed as a float64 dot product."""
     rng = np.random.default_rng(11)
     T, H, F = 4096, 4096, 11008
     g = torch.Generator(device="cuda").manual_seed(5)
-    a = torch.randn(T, F, device="cuda", generator=g).to(torch.bfloat16)
-    W = (torch.randn(F, H, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
-    dy = (torch.randn(T, H, device="cuda", generator=g) * 0.01).to(torch.bfloat16)
-    y = torch.empty(T, H, dtype=torch.bfloat16, device="cuda")
-    da = torch.empty(T, F, dtype=torch.bfloat16, device="cuda")
+    a = torch.randn(T, F, device="cuda", generator=g).to(TD[dtype])
+    W = (torch.randn(F, H, device="cuda", generator=g) * 0.02).to(TD[dtype])
+    dy = (torch.randn(T, H, device="cuda", generator=g) * 0.01).to(TD[dtype])
+    y = torch.empty(T, H, dtype=TD[dtype], device="cuda")
+    da = torch.empty(T, F, dtype=TD[dtype], device="cuda")
     dW = torch.zeros(F, H, dtype=torch.float32, device="cuda")
     print("[case] gemm full shape NN", flush=True)
-    zs.ops.gemm(st(), 1, 0, 0, T, H, F, a, F, W, H, y, H, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
+    zs.ops.gemm(st(), dtype, 0, 0, T, H, F, a, F, W, H, y, H, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
     print("[case] gemm full shape NT", flush=True)
-    zs.ops.gemm(st(), 1, 0, 1, T, F, H, dy, H, W, H, da, F, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
+    zs.ops.gemm(st(), dtype, 0, 1, T, F, H, dy, H, W, H, da, F, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
     print("[case] gemm full shape TN", flush=True)
-    zs.ops.gemm(st(), 1, 1, 0, F, H, T, a, F, dy, H, dW, H, 1, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
+    zs.ops.gemm(st(), dtype, 1, 0, F, H, T, a, F, dy, H, dW, H, 1, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0)
     torch.cuda.synchronize()
     a64, W64, dy64 = (t.float().cpu().numpy().astype(np.float64) for t in (a, W, dy))
     yh, dah, dWh = y.float().cpu().numpy(), da.float().cpu().numpy(), dW.cpu().numpy()
@@ -194,7 +195,7 @@ def test_gemm_with_operands_beyond_the_kernels_offset_range(gpu_device):
 # ----------------------------------------------------------------------------- norms
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 @pytest.mark.parametrize("kind", [0, 1])
 # (T, H, blocks of the vector-gradient partials; 0 = rows/8); H = 64 lanes x vector x {1,2,4,8,10} selects the
 # register-resident kernels
@@ -205,7 +206,7 @@ def test_norm_fwd_bwd(gpu_device, dtype, kind, T, H, nblk):
     rng = np.random.default_rng(3)
     x = draw(rng, (T, H), dtype, 2.0)
     g = draw(rng, (H,), dtype) + 1
-    g = round_bf16(g) if dtype else g
+    g = round_bf16(g) if dtype == 1 else round_f16(g) if dtype == 2 else g
     b = draw(rng, (H,), dtype)
     dn = draw(rng, (T, H), dtype)
     dres = draw(rng, (T, H), dtype)
@@ -239,7 +240,7 @@ def test_norm_fwd_bwd(gpu_device, dtype, kind, T, H, nblk):
 # ----------------------------------------------------------------------------- RoPE, activations
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_rope_and_inverse(gpu_device, dtype):
     print(f"[case] rope dtype={dtype}", flush=True)
     rng = np.random.default_rng(4)
@@ -258,7 +259,7 @@ def test_rope_and_inverse(gpu_device, dtype):
         assert rel_err(back(a), u) <= 2e-6
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_gelu_and_swiglu(gpu_device, dtype):
     print(f"[case] activations dtype={dtype}", flush=True)
     rng = np.random.default_rng(5)
@@ -288,7 +289,7 @@ ATTN_CASES = [(2, 128, 4, 64), (1, 256, 4, 128), (2, 200, 3, 128), (1, 1, 2, 128
 
 
 @pytest.mark.parametrize("impl", [1, 2])
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 @pytest.mark.parametrize("mb,S,nh,d", ATTN_CASES)
 def test_attention_fwd_bwd(gpu_device, mb, S, nh, d, dtype, impl):
     if impl == 2 and (dtype == 0 or d != 128):
@@ -332,7 +333,7 @@ def test_attention_fwd_bwd(gpu_device, mb, S, nh, d, dtype, impl):
 
 
 @pytest.mark.parametrize("impl", [0, 1, 2, 3, 4])
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 @pytest.mark.parametrize("shape", [(296, 520, 128, 72, 2), (256, 256, 64, 64, 1), (1000, 40, 1024, 200, 1), (304, 264, 100, 64, 1)])
 def test_weight_gradient_of_two_microbatches(gpu_device, dtype, impl, shape):
     """C += A1^T B1 + A2^T B2 in one product over both parts' rows, against float64."""
@@ -356,7 +357,7 @@ def test_weight_gradient_of_two_microbatches(gpu_device, dtype, impl, shape):
 
 
 @pytest.mark.parametrize("impl", [1, 2, 3, 4])
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_gemm_with_fused_rotation(gpu_device, dtype, impl):
     """Q|K|V projection as a batch of three products whose first two results are rotated in the store:
     against float64 matmul followed by the oracle's rotation; V must be the plain product."""
@@ -386,7 +387,7 @@ def test_gemm_with_fused_rotation(gpu_device, dtype, impl):
 
 
 @pytest.mark.parametrize("impl", [1, 2])
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_attention_bwd_with_fused_inverse_rotation(gpu_device, dtype, impl):
     """dq and dk leave the backward kernels rotated back: against the oracle's gradients, rotated by
     the oracle with sign -1; dv is unchanged."""
@@ -425,7 +426,7 @@ def test_attention_bwd_with_fused_inverse_rotation(gpu_device, dtype, impl):
 # ----------------------------------------------------------------------------- embedding, cross entropy, AdamW
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_embedding_is_bit_exact_and_scatter_matches(gpu_device, dtype):
     print(f"[case] embedding dtype={dtype}", flush=True)
     rng = np.random.default_rng(7)
@@ -445,7 +446,7 @@ def test_embedding_is_bit_exact_and_scatter_matches(gpu_device, dtype):
     assert rel_err(back(dE), want) <= 2e-6
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_cross_entropy(gpu_device, dtype):
     print(f"[case] cross entropy dtype={dtype}", flush=True)
     rng = np.random.default_rng(8)
@@ -469,7 +470,7 @@ def test_cross_entropy(gpu_device, dtype):
     assert rel_err(back(zd), want * scale) <= (4e-3 if dtype else 1e-5)
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 @pytest.mark.parametrize("n,begin", [(1 << 16, 0), (100003, 8), (1001, 5), (3, 0), (0, 0)])
 def test_adamw_kernel_matches_oracle_for_t_1_2_10(gpu_device, dtype, n, begin):
     print(f"[case] adamw dtype={dtype} n={n} begin={begin}", flush=True)
@@ -479,7 +480,8 @@ def test_adamw_kernel_matches_oracle_for_t_1_2_10(gpu_device, dtype, n, begin):
     P = begin + n + 13
     p0 = (rng.standard_normal(P) * 0.02).astype(np.float32)
     master = dev(p0[begin:begin + n]) if dtype else None
-    params = dev(round_bf16(p0), torch.bfloat16) if dtype else dev(p0)
+    rnd = round_bf16 if dtype == 1 else round_f16
+    params = dev(rnd(p0), TD[dtype]) if dtype else dev(p0)
     m = torch.zeros(max(n, 1), device="cuda")
     v = torch.zeros(max(n, 1), device="cuda")
     po, mo, vo = p0[begin:begin + n].astype(np.float64), np.zeros(n), np.zeros(n)
@@ -500,8 +502,8 @@ def test_adamw_kernel_matches_oracle_for_t_1_2_10(gpu_device, dtype, n, begin):
         assert not gz[begin:begin + n].any() and np.array_equal(gz[:begin], g[:begin].astype(np.float64))
         assert np.array_equal(gz[begin + n:], g[begin + n:].astype(np.float64))
         if dtype:
-            want = master.to(torch.bfloat16).cpu()
+            want = master.to(TD[dtype]).cpu()
             assert torch.equal(want.view(torch.int16), params[begin:begin + n].cpu().view(torch.int16))
-            assert np.array_equal(back(params)[:begin], round_bf16(p0)[:begin].astype(np.float64))
+            assert np.array_equal(back(params)[:begin], rnd(p0)[:begin].astype(np.float64))
         po = got_p.copy()      # continue from the GPU's fp32 state so that only one step's rounding is compared
         mo, vo = back(m)[:n].copy(), back(v)[:n].copy()
