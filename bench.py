@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # tokens per launch), from the same counters over one step of this file
 # (profiles/stage_step_C3_mfma_busy_hbm_bytes.txt).  Keys: workload, kernel class, pair_wgrad.  Workloads that
 # were not measured report null.
-MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 1): 1781.2e6}
+MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 1): 1781.2e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6}
 
 
 def model_flops_per_step(cfg):
@@ -237,7 +237,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket launches with HIP events")
     ap.add_argument("--no-pair-wgrad", action="store_true",
-                    help="do not fold every other backward's weight-gradient products into the next one's (stage_config.pair_wgrad = 0)")
+                    help="every backward runs its own weight-gradient products (stage_config.pair_wgrad = 0)")
+    ap.add_argument("--wgrad-group", type=int, default=8, metavar="G",
+                    help="microbatches whose weight-gradient products share one K loop (stage_config.pair_wgrad = G, "
+                         "at most 16 and at most the number of microbatches)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the microbatch loop of a step in a HIP graph and replay it (for launch-bound stages); "
                          "per-kernel events are off in this mode")
@@ -267,7 +270,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    cfg = get_config(args.workload).with_(pair_wgrad=0 if args.no_pair_wgrad else 1)
+    cfg = get_config(args.workload).with_(pair_wgrad=0 if args.no_pair_wgrad else max(args.wgrad_group, 1))
     if args.recompute or args.offload:
         cfg = cfg.with_(recompute=1, offload_acts=1 if args.offload else 0)
     loss_scale = 1.0

@@ -75,11 +75,14 @@ typedef struct {
   int32_t has_embed;         /* 1: stage input is int32 token ids, x = E[ids] */
   int32_t has_head;          /* 1: final RMSNorm, LM head and mean cross entropy close the stage */
   int32_t recompute;         /* 0 keep every intermediate; 1 keep layer inputs only and recompute (Section 4.1.3) */
-  int32_t pair_wgrad;        /* 1: the weight-gradient products of every other backward are deferred and folded into
-                                the next backward's (one product over the tokens of both microbatches, half as many
-                                read-add-write passes over grad_acc).  grad_acc then holds the complete sum once no
-                                forwarded microbatch is outstanding, not after every stage_accumulate.  Ignored with
-                                recompute, with max_microbatches < 2 and when seq*microbatch is no multiple of 64. */
+  int32_t pair_wgrad;        /* g >= 2: the weight-gradient products of a group of g microbatches (at most 16, at most
+                                max_microbatches; 1 means 2) run as ONE product per weight over the tokens of all of them:
+                                every backward but the one that completes a group (or the last outstanding one) only
+                                keeps its operands, and grad_acc is read, added to and written once per group instead
+                                of once per microbatch.  grad_acc then holds the complete sum once no forwarded
+                                microbatch is outstanding, not after every stage_accumulate.  Costs (g-1) * layers * 5
+                                activation-sized buffers of scratch.  Ignored with recompute, with max_microbatches < 2
+                                and when seq*microbatch is no multiple of 128. */
   int64_t act_budget_bytes;  /* 0 = unlimited; otherwise stage_query/stage_init fail with STAGE_ERR_BUDGET
                                 when the activation term exceeds it */
   int64_t shard_begin, shard_end; /* [begin, end) in flat parameter index space: the optimizer's range */

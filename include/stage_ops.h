@@ -41,10 +41,17 @@ int stage_op_gemm_rope(void* stream, int32_t dtype, int32_t transA, int32_t tran
 /* Weight gradients of two microbatches in one product: C[M,N] (float) += A1^T B1 + A2^T B2 with A1 stored
  * [K1,M], A2 [K2,M] (row stride lda), B1 [K1,N], B2 [K2,N] (row stride ldb); batch >= 1 with element strides
  * sA, sB (applied to both parts) and sC.  impl as for stage_op_gemm; the MFMA kernel needs K1 to be a multiple
- * of 64 (STAGE_ERR_ARG otherwise when it is forced), impl 0 falls back to two plain products. */
+ * of 128 (STAGE_ERR_ARG otherwise when it is forced), impl 0 falls back to one product per part. */
 int stage_op_wgrad_pair(void* stream, int32_t dtype, int32_t M, int32_t N, int32_t K1, int32_t K2, const void* A1,
                         const void* A2, int64_t lda, const void* B1, const void* B2, int64_t ldb, float* C, int64_t ldc,
                         int32_t batch, int64_t sA, int64_t sB, int64_t sC, int32_t impl);
+
+/* The same for up to 16 microbatches: C += sum_p A_p^T B_p over nparts parts, A_parts / B_parts being HOST arrays
+ * of nparts device pointers; parts 0..nparts-2 have K_each rows, the last one K_last rows.  The MFMA kernel needs
+ * K_each to be a multiple of 128 (when there is more than one part). */
+int stage_op_wgrad_parts(void* stream, int32_t dtype, int32_t M, int32_t N, int32_t K_each, int32_t K_last, int32_t nparts,
+                         const void* const* A_parts, int64_t lda, const void* const* B_parts, int64_t ldb, float* C,
+                         int64_t ldc, int32_t batch, int64_t sA, int64_t sB, int64_t sC, int32_t impl);
 
 /* kind 0: LayerNorm n = (x-mean)/sqrt(var+eps)*g + b (biased variance), saves rstd[T], mean[T].
  * kind 1: RMSNorm n = x/sqrt(mean(x^2)+eps)*g, saves rstd[T].  x, n: [T,H]. */

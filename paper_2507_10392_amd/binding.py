@@ -110,6 +110,8 @@ def lib():
         L.stage_op_gemm_rope.argtypes = L.stage_op_gemm.argtypes + [vp, i32, i32, i32]
         L.stage_op_rope_table.argtypes = [vp, i32, i32, f32, vp]
         L.stage_op_wgrad_pair.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, vp, i64, vp, i64, i32, i64, i64, i64, i32]
+        L.stage_op_wgrad_parts.argtypes = [vp, i32, i32, i32, i32, i32, i32, C.POINTER(vp), i64, C.POINTER(vp), i64, vp, i64, i32,
+                                           i64, i64, i64, i32]
         L.stage_op_norm_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, f32, vp, vp, vp]
         L.stage_op_norm_bwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32]
         L.stage_op_rope.argtypes = [vp, i32, i32, i32, i32, i32, vp, i64, f32, f32, vp]
@@ -323,3 +325,13 @@ class _Ops:
 
 
 ops = _Ops()
+
+
+def wgrad_parts(stream, dtype, M, N, K_each, K_last, A_parts, lda, B_parts, ldb, Cbuf, ldc, batch=1, sA=0, sB=0, sC=0, impl=0):
+    """stage_op_wgrad_parts with lists of device tensors for the parts."""
+    n = len(A_parts)
+    pa = (C.c_void_p * n)(*[t.data_ptr() for t in A_parts])
+    pb = (C.c_void_p * n)(*[t.data_ptr() for t in B_parts])
+    code = lib().stage_op_wgrad_parts(stream, dtype, M, N, K_each, K_last, n, pa, lda, pb, ldb, _ptr(Cbuf), ldc, batch, sA, sB, sC, impl)
+    if code != STAGE_OK:
+        raise StageError(code, "stage_op_wgrad_parts")

@@ -25,9 +25,12 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
   if (g.K % 8) return false;                       // k-contiguous operands are read 8 k at a time; tails are zero-filled
   if (g.transA && g.M % 8) return false;           // row-contiguous operands are read 8 rows at a time
   if (!g.transB && g.N % 8) return false;
-  if (g.A2) {   // two-part K range of an accumulating product
-    if (!g.transA || g.transB || !g.c_f32_accum || !g.B2 || g.kseg <= 0 || g.kseg >= g.K || g.kseg % 64) return false;
-    if (!aligned16(g.A2) || !aligned16(g.B2)) return false;
+  if (g.nx) {   // multi-part K range of an accumulating product
+    if (g.nx < 0 || g.nx >= GEMM_MAX_PARTS) return false;
+    // the K loop takes two slabs of 64 rows per step, and a step must lie inside one part
+    if (!g.transA || g.transB || !g.c_f32_accum || g.kseg <= 0 || g.kseg % 128 || (int64_t)g.kseg * g.nx >= g.K) return false;
+    for (int p = 0; p < g.nx; ++p)
+      if (!g.Ax[p] || !g.Bx[p] || !aligned16(g.Ax[p]) || !aligned16(g.Bx[p])) return false;
   } else if (g.kseg) {
     if (!g.transB || g.kseg % 8 || g.segB % 8 || g.K % g.kseg) return false;
   }
@@ -46,9 +49,12 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
     if (((int64_t)g.M + 256) * g.ldc * 4 >= (1ll << 31)) return false;
   }
   // byte offsets inside one operand are 32-bit in the kernel
-  const int64_t extA = (g.transA ? (int64_t)g.K * g.lda : (int64_t)g.M * g.lda) * 2;
+  // every part of a multi-part range has a descriptor of its own; the last part may be the longest
+  const int64_t rowsA = g.nx ? ((int64_t)g.K - (int64_t)g.nx * g.kseg > g.kseg ? (int64_t)g.K - (int64_t)g.nx * g.kseg : g.kseg) : g.K;
+  const int64_t extA = (g.transA ? rowsA * g.lda : (int64_t)g.M * g.lda) * 2;
   const int64_t nseg = g.kseg ? g.K / g.kseg : 1;
-  const int64_t extB = (g.transB ? (nseg - 1) * g.segB + (int64_t)g.N * g.ldb : (int64_t)g.K * g.ldb) * 2;
+  const int64_t nsegB = g.nx ? 1 : nseg;
+  const int64_t extB = (g.transB ? (nsegB - 1) * g.segB + (int64_t)g.N * g.ldb : rowsA * g.ldb) * 2;
   if (extA >= (1ll << 30) || extB >= (1ll << 30)) return false;
   return true;
 }

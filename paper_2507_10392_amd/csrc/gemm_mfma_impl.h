@@ -299,30 +299,33 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   Frag<BM, NT> fa0, fa1;
   Frag<BN, NT> fb0, fb1;
   const int lda = (int)g.lda, ldb = (int)g.ldb;
-  // PAIR: K rows [0, kseg) come from A, B and rows [kseg, K) from A2, B2 (both operands row-contiguous)
+  // PAIR: the K range is made of g.nx+1 parts of kseg rows, each with operands of its own (both row-contiguous)
   constexpr bool PAIR = SEG && TA == 1 && TB == 0;
-  const int K1 = PAIR ? g.kseg : g.K;                    // rows of the first (or only) part
+  const int K1 = PAIR ? g.kseg : g.K;                    // rows of a part (or of the only one)
   const __amdgpu_buffer_rsrc_t rsA =
       make_rsrc(A, (uint32_t)(TA == 0 ? ((int64_t)(g.M - 1) * lda + g.K) : ((int64_t)(K1 - 1) * lda + g.M)) * 2u);
   const int nseg = (SEG && !PAIR) ? g.K / g.kseg : 1;
   const __amdgpu_buffer_rsrc_t rsB = make_rsrc(
       B, (uint32_t)(TB == 1 ? ((int64_t)(nseg - 1) * g.segB + (int64_t)(g.N - 1) * ldb + (SEG ? g.kseg : g.K))
                             : ((int64_t)(K1 - 1) * ldb + g.N)) * 2u);
-  const __amdgpu_buffer_rsrc_t rsA2 =
-      PAIR ? make_rsrc((const bf16*)g.A2 + (int64_t)z * g.sA, (uint32_t)((int64_t)(g.K - K1 - 1) * lda + g.M) * 2u) : rsA;
-  const __amdgpu_buffer_rsrc_t rsB2 =
-      PAIR ? make_rsrc((const bf16*)g.B2 + (int64_t)z * g.sB, (uint32_t)((int64_t)(g.K - K1 - 1) * ldb + g.N) * 2u) : rsB;
+  // Descriptors of part p >= 1 (the last part has the rows that remain); a part past the last one gets an empty
+  // range, so a surplus slab reads zeros.
+  auto part_a = [&](int p) {
+    const int rows = p < g.nx ? K1 : g.K - g.nx * K1;
+    return p <= g.nx ? make_rsrc((const bf16*)g.Ax[p - 1] + (int64_t)z * g.sA, (uint32_t)((int64_t)(rows - 1) * lda + g.M) * 2u)
+                     : make_rsrc(A, 0u);
+  };
+  auto part_b = [&](int p) {
+    const int rows = p < g.nx ? K1 : g.K - g.nx * K1;
+    return p <= g.nx ? make_rsrc((const bf16*)g.Bx[p - 1] + (int64_t)z * g.sB, (uint32_t)((int64_t)(rows - 1) * ldb + g.N) * 2u)
+                     : make_rsrc(B, 0u);
+  };
+  __amdgpu_buffer_rsrc_t curA = rsA, curB = rsB;         // PAIR: descriptors of the part whose slabs are being loaded
   const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : voff_rmajor<BM>(lda, tid, m0, g.M);
   const int voffB = TB == 1 ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2 : voff_rmajor<BN>(ldb, tid, n0, g.N);
 
   auto fetch = [&](int kt, Frag<BM, NT>& fa0, Frag<BN, NT>& fb0) {
     const int k0 = kt * BK;
-    if (PAIR) {   // a slab lies in one part (kseg is a multiple of the slab); rows past a part's end are out of its range
-      const bool second = k0 >= K1;
-      load_rmajor<BM, NT>(fa0, second ? rsA2 : rsA, voffA, lda, m0, second ? k0 - K1 : k0);
-      load_rmajor<BN, NT>(fb0, second ? rsB2 : rsB, voffB, ldb, n0, second ? k0 - K1 : k0);
-      return;
-    }
     if (TA == 0) load_kmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0, g.K, tid);
     else load_rmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0);
     if (TB == 1) {
@@ -372,18 +375,49 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 
   // Slabs past K read zeros (their loads are out of range), so the loop needs no conditions: it walks K in
   // pairs of slabs and a surplus slab contributes nothing.
-  fetch(0, fa0, fb0);
-  stash_a(0, fa0);
-  stash_b(0, fb0);
-  fetch(1, fa1, fb1);
-  __syncthreads();
-  for (int kt = 0; kt < nk; kt += 2) {
-    fetch(kt + 2, fa0, fb0);
-    multiply(0, fa1, fb1);
+  if (PAIR) {
+    // The same pipeline over a K range made of parts: the loads run one pair of slabs ahead of the products, a
+    // pair lies inside one part (kseg is a multiple of two slabs), and the descriptors change between the inner
+    // loops, so the inner loop is that of the single-range kernel.  After the last part comes an empty one whose
+    // single pair of loads returns zeros while the last real pair is multiplied.
+    auto fetch_part = [&](int kin, Frag<BM, NT>& fa, Frag<BN, NT>& fb) {
+      load_rmajor<BM, NT>(fa, curA, voffA, lda, m0, kin);
+      load_rmajor<BN, NT>(fb, curB, voffB, ldb, n0, kin);
+    };
+    const int full = K1 / (2 * BK);                                    // slab pairs of a part of kseg rows
+    const int tail = (g.K - g.nx * K1 + 2 * BK - 1) / (2 * BK);        // of the last part (rows past its end read as zero)
+    fetch_part(0, fa0, fb0);
+    stash_a(0, fa0);
+    stash_b(0, fb0);
+    fetch_part(BK, fa1, fb1);
     __syncthreads();
-    fetch(kt + 3, fa1, fb1);
-    multiply(1, fa0, fb0);
+    for (int p = 0; p <= g.nx + 1; ++p) {
+      const int pairs = p < g.nx ? full : p == g.nx ? tail : 1;
+      for (int j = p == 0 ? 1 : 0; j < pairs; ++j) {
+        fetch_part(j * 2 * BK, fa0, fb0);
+        multiply(0, fa1, fb1);
+        __syncthreads();
+        fetch_part(j * 2 * BK + BK, fa1, fb1);
+        multiply(1, fa0, fb0);
+        __syncthreads();
+      }
+      curA = part_a(p + 1);
+      curB = part_b(p + 1);
+    }
+  } else {
+    fetch(0, fa0, fb0);
+    stash_a(0, fa0);
+    stash_b(0, fb0);
+    fetch(1, fa1, fb1);
     __syncthreads();
+    for (int kt = 0; kt < nk; kt += 2) {
+      fetch(kt + 2, fa0, fb0);
+      multiply(0, fa1, fb1);
+      __syncthreads();
+      fetch(kt + 3, fa1, fb1);
+      multiply(1, fa0, fb0);
+      __syncthreads();
+    }
   }
 
   if (ACC) epilogue_accum<BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
@@ -410,7 +444,7 @@ template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG> hipError_
 }
 
 template <typename E, int BM, int BN, int NW> hipError_t gemm_mfma_tile(hipStream_t st, const Gemm& g) {
-  if (g.A2) return launch<E, BM, BN, NW, 1, 0, 1>(st, g);
+  if (g.nx) return launch<E, BM, BN, NW, 1, 0, 1>(st, g);
   if (g.kseg) return g.transA ? launch<E, BM, BN, NW, 1, 1, 1>(st, g) : launch<E, BM, BN, NW, 0, 1, 1>(st, g);
   if (!g.transA && !g.transB) return launch<E, BM, BN, NW, 0, 0, 0>(st, g);
   if (!g.transA && g.transB) return launch<E, BM, BN, NW, 0, 1, 0>(st, g);

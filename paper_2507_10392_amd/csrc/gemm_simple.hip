@@ -111,16 +111,24 @@ int gemm_select(DType dt, const Gemm& g, int force) {
 
 namespace {
 
+// Part p of a multi-part K range as a product of its own.
+Gemm part_of(const Gemm& g, int p) {
+  Gemm a = g;
+  a.nx = 0; a.K = p < g.nx ? g.kseg : g.K - g.nx * g.kseg; a.kseg = 0;
+  if (p > 0) { a.A = g.Ax[p - 1]; a.B = g.Bx[p - 1]; }
+  return a;
+}
+
 // One launch: the MFMA kernel when it takes the arguments, else the plain kernel (with the rotation and the
 // two-part K range done in extra passes).
 hipError_t gemm_one(hipStream_t st, DType dt, const Gemm& g, int force) {
   if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, dt, g);   // rotation fused into its epilogue
-  if (g.A2) {   // two-part K range: one plain product per part
-    Gemm a = g, b = g;
-    a.A2 = a.B2 = nullptr; a.K = g.kseg; a.kseg = 0;
-    b.A = g.A2; b.B = g.B2; b.A2 = b.B2 = nullptr; b.K = g.K - g.kseg; b.kseg = 0;
-    const hipError_t e2 = gemm_simple(st, dt, a);
-    return e2 != hipSuccess ? e2 : gemm_simple(st, dt, b);
+  if (g.nx) {   // multi-part K range: one plain product per part
+    for (int p = 0; p <= g.nx; ++p) {
+      const hipError_t e = gemm_simple(st, dt, part_of(g, p));
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
   }
   hipError_t e = gemm_simple(st, dt, g);
   const int elem = dt == F32 ? 4 : 2;
@@ -139,7 +147,7 @@ hipError_t gemm_one(hipStream_t st, DType dt, const Gemm& g, int force) {
 constexpr int64_t OPERAND_LIMIT = 1ll << 30;
 
 bool split_rows(const Gemm& g, std::vector<Gemm>& parts) {
-  if (g.transA || g.A2 || g.lda <= 0) return false;
+  if (g.transA || g.nx || g.lda <= 0) return false;
   if ((int64_t)g.M * g.lda * 2 < OPERAND_LIMIT) return false;
   int64_t unit = 256;
   if (g.rope) {   // least common multiple of the tile height and the sequence length
@@ -161,7 +169,7 @@ bool split_rows(const Gemm& g, std::vector<Gemm>& parts) {
 }
 
 bool split_k(const Gemm& g, std::vector<Gemm>& parts) {
-  if (!g.transA || g.transB || !g.c_f32_accum || g.kseg || g.A2 || g.lda <= 0 || g.ldb <= 0) return false;
+  if (!g.transA || g.transB || !g.c_f32_accum || g.kseg || g.nx || g.lda <= 0 || g.ldb <= 0) return false;
   const int64_t ld = g.lda > g.ldb ? g.lda : g.ldb;
   if ((int64_t)g.K * ld * 2 < OPERAND_LIMIT) return false;
   const int64_t kc = (OPERAND_LIMIT - 1) / (ld * 2) / 64 * 64;
@@ -190,12 +198,12 @@ bool gemm_splits(DType dt, const Gemm& g) {
 hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
   if (dt != F32 && force != GEMM_SIMPLE && !gemm_mfma_supported(dt, g)) {
     std::vector<Gemm> parts;
-    if (g.A2) {   // the two parts of a paired weight gradient on their own, each cut further if it has to be
-      Gemm a = g, b = g;
-      a.A2 = a.B2 = nullptr; a.K = g.kseg; a.kseg = 0;
-      b.A = g.A2; b.B = g.B2; b.A2 = b.B2 = nullptr; b.K = g.K - g.kseg; b.kseg = 0;
-      const hipError_t e = gemm(st, dt, a, force);
-      return e != hipSuccess ? e : gemm(st, dt, b, force);
+    if (g.nx) {   // the parts of a multi-part weight gradient on their own, each cut further if it has to be
+      for (int p = 0; p <= g.nx; ++p) {
+        const hipError_t e = gemm(st, dt, part_of(g, p), force);
+        if (e != hipSuccess) return e;
+      }
+      return hipSuccess;
     }
     if (split_rows(g, parts) || split_k(g, parts)) {
       for (const Gemm& p : parts) {

@@ -13,12 +13,14 @@ namespace zs {
 //   batch > 1: operand z uses A + z*sA, B + z*sB, C + z*sC, bias + z*sBias, R + z*sC.
 //   kseg > 0: the K range is cut in segments of kseg; segment s reads B from B + s*segB
 //             (dgrad through several weight matrices stored one after another).
-//   A2 != NULL (transA = 1, transB = 0, c_f32_accum = 1 only): the K range consists of two parts with operands of
-//             their own, rows [0, kseg) from A, B and rows [kseg, K) from A2, B2 (same leading dimensions and
-//             batch strides): C += A^T B + A2^T B2 in one K loop (weight gradients of two microbatches).
+//   nx > 0 (transA = 1, transB = 0, c_f32_accum = 1 only): the K range consists of nx+1 parts with operands of
+//             their own, part 0 from A, B and part p from Ax[p-1], Bx[p-1] (same leading dimensions and batch
+//             strides); parts 0..nx-1 have kseg rows each, the last one the remaining K - nx*kseg > 0 rows:
+//             C += sum_p A_p^T B_p in one K loop (weight gradients of several microbatches).
 //   rope != NULL (c_f32_accum = 0 only): for batch indices z < rope_batches the adjacent column pairs of
 //             every head (rope_d columns wide) of C are rotated, after bias and residual and before the
 //             result is rounded, by the angle table[(row % rope_S) * rope_d/2 + pair] (cos, sin).
+constexpr int GEMM_MAX_PARTS = 16;   // parts of a multi-part K range
 struct Gemm {
   int M = 0, N = 0, K = 0, transA = 0, transB = 0;
   const void* A = nullptr; int64_t lda = 0;
@@ -29,7 +31,7 @@ struct Gemm {
   const void* resid = nullptr; int64_t ldr = 0;
   int batch = 1; int64_t sA = 0, sB = 0, sC = 0, sBias = 0;
   int kseg = 0; int64_t segB = 0;
-  const void* A2 = nullptr; const void* B2 = nullptr;
+  int nx = 0; const void* Ax[GEMM_MAX_PARTS - 1] = {}; const void* Bx[GEMM_MAX_PARTS - 1] = {};
   const float2* rope = nullptr; int rope_S = 0, rope_d = 0, rope_batches = 0;
 };
 enum GemmImpl { GEMM_AUTO = 0, GEMM_SIMPLE = 1, GEMM_MFMA = 2 };

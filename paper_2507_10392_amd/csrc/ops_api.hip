@@ -47,7 +47,29 @@ int stage_op_wgrad_pair(void* stream, int32_t dtype, int32_t M, int32_t N, int32
   Gemm g;
   g.M = M; g.N = N; g.K = K1 + K2; g.transA = 1; g.transB = 0; g.A = A1; g.lda = lda; g.B = B1; g.ldb = ldb;
   g.C = C; g.ldc = ldc; g.c_f32_accum = 1; g.batch = batch; g.sA = sA; g.sB = sB; g.sC = sC;
-  g.A2 = A2; g.B2 = B2; g.kseg = K1;
+  g.nx = 1; g.Ax[0] = A2; g.Bx[0] = B2; g.kseg = K1;
+  if (impl >= GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
+  if (impl > GEMM_MFMA) gemm_mfma_force_tile(impl - GEMM_MFMA);
+  const hipError_t e = gemm((hipStream_t)stream, (DType)dtype, g, impl > GEMM_MFMA ? GEMM_MFMA : impl);
+  gemm_mfma_force_tile(0);
+  return rc(e);
+}
+
+int stage_op_wgrad_parts(void* stream, int32_t dtype, int32_t M, int32_t N, int32_t K_each, int32_t K_last, int32_t nparts,
+                         const void* const* A_parts, int64_t lda, const void* const* B_parts, int64_t ldb, float* C, int64_t ldc,
+                         int32_t batch, int64_t sA, int64_t sB, int64_t sC, int32_t impl) {
+  if (!dt_ok(dtype) || M < 1 || N < 1 || K_each < 1 || K_last < 1 || nparts < 1 || nparts > GEMM_MAX_PARTS || batch < 1 ||
+      !A_parts || !B_parts || !C)
+    return STAGE_ERR_ARG;
+  if (impl < 0 || impl > 4) return STAGE_ERR_ARG;
+  for (int p = 0; p < nparts; ++p)
+    if (!A_parts[p] || !B_parts[p]) return STAGE_ERR_ARG;
+  Gemm g;
+  g.M = M; g.N = N; g.K = K_each * (nparts - 1) + K_last; g.transA = 1; g.transB = 0; g.A = A_parts[0]; g.lda = lda;
+  g.B = B_parts[0]; g.ldb = ldb; g.C = C; g.ldc = ldc; g.c_f32_accum = 1; g.batch = batch; g.sA = sA; g.sB = sB; g.sC = sC;
+  g.nx = nparts - 1;
+  if (g.nx) g.kseg = K_each;
+  for (int p = 1; p < nparts; ++p) { g.Ax[p - 1] = A_parts[p]; g.Bx[p - 1] = B_parts[p]; }
   if (impl >= GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
   if (impl > GEMM_MFMA) gemm_mfma_force_tile(impl - GEMM_MFMA);
   const hipError_t e = gemm((hipStream_t)stream, (DType)dtype, g, impl > GEMM_MFMA ? GEMM_MFMA : impl);

@@ -23,6 +23,7 @@ struct Seg { std::string name; int64_t off, rows, cols; };
 struct Shape {
   int arch, L, H, nh, d, F, S, mb, T, M, V, dtype;
   bool bf /* 16-bit elements (bf16 or fp16) with an fp32 master copy */, embed, head, recompute, pair, offload;
+  int group;   // pair: microbatches whose weight-gradient products share one K loop (2..GEMM_MAX_PARTS)
   int64_t E;  // bytes per element
 };
 
@@ -35,7 +36,10 @@ Shape shape_of(const stage_config& c) {
   s.offload = c.offload_acts != 0;
   // weight gradients of two microbatches in one product: needs the first one's activations to stay (no
   // recompute), a second microbatch to pair with, and the part boundary on a K slab of the MFMA kernel
-  s.pair = c.pair_wgrad != 0 && !s.recompute && s.M >= 2 && s.T % 64 == 0;
+  s.pair = c.pair_wgrad != 0 && !s.recompute && s.M >= 2 && s.T % 128 == 0;
+  s.group = c.pair_wgrad < 2 ? 2 : c.pair_wgrad;
+  if (s.group > GEMM_MAX_PARTS) s.group = GEMM_MAX_PARTS;
+  if (s.group > s.M) s.group = s.M;
   return s;
 }
 
@@ -89,6 +93,7 @@ int validate(const stage_config* c, std::string& err) {
   if (c->recompute != 0 && c->recompute != 1) return bad("recompute must be 0 or 1");
   if (c->offload_acts != 0 && c->offload_acts != 1) return bad("offload_acts must be 0 or 1");
   if (c->offload_acts && !c->recompute) return bad("offload_acts needs recompute = 1 (only layer-boundary activations are offloaded)");
+  if (c->pair_wgrad < 0) return bad("pair_wgrad must be >= 0");
   if (c->act_budget_bytes < 0) return bad("act_budget_bytes must be >= 0");
   const int64_t P = count_params(*c);
   if (c->shard_begin < 0 || c->shard_end < c->shard_begin || c->shard_end > P) return bad("shard range outside [0, n_params]");
@@ -130,7 +135,7 @@ struct Plan {
   std::vector<int32_t*> ids, targets;  // per slot copies
   // scratch
   char *gA, *gB, *gN, *gO, *gQKV, *gF1, *ytmp;
-  std::vector<char*> kdy, kdx2, kdqkv;   // pair_wgrad: per layer, the deferred microbatch's dy, dx2 and dqkv
+  std::vector<char*> kdy, kdx2, kdqkv;   // pair_wgrad: per deferred microbatch and layer (index set*L + l), its dy, dx2 and dqkv
   float* delta; float* lossdump;
   float2* rope;
   float* partials; int64_t partial_floats;
@@ -218,8 +223,9 @@ void make_plan(const stage_config& c, char* base, Plan& p) {
   p.gF1 = b.take((int64_t)s.T * s.F * s.E);
   p.ytmp = b.take(TH);
   if (s.pair) {
-    p.kdy.resize(s.L); p.kdx2.resize(s.L); p.kdqkv.resize(s.L);
-    for (int l = 0; l < s.L; ++l) { p.kdy[l] = b.take(TH); p.kdx2[l] = b.take(TH); p.kdqkv[l] = b.take(3 * TH); }
+    const size_t n = (size_t)(s.group - 1) * s.L;
+    p.kdy.resize(n); p.kdx2.resize(n); p.kdqkv.resize(n);
+    for (size_t i = 0; i < n; ++i) { p.kdy[i] = b.take(TH); p.kdx2[i] = b.take(TH); p.kdqkv[i] = b.take(3 * TH); }
   }
   p.delta = b.take<float>(4ll * s.mb * s.nh * s.S);
   p.lossdump = b.take<float>(256);
@@ -260,7 +266,7 @@ struct stage {
   std::vector<int> slot;     // 0 empty, 1 forwarded, 2 backward done (waiting for accumulate)
   int pending = -1;          // slot whose backward waits for stage_accumulate
   int outstanding = 0, accumulated = 0;
-  int deferred = -1;         // pair_wgrad: slot whose weight-gradient products wait for the next backward
+  std::vector<int> deferred; // pair_wgrad: slots whose weight-gradient products wait for a later backward (set i = deferred[i])
   int* overflow = nullptr;   // device flag of loss-scaled training (stage_set_overflow_flag), or NULL
   std::vector<ReduceJob> jobs_host;
   int njobs = 0, max_job_width = 0;
@@ -471,9 +477,10 @@ bool colsum(stage_t* s, const std::string& seg, int N, const void* a, int64_t ld
 // Weight-gradient products of a layer: done now (mode 0), left for later (1: this microbatch's operands
 // stay where they are), or done for this microbatch and a deferred one in one product (2).
 struct WgradPlan {
-  int mode = 0;
-  const LayerActs* A2 = nullptr;                          // mode 2: the deferred microbatch's activations ...
-  const char *dy2 = nullptr, *dx2_2 = nullptr, *dqkv2 = nullptr;   // ... and its dy, dx2, dqkv of this layer
+  int mode = 0;                                           // 0 plain, 1 leave the products to a later backward, 2 multiply for nx more
+  int nx = 0;
+  const LayerActs* Ax[GEMM_MAX_PARTS - 1] = {};           // mode 2: the deferred microbatches' activations of this layer ...
+  const char *dy_x[GEMM_MAX_PARTS - 1] = {}, *dx2_x[GEMM_MAX_PARTS - 1] = {}, *dqkv_x[GEMM_MAX_PARTS - 1] = {};   // ... and their dy, dx2, dqkv
 };
 
 bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const char* dy, char* tmp, char* dx, char* gqkv,
@@ -488,10 +495,14 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   auto W = [&](const char* n) { return s->P(s->seg_off(p + n)); };
   auto GW = [&](const char* n) { return s->G(s->seg_off(p + n)); };
   Gemm g;
-  // dW += X^T dY over this microbatch's tokens, and over the deferred microbatch's too when there is one
-  auto wgrad = [&](Gemm w, const void* x2, const void* dy2) {
+  // dW += X^T dY over this microbatch's tokens, and over the deferred microbatches' too when there are any:
+  // xsel picks the activation of a deferred microbatch, dsel its gradient operand
+  auto wgrad = [&](Gemm w, char* LayerActs::*xsel, auto dsel) {
     if (wg.mode == 1) return true;
-    if (wg.mode == 2) { w.A2 = x2; w.B2 = dy2; w.kseg = T; w.K = 2 * T; }
+    if (wg.mode == 2) {
+      w.nx = wg.nx; w.kseg = T; w.K = (wg.nx + 1) * T;
+      for (int i = 0; i < wg.nx; ++i) { w.Ax[i] = wg.Ax[i]->*xsel; w.Bx[i] = dsel(i); }
+    }
     return do_gemm(s, w);
   };
 
@@ -502,7 +513,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   g = Gemm();
   g.M = F; g.N = H; g.K = T; g.A = A.a; g.lda = F; g.transA = 1; g.B = dy; g.ldb = H;
   g.C = gpt ? GW("W2") : GW("Wd"); g.ldc = H; g.c_f32_accum = 1;
-  if (!wgrad(g, wg.A2 ? wg.A2->a : nullptr, wg.dy2)) return false;
+  if (!wgrad(g, &LayerActs::a, [&](int i) { return wg.dy_x[i]; })) return false;
   if (gpt && !colsum(s, p + "b2", H, dy, H, nullptr, nullptr, nullptr)) return false;
 
   // activation backward, in place over the saved pre-activations
@@ -522,7 +533,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   g.M = H; g.N = F; g.K = T; g.A = A.n2; g.lda = H; g.transA = 1; g.B = dff; g.c_f32_accum = 1; g.ldc = F;
   if (gpt) { g.ldb = F; g.C = GW("W1"); }
   else { g.ldb = 2 * F; g.C = GW("Wg"); g.batch = 2; g.sB = F; g.sC = (int64_t)H * F; }
-  if (!wgrad(g, wg.A2 ? wg.A2->n2 : nullptr, wg.A2 ? wg.A2->ff : nullptr)) return false;
+  if (!wgrad(g, &LayerActs::n2, [&](int i) { return (const char*)wg.Ax[i]->ff; })) return false;
   if (gpt && !colsum(s, p + "b1", F, dff, F, nullptr, nullptr, nullptr)) return false;
 
   // second norm: gain (and bias) partials, dx2 = dy + norm'(x2)^T dn2
@@ -539,7 +550,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   g = Gemm();
   g.M = H; g.N = H; g.K = T; g.A = A.o; g.lda = H; g.transA = 1; g.B = tmp; g.ldb = H; g.C = GW("Wo"); g.ldc = H;
   g.c_f32_accum = 1;
-  if (!wgrad(g, wg.A2 ? wg.A2->o : nullptr, wg.dx2_2)) return false;
+  if (!wgrad(g, &LayerActs::o, [&](int i) { return wg.dx2_x[i]; })) return false;
   if (gpt && !colsum(s, p + "bo", H, tmp, H, nullptr, nullptr, nullptr)) return false;
 
   // attention backward (+ inverse rotation of dq, dk)
@@ -561,7 +572,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   g.M = H; g.K = T; g.A = A.n1; g.lda = H; g.transA = 1; g.B = gqkv; g.ldb = 3 * H; g.c_f32_accum = 1;
   if (gpt) { g.N = 3 * H; g.C = GW("Wqkv"); g.ldc = 3 * H; }
   else { g.N = H; g.C = GW("Wq"); g.ldc = H; g.batch = 3; g.sB = H; g.sC = (int64_t)H * H; }
-  if (!wgrad(g, wg.A2 ? wg.A2->n1 : nullptr, wg.dqkv2)) return false;
+  if (!wgrad(g, &LayerActs::n1, [&](int i) { return wg.dqkv_x[i]; })) return false;
   if (gpt && !colsum(s, p + "bqkv", 3 * H, gqkv, 3 * H, nullptr, nullptr, nullptr)) return false;
 
   // first norm: dx = dx2 + norm'(x)^T dn1
@@ -607,38 +618,49 @@ bool head_backward(stage_t* s, const char* y, HeadActs& A, const int32_t* target
 
 bool check_slot(stage_t* s, int mb) { return mb >= 0 && mb < s->sh.M; }
 
-// The weight-gradient products of the deferred microbatch on their own (its slot is about to be reused, or
-// the step ends).
+// The weight-gradient products of the deferred microbatches on their own (a slot is about to be reused, or
+// the step ends): one multi-part product per weight over all of them.
 bool flush_deferred(stage_t* s) {
-  if (s->deferred < 0) return true;
+  const int nd = (int)s->deferred.size();
+  if (nd == 0) return true;
   const Shape& h = s->sh;
   Plan& pl = s->plan;
   const int T = h.T, H = h.H, F = h.F;
   const bool gpt = h.arch == STAGE_ARCH_GPT;
   for (int l = h.L - 1; l >= 0; --l) {
-    const LayerActs& A = pl.acts[(size_t)s->deferred * h.L + l];
+    auto acts = [&](int i) -> const LayerActs& { return pl.acts[(size_t)s->deferred[i] * h.L + l]; };
     const std::string p = "L" + std::to_string(l) + ".";
     auto GW = [&](const char* n) { return s->G(s->seg_off(p + n)); };
+    auto parts = [&](Gemm& g, char* LayerActs::*xsel, auto dsel) {   // part 0 = first deferred, the others follow
+      g.A = acts(0).*xsel; g.B = dsel(0);
+      g.K = nd * T;
+      if (nd > 1) { g.nx = nd - 1; g.kseg = T; }
+      for (int i = 1; i < nd; ++i) { g.Ax[i - 1] = acts(i).*xsel; g.Bx[i - 1] = dsel(i); }
+    };
     Gemm g;
-    g.M = F; g.N = H; g.K = T; g.A = A.a; g.lda = F; g.transA = 1; g.B = pl.kdy[l]; g.ldb = H;
+    g.M = F; g.N = H; g.lda = F; g.transA = 1; g.ldb = H;
     g.C = gpt ? GW("W2") : GW("Wd"); g.ldc = H; g.c_f32_accum = 1;
+    parts(g, &LayerActs::a, [&](int i) { return (const char*)pl.kdy[(size_t)i * h.L + l]; });
     if (!do_gemm(s, g)) return false;
     g = Gemm();
-    g.M = H; g.N = F; g.K = T; g.A = A.n2; g.lda = H; g.transA = 1; g.B = A.ff; g.c_f32_accum = 1; g.ldc = F;
+    g.M = H; g.N = F; g.lda = H; g.transA = 1; g.c_f32_accum = 1; g.ldc = F;
     if (gpt) { g.ldb = F; g.C = GW("W1"); }
     else { g.ldb = 2 * F; g.C = GW("Wg"); g.batch = 2; g.sB = F; g.sC = (int64_t)H * F; }
+    parts(g, &LayerActs::n2, [&](int i) { return (const char*)acts(i).ff; });
     if (!do_gemm(s, g)) return false;
     g = Gemm();
-    g.M = H; g.N = H; g.K = T; g.A = A.o; g.lda = H; g.transA = 1; g.B = pl.kdx2[l]; g.ldb = H; g.C = GW("Wo"); g.ldc = H;
+    g.M = H; g.N = H; g.lda = H; g.transA = 1; g.ldb = H; g.C = GW("Wo"); g.ldc = H;
     g.c_f32_accum = 1;
+    parts(g, &LayerActs::o, [&](int i) { return (const char*)pl.kdx2[(size_t)i * h.L + l]; });
     if (!do_gemm(s, g)) return false;
     g = Gemm();
-    g.M = H; g.K = T; g.A = A.n1; g.lda = H; g.transA = 1; g.B = pl.kdqkv[l]; g.ldb = 3 * H; g.c_f32_accum = 1;
+    g.M = H; g.lda = H; g.transA = 1; g.ldb = 3 * H; g.c_f32_accum = 1;
     if (gpt) { g.N = 3 * H; g.C = GW("Wqkv"); g.ldc = 3 * H; }
     else { g.N = H; g.C = GW("Wq"); g.ldc = H; g.batch = 3; g.sB = H; g.sC = (int64_t)H * H; }
+    parts(g, &LayerActs::n1, [&](int i) { return (const char*)pl.kdqkv[(size_t)i * h.L + l]; });
     if (!do_gemm(s, g)) return false;
   }
-  s->deferred = -1;
+  s->deferred.clear();
   return true;
 }
 
@@ -763,7 +785,8 @@ int stage_forward(stage_t* s, int32_t mb, const void* x_or_ids, void* y_out, con
   if (!h.head && !y_out) return fail(s, STAGE_ERR_ARG, "y_out is NULL");
   if (s->pending >= 0) return fail(s, STAGE_ERR_STATE, "a backward is waiting for stage_accumulate");
   if (s->slot[mb] != 0) return fail(s, STAGE_ERR_STATE, "slot already holds a forward that was not backpropagated");
-  if (s->deferred == mb && !flush_deferred(s)) return STAGE_ERR_DEVICE;   // its activations are about to be overwritten
+  for (int d : s->deferred)   // a deferred microbatch's activations are about to be overwritten
+    if (d == mb) { if (!flush_deferred(s)) return STAGE_ERR_DEVICE; break; }
   Plan& pl = s->plan;
   const DType dt = dt_of(s);
   const int64_t TH = (int64_t)h.T * h.H * h.E;
@@ -835,12 +858,16 @@ int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float l
       return STAGE_ERR_DEVICE;
   }
   auto in_of = [&](int l) { return h.recompute ? pl.stash[(size_t)k * h.L + l] : pl.acts[(size_t)mb * h.L + l].x_in; };
-  // pair_wgrad: a backward with further backwards to come leaves its weight-gradient products to the next
-  // one and keeps their dY operands in per-layer buffers; the next one multiplies for both.
-  const bool fuse = h.pair && s->deferred >= 0;
-  const bool defer = h.pair && !fuse && s->outstanding > 1;
+  // pair_wgrad: a backward with further backwards to come leaves its weight-gradient products to a later one and
+  // keeps their dY operands in per-layer buffers; the backward that completes a group of `group` microbatches,
+  // or the last outstanding one, multiplies for all of them in one K loop per weight.
+  const int nd = (int)s->deferred.size();
+  const bool last = s->outstanding == 1;
+  const bool fuse = h.pair && nd > 0 && (nd == h.group - 1 || last);
+  const bool defer = h.pair && !fuse && !last;
+  const size_t set = (size_t)nd * h.L;   // defer: this microbatch's buffers are kdy[set + l], ...
   // cur: gradient entering the layer (never written); its dx goes to the other scratch buffer
-  char* top = defer ? pl.kdy[h.L - 1] : pl.gA;
+  char* top = defer ? pl.kdy[set + h.L - 1] : pl.gA;
   const char* cur = h.head ? top : (const char*)dy;
   char* bufs[2] = {pl.gB, pl.gA};
   int bi = 0;
@@ -856,20 +883,23 @@ int stage_backward(stage_t* s, int32_t mb, const void* dy, void* dx_out, float l
   for (int l = h.L - 1; l >= 0; --l) {
     LayerActs& A = h.recompute ? pl.acts[0] : pl.acts[(size_t)mb * h.L + l];
     if (h.recompute && !layer_forward(s, l, in_of(l), A, nullptr)) return STAGE_ERR_DEVICE;
-    char* dst = (l == 0 && !h.embed) ? (char*)dx_out : (defer && l > 0) ? pl.kdy[l - 1] : bufs[bi];
+    char* dst = (l == 0 && !h.embed) ? (char*)dx_out : (defer && l > 0) ? pl.kdy[set + l - 1] : bufs[bi];
     WgradPlan wg;
     if (defer) wg.mode = 1;
     if (fuse) {
-      wg.mode = 2; wg.A2 = &pl.acts[(size_t)s->deferred * h.L + l];
-      wg.dy2 = pl.kdy[l]; wg.dx2_2 = pl.kdx2[l]; wg.dqkv2 = pl.kdqkv[l];
+      wg.mode = 2; wg.nx = nd;
+      for (int i = 0; i < nd; ++i) {
+        wg.Ax[i] = &pl.acts[(size_t)s->deferred[i] * h.L + l];
+        wg.dy_x[i] = pl.kdy[(size_t)i * h.L + l]; wg.dx2_x[i] = pl.kdx2[(size_t)i * h.L + l]; wg.dqkv_x[i] = pl.kdqkv[(size_t)i * h.L + l];
+      }
     }
-    if (!layer_backward(s, l, in_of(l), A, cur, defer ? pl.kdx2[l] : pl.ytmp, dst, defer ? pl.kdqkv[l] : pl.gQKV, wg))
+    if (!layer_backward(s, l, in_of(l), A, cur, defer ? pl.kdx2[set + l] : pl.ytmp, dst, defer ? pl.kdqkv[set + l] : pl.gQKV, wg))
       return STAGE_ERR_DEVICE;
     cur = dst;
     bi ^= 1;
   }
-  if (fuse) s->deferred = -1;
-  if (defer) s->deferred = mb;
+  if (fuse) s->deferred.clear();
+  if (defer) s->deferred.push_back(mb);
   if (h.embed) {
     // cur now holds the gradient of the embedding output
     if (!run(s, "embed", 0, 3.0 * TH, [&] {

@@ -338,8 +338,8 @@ def test_attention_fwd_bwd(gpu_device, mb, S, nh, d, dtype, impl):
 def test_weight_gradient_of_two_microbatches(gpu_device, dtype, impl, shape):
     """C += A1^T B1 + A2^T B2 in one product over both parts' rows, against float64."""
     M, N, K1, K2, batch = shape
-    if impl >= 2 and (dtype == 0 or K1 % 64):
-        pytest.skip("the MFMA kernel is bf16 only and needs the first part to be a multiple of 64 rows")
+    if impl >= 2 and (dtype == 0 or K1 % 128):
+        pytest.skip("the MFMA kernel is 16-bit only and needs the first part to be a multiple of 128 rows")
     print(f"[case] wgrad pair {shape} dtype={dtype} impl={impl}", flush=True)
     rng = np.random.default_rng(41)
     td = TD[dtype]
@@ -353,6 +353,34 @@ def test_weight_gradient_of_two_microbatches(gpu_device, dtype, impl, shape):
                       0, N, M * N, impl)
     err = rel_err(back(C), want)
     log_report(f"wgrad pair {shape} dtype={dtype} impl={impl}", [("C", err)])
+    assert err <= 2e-5
+
+
+@pytest.mark.parametrize("impl", [0, 1, 3, 4])
+@pytest.mark.parametrize("dtype", [1, 2])
+@pytest.mark.parametrize("shape", [(200, 136, 128, 128, 3, 1), (384, 520, 128, 40, 5, 2), (72, 264, 256, 256, 16, 1),
+                                   (256, 256, 128, 200, 2, 1), (136, 64, 320, 320, 1, 1), (264, 136, 384, 520, 4, 1),
+                                   (128, 128, 64, 64, 3, 1)])
+def test_weight_gradient_of_several_microbatches(gpu_device, dtype, impl, shape):
+    """C += sum_p A_p^T B_p over up to 16 parts in one K loop (the last part may have its own length, also one
+    that is longer than the others or no multiple of the slab), against float64."""
+    M, N, K_each, K_last, nparts, batch = shape
+    if impl >= 3 and nparts > 1 and K_each % 128:
+        pytest.skip("the MFMA kernel needs parts of a multiple of 128 rows")
+    print(f"[case] wgrad parts {shape} dtype={dtype} impl={impl}", flush=True)
+    rng = np.random.default_rng(43)
+    td = TD[dtype]
+    rows = [K_each] * (nparts - 1) + [K_last]
+    A = [draw(rng, (k, M), dtype) for k in rows]
+    B = [draw(rng, (k, N * batch), dtype, 0.05) for k in rows]
+    C0 = rng.standard_normal((batch, M, N)).astype(np.float32)
+    want = np.stack([C0[z] + sum(a.astype(np.float64).T @ b[:, z * N:(z + 1) * N].astype(np.float64) for a, b in zip(A, B))
+                     for z in range(batch)])
+    C = dev(C0)
+    zs.wgrad_parts(st(), dtype, M, N, K_each, K_last, [dev(a, td) for a in A], M, [dev(b, td) for b in B], N * batch, C, N,
+                   batch, 0, N, M * N, impl)
+    err = rel_err(back(C), want)
+    log_report(f"wgrad parts {shape} dtype={dtype} impl={impl}", [("C", err)])
     assert err <= 2e-5
 
 

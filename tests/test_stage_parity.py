@@ -49,30 +49,34 @@ def test_stage_step_with_ragged_sequence_lengths(gpu_device, name, seq, mb):
     log_report(f"ragged stage step {name} S={seq} mb={mb}", sorted(rep, key=lambda r: -r[1])[:6])
 
 
-@pytest.mark.parametrize("name,M", [("C3t", 16), ("C3t", 3), ("C2t", 8), ("C5t", 5), ("C4at", 2)])
-def test_paired_weight_gradients_match_oracle(gpu_device, name, M):
+@pytest.mark.parametrize("name,M,group", [("C3t", 16, 1), ("C3t", 3, 1), ("C2t", 8, 1), ("C5t", 5, 1), ("C4at", 2, 1),
+                                          ("C3t", 16, 16), ("C3t", 16, 4), ("C3t", 7, 3), ("C3t", 5, 64), ("C2t", 8, 8),
+                                          ("C5t", 5, 4), ("C3h", 4, 4)])
+def test_paired_weight_gradients_match_oracle(gpu_device, name, M, group):
     """pair_wgrad = 1: every other backward leaves its weight-gradient products to the next one, which runs them
-    over both microbatches' tokens.  Same sums, so the accumulated gradient and everything else must match
-    the oracle as before, for even and odd numbers of microbatches."""
-    cfg = get_config(name).with_(num_microbatches=M, pair_wgrad=1)
-    print(f"[case] paired wgrad {name} M={M}", flush=True)
+    over both microbatches' tokens; pair_wgrad = g >= 2: groups of g microbatches (at most 16) share one K loop,
+    and a last group may be smaller.  Same sums, so the accumulated gradient and everything else must match the
+    oracle as before."""
+    cfg = get_config(name).with_(num_microbatches=M, pair_wgrad=group)
+    print(f"[case] paired wgrad {name} M={M} group={group}", flush=True)
     inp = make_inputs(cfg, perturbed=True)
     g = GpuStage(cfg, inp)
     gpu = g.run_microbatches(inp)
     ora = oracle_step(cfg, inp)
     rep = []
     compare_step(cfg, gpu, ora, TOL[cfg.dtype], rep)
-    log_report(f"paired wgrad {name} M={M}", sorted(rep, key=lambda r: -r[1])[:6])
+    log_report(f"paired wgrad {name} M={M} group={group}", sorted(rep, key=lambda r: -r[1])[:6])
     res = g.step(1)
     compare_optimizer(cfg, inp, g.shard, gpu["grad"], res, ora["grad"], TOL[cfg.dtype])
     g.stage.close()
 
 
-def test_paired_weight_gradients_with_interleaved_calls(gpu_device):
+@pytest.mark.parametrize("group", [1, 3, 4])
+def test_paired_weight_gradients_with_interleaved_calls(gpu_device, group):
     """Orders other than all-forwards-then-all-backwards: a deferred microbatch whose slot is reused is flushed
     first, a backward with nothing else outstanding is not deferred, and the sum is the same."""
-    cfg = get_config("C3t").with_(num_microbatches=4, pair_wgrad=1)
-    print("[case] paired wgrad, interleaved order", flush=True)
+    cfg = get_config("C3t").with_(num_microbatches=4, pair_wgrad=group)
+    print(f"[case] paired wgrad, interleaved order, group={group}", flush=True)
     inp = make_inputs(cfg, perturbed=True)
     td = torch.bfloat16
     T, H = cfg.tokens, cfg.hidden
