@@ -27,13 +27,18 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (256 CUs x 4 SIMDs x 1024 flop/clk x 2.4 GHz)
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per launch of a workload's dominant kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of `bench.py --traffic-probe`, each counter scaled by what it reads for a copy of known size
-# (profiles/gemm_wgrad_C3_hbm_traffic.txt), and, for the paired launches (pair_wgrad = 1: two microbatches'
-# tokens per launch), from the same counters over one step of this file
-# (profiles/stage_step_C3_mfma_busy_hbm_bytes.txt).  Keys: workload, kernel class, pair_wgrad.  Workloads that
-# were not measured report null.
-MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 1): 1781.2e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6}
+# HBM-side bytes per launch of a workload's large kernel classes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# each counter scaled by what it reads for a copy of known size (profiles/gemm_wgrad_C3_hbm_traffic.txt: the
+# unpaired weight-gradient launches, `bench.py --traffic-probe`; profiles/stage_step_C3_mfma_busy_hbm_bytes.txt: one
+# step of this file).  Keys: workload, kernel class, weight-gradient group size (None: does not depend on it).
+# Anything that was not measured reports null.
+MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6, ("C3", "gemm_mfma_tn", 8): 5947.6e6,
+                    ("C3", "gemm_mfma_nn", None): 782.9e6, ("C3", "gemm_mfma_nt", None): 682.1e6}
+
+
+def measured_traffic(workload, kernel, cfg):
+    group = 0 if not cfg.pair_wgrad else min(max(cfg.pair_wgrad, 2), 16, cfg.num_microbatches)
+    return MEASURED_TRAFFIC.get((workload, kernel, group), MEASURED_TRAFFIC.get((workload, kernel, None)))
 
 
 def model_flops_per_step(cfg):
@@ -423,7 +428,7 @@ def main():
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k.get("gbs", 0.0), "peak": PEAK_HBM_GBS,
                         "unit": "GB/s", "frac": k.get("gbs", 0.0) / PEAK_HBM_GBS}
         roofline["avg_launch_ms"] = k["avg_ms"]
-        roofline["traffic"] = MEASURED_TRAFFIC.get((args.workload, dom, int(cfg.pair_wgrad)))
+        roofline["traffic"] = measured_traffic(args.workload, dom, cfg)
 
     out = {
         "metric": "stage train tokens/s on 1 MI355X (fwd+bwd+AdamW); MFMA util % of bf16 peak",
