@@ -77,10 +77,50 @@ int gemm_mfma_pick_tile(const Gemm& g) {
 
 void gemm_mfma_force_tile(int id) { g_force_tile = id; }
 
-hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g) {
-  const bool small = gemm_mfma_pick_tile(g) == 2;
+namespace {
+
+hipError_t run_tile(hipStream_t st, DType dt, const Gemm& g, bool small) {
   if (dt == F16) return small ? gemm_mfma_128x128_f16(st, g) : gemm_mfma_256x256_f16(st, g);
   return small ? gemm_mfma_128x128(st, g) : gemm_mfma_256x256(st, g);
+}
+
+// A grid of 256x256 tiles that ends in a round with few tiles (1376 tiles = 5 rounds + 96 tiles on 256 CUs) pays a
+// whole round for them.  When the leading tile columns make up whole rounds exactly, the product is cut along N:
+// those columns run on big tiles, the remaining ones on 128x128 tiles, which fill the chip (two workgroups per CU)
+// and take about 0.625 of a big round.  Returns false when the shape does not ask for it.
+bool split_tail(DType dt, const Gemm& g, Gemm& head, Gemm& tail) {
+  const int64_t tm = cdiv(g.M, 256), tn = cdiv(g.N, 256);
+  const int64_t tiles = tm * tn * g.batch, rem = tiles % 256;
+  if (tiles < 256 || rem == 0 || rem > 128) return false;   // up to 128 big tiles make one round of small ones
+  const int64_t col = tm * g.batch;                       // tiles per tile column
+  if (rem % col) return false;
+  const int64_t c1 = tn - rem / col;                      // leading columns: (tiles - rem) tiles, whole rounds
+  if (c1 < 1) return false;
+  const int64_t n1 = c1 * 256;
+  if (g.rope && n1 % g.rope_d) return false;
+  head = g; tail = g;
+  head.N = (int)n1;
+  tail.N = g.N - (int)n1;
+  const int64_t cb = g.c_f32_accum ? 4 : 2;
+  tail.C = (char*)g.C + n1 * cb;
+  if (g.bias) tail.bias = (const char*)g.bias + n1 * 2;
+  if (g.resid) tail.resid = (const char*)g.resid + n1 * 2;
+  const int64_t boff = (g.transB ? n1 * g.ldb : n1) * 2;
+  tail.B = (const char*)g.B + boff;
+  for (int p = 0; p < g.nx; ++p) tail.Bx[p] = (const char*)g.Bx[p] + boff;
+  return gemm_mfma_supported(dt, head) && gemm_mfma_supported(dt, tail);
+}
+
+}  // namespace
+
+hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g) {
+  const bool small = gemm_mfma_pick_tile(g) == 2;
+  Gemm head, tail;
+  if (!g_force_tile && !small && split_tail(dt, g, head, tail)) {
+    const hipError_t e = run_tile(st, dt, head, false);
+    return e != hipSuccess ? e : run_tile(st, dt, tail, true);
+  }
+  return run_tile(st, dt, g, small);
 }
 
 }  // namespace zs

@@ -137,6 +137,47 @@ def test_gemm_full_shape_sampled_outputs(gpu_device, dtype):
     assert ey <= 1e-2 and eda <= 1e-2 and edw <= 1e-4
 
 
+@pytest.mark.parametrize("dtype", [1, 2])
+def test_gemm_whose_last_round_runs_on_small_tiles(gpu_device, dtype):
+    """4096 x 11008 outputs in a batch of two are 1376 tiles of 256 x 256: five rounds on 256 CUs and 96 tiles.  The
+    dispatcher runs the leading 40 tile columns on big tiles and the last 768 columns on 128 x 128 tiles.  Sampled
+    outputs on both sides of the cut against float64 dot products, for the forward form (bias and residual
+    added), the segmented input-gradient form and the grouped weight gradient."""
+    rng = np.random.default_rng(23)
+    T, H, F, K = 4096, 4096, 11008, 256
+    td = TD[dtype]
+    g = torch.Generator(device="cuda").manual_seed(13)
+    x = torch.randn(T, K, device="cuda", generator=g).to(td)
+    W = (torch.randn(2, K, F, device="cuda", generator=g) * 0.05).to(td)
+    bias = torch.randn(2, F, device="cuda", generator=g).to(td)
+    res = torch.randn(2, T, F, device="cuda", generator=g).to(td)
+    y = torch.empty(2, T, F, dtype=td, device="cuda")
+    print("[case] gemm tail split NN batch 2", flush=True)
+    zs.ops.gemm(st(), dtype, 0, 0, T, F, K, x, K, W, F, y, F, 0, bias, res, F, 2, 0, K * F, T * F, F, 0, 0, 0)
+    torch.cuda.synchronize()
+    ii = rng.integers(0, T, 400)
+    jj = np.concatenate([rng.integers(0, F, 300), rng.integers(10240 - 4, 10240 + 4, 50), rng.integers(F - 300, F, 50)])
+    zz = rng.integers(0, 2, 400)
+    x64, W64 = x.float().cpu().numpy().astype(np.float64), W.float().cpu().numpy().astype(np.float64)
+    want = np.einsum("sk,sk->s", x64[ii], W64[zz, :, jj]) + bias.float().cpu().numpy()[zz, jj] + res.float().cpu().numpy()[zz, ii, jj]
+    got = y.float().cpu().numpy()[zz, ii, jj]
+    assert np.abs(got - want).max() / np.abs(want).max() <= 1e-2
+
+    print("[case] gemm tail split TN batch 2, three parts", flush=True)
+    parts = 3
+    xs = [torch.randn(256, H, device="cuda", generator=g).to(td) for _ in range(parts)]
+    dys = [(torch.randn(256, 2 * F, device="cuda", generator=g) * 0.05).to(td) for _ in range(parts)]
+    dW = torch.zeros(2, H, F, dtype=torch.float32, device="cuda")
+    zs.wgrad_parts(st(), dtype, H, F, 256, 256, xs, H, dys, 2 * F, dW, F, 2, 0, F, H * F, 0)
+    torch.cuda.synchronize()
+    rr = rng.integers(0, H, 400)
+    X = np.concatenate([t.float().cpu().numpy() for t in xs]).astype(np.float64)
+    D = np.concatenate([t.float().cpu().numpy() for t in dys]).astype(np.float64)
+    want = np.einsum("ks,ks->s", X[:, rr], D[:, zz * F + jj])
+    got = dW.cpu().numpy()[zz, rr, jj]
+    assert np.abs(got - want).max() / np.abs(want).max() <= 2e-5
+
+
 def test_gemm_with_operands_beyond_the_kernels_offset_range(gpu_device):
     """Token-sized operands of more than 2^30 bytes (26 624 tokens x 22 016 columns of bf16): the dispatcher cuts
     the product into launches of the MFMA kernel over row ranges (forward and input-gradient products, also
