@@ -63,16 +63,21 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
 // L2 bytes per flop; 128x128 tiles (two workgroups per CU) run at about 0.8 of their rate (measured at
 // K = 4096) but waste less of the last round of workgroups and give small problems enough workgroups to
 // fill the chip.  The shape with the smaller estimated time wins.
+namespace {
+// Estimated time of a grid of `small` 128x128 tiles in units of one round of 256x256 tiles: full rounds hold
+// 512 small tiles (two per CU, each at 0.8 of the big tile's rate); a remainder of at most 256 tiles runs
+// one per CU.
+double small_rounds(int64_t small) {
+  const int64_t rem = small % 512;
+  return ((double)(small / 512) * 2.0 + (rem == 0 ? 0.0 : rem <= 256 ? 1.0 : 2.0)) * 0.25 / 0.8;
+}
+}  // namespace
+
 int gemm_mfma_pick_tile(const Gemm& g) {
   if (g_force_tile) return g_force_tile;
   const int64_t big = cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
   const int64_t small = cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch;
-  const double t_big = (double)cdiv(big, 256) * 256.0 * 256.0;
-  // full rounds hold 512 small tiles (two per CU, each at 0.8 of the big tile's rate); a remainder of at
-  // most 256 tiles runs one per CU
-  const int64_t rem = small % 512;
-  const double t_small = ((double)(small / 512) * 2.0 + (rem == 0 ? 0.0 : rem <= 256 ? 1.0 : 2.0)) * 128.0 * 128.0 / 0.8;
-  return t_small < t_big ? 2 : 1;
+  return small_rounds(small) < (double)cdiv(big, 256) ? 2 : 1;
 }
 
 void gemm_mfma_force_tile(int id) { g_force_tile = id; }
@@ -116,9 +121,15 @@ bool split_tail(DType dt, const Gemm& g, Gemm& head, Gemm& tail) {
 hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g) {
   const bool small = gemm_mfma_pick_tile(g) == 2;
   Gemm head, tail;
-  if (!g_force_tile && !small && split_tail(dt, g, head, tail)) {
-    const hipError_t e = run_tile(st, dt, head, false);
-    return e != hipSuccess ? e : run_tile(st, dt, tail, true);
+  if (!g_force_tile && split_tail(dt, g, head, tail)) {
+    // whole rounds of big tiles + the rest on small ones, against the better of the two uniform grids
+    const int64_t big = cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
+    const double t_split = (double)(big / 256) + small_rounds(cdiv(tail.M, 128) * cdiv(tail.N, 128) * tail.batch);
+    const double t_uniform = small ? small_rounds(cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch) : (double)cdiv(big, 256);
+    if (t_split < t_uniform) {
+      const hipError_t e = run_tile(st, dt, head, false);
+      return e != hipSuccess ? e : run_tile(st, dt, tail, true);
+    }
   }
   return run_tile(st, dt, g, small);
 }
