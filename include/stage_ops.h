@@ -2,7 +2,7 @@
  * Single-kernel entry points of libstage, used to check each kernel of the stage step against
  * the CPU oracle on its own.  Same conventions as stage.h: device pointers, caller-owned
  * buffers, enqueue-only on the given hipStream_t, int status (STAGE_OK / STAGE_ERR_ARG /
- * STAGE_ERR_DEVICE).  dtype: 0 float, 1 bf16.  Argument checks happen on the host before any
+ * STAGE_ERR_DEVICE).  dtype: 0 float, 1 bf16, 2 IEEE half.  Argument checks happen on the host before any
  * launch.  The operations are the steps of one decoder layer's forward and backward pass and of
  * the optimizer update that the paper's training iteration consists of (Section 1: forward pass,
  * backward pass, optimizer update); the formulas are stated with each function.
@@ -19,7 +19,7 @@ extern "C" {
  * transB 0: B stored [K,N]; 1: stored [N,K].  c_f32_accum 0: C has `dtype`, overwritten;
  * 1: C is float and the product is added to it.  bias/resid may be NULL.  batch >= 1 with element
  * strides sA, sB, sC (sC also for resid), sBias.  kseg > 0: K is cut in segments of kseg and segment
- * s reads B from B + s*segB.  impl: 0 automatic, 1 the plain fp32-FMA kernel, 2 the bf16 MFMA
+ * s reads B from B + s*segB.  impl: 0 automatic, 1 the plain fp32-FMA kernel, 2 the 16-bit MFMA
  * kernel with its own choice of workgroup tile, 3 / 4 the MFMA kernel with the 256x256 / 128x128
  * tile (STAGE_ERR_ARG if the shape/alignment is not supported by the MFMA kernel). */
 int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
