@@ -287,8 +287,8 @@ def main():
     if args.offload and args.graph:
         print("bench.py: --offload cannot be combined with --graph", file=sys.stderr)
         sys.exit(2)
-    if args.ministages and (args.graph or args.offload or cfg.has_embed or cfg.has_head or cfg.layers % args.ministages):
-        print("bench.py: --ministages K needs an interior stage whose layer count K divides, and neither --graph nor --offload",
+    if args.ministages and (args.graph or cfg.has_embed or cfg.has_head or cfg.layers % args.ministages):
+        print("bench.py: --ministages K needs an interior stage whose layer count K divides, and no --graph",
               file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
@@ -330,7 +330,7 @@ def main():
     else:
         stage = zs.Stage(cc, params, master, grad, m, v, ws)
         shard_elems = e - b
-    if cfg.offload_acts:
+    if cfg.offload_acts and not args.ministages:
         stage.attach_host_stash(torch.empty(mem["host_stash"], dtype=torch.uint8, pin_memory=True))
 
     def microbatches():

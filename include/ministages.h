@@ -17,12 +17,14 @@
  *                                   still in flight, the one being loaded),
  *     1 fp32 gradient buffer       (shared: a ministage's gradients are dropped by its optimizer step
  *                                   before the next ministage's backward starts),
- *     K workspaces                 (each ministage's activations wait for its backward).
+ *     K activation workspaces      (each ministage's activations wait for its backward; with offload_acts two
+ *                                   microbatch slots each, the rest in the host block),
+ *     1 scratch buffer             (call-local, shared by all ministages).
  * Ministage k uses parameter slot k mod 2 and optimizer-state slot k mod 3 (fewer slots when K is smaller).
  *
  * Host block layout: ministage k occupies [k * per_stage_host, (k+1) * per_stage_host); inside it, at the
  * offsets ministages_query reports, the working parameters elem[P], then for the shard the fp32 master
- * (dtype 1 only), m and v.  The caller fills it before the first call (m = v = 0 for a fresh run); after a
+ * (16-bit dtypes only), m and v, then (offload_acts) the stash of its boundary activations.  The caller fills it before the first call (m = v = 0 for a fresh run); after a
  * ministage's optimizer step and a synchronisation of the device it holds the updated shard (working
  * parameters in [shard_begin, shard_end), master, m, v).  Parameters outside the shard are never written.
  *
@@ -44,8 +46,8 @@ typedef struct ministages ministages_t;
 
 typedef struct {
   stage_config stage;     /* shape of every ministage; shard_begin/end index one ministage's flat parameters;
-                             pair_wgrad and offload_acts are passed through to every ministage (offload_acts
-                             is not supported here and must be 0) */
+                             pair_wgrad, recompute and offload_acts are passed through to every ministage (with
+                             offload_acts the host block also holds each ministage's boundary activations) */
   int32_t n_ministages;   /* K >= 1 */
   int32_t reserved;
 } ministages_config;
@@ -54,8 +56,10 @@ typedef struct {
   int64_t per_stage_host;                        /* bytes of one ministage's host block (multiple of 256) */
   int64_t host_bytes;                            /* K * per_stage_host */
   int64_t off_params, off_master, off_m, off_v;  /* offsets inside one ministage's host block; off_master = -1 for dtype 0 */
-  int64_t param_slot, state_slot, grad, workspace_each;   /* bytes of one slot / buffer on the device */
-  int64_t device_bytes;                          /* arena: min(K,2) param slots + min(K,3) state slots + grad + K workspaces */
+  int64_t off_stash;                             /* offload_acts: offset of the ministage's boundary activations, else -1 */
+  int64_t param_slot, state_slot, grad, workspace_each, scratch;   /* bytes of one slot / buffer on the device */
+  int64_t device_bytes;                          /* arena: min(K,2) param slots + min(K,3) state slots + grad + scratch +
+                                                    K activation workspaces, in that order */
   int64_t resident_bytes;                        /* what the same K ministages need when all stay on the GPU:
                                                     K * (params + grads + optimizer state + workspace) */
 } ministages_memory;

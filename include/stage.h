@@ -129,6 +129,15 @@ int stage_layout(const stage_config* cfg, stage_segment* out, int32_t n_segments
 int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* master, float* grad_acc,
                float* adam_m, float* adam_v, void* workspace, int64_t workspace_bytes, stage_t** out);
 
+/* stage_init with the call-local part of the workspace in a buffer of its own: workspace then needs only
+ * mem.activations bytes (rounded up to 256) and scratch mem.workspace minus that.  Stages of ONE configuration
+ * that are bound to the same grad_acc and stream and whose calls never interleave inside a microbatch's forward
+ * or backward (the ministages of include/ministages.h) may share one scratch buffer; with pair_wgrad a stage's
+ * optimizer step must have run before another stage's backward starts.  scratch = NULL is stage_init. */
+int stage_init_split(const stage_config* cfg, void* hip_stream, void* params, float* master, float* grad_acc,
+                     float* adam_m, float* adam_v, void* workspace, int64_t workspace_bytes, void* scratch,
+                     int64_t scratch_bytes, stage_t** out);
+
 /* offload_acts = 1 only (else STAGE_ERR_ARG): hands the library the pinned host buffer that holds the
  * layer-boundary activations between a microbatch's forward and its backward (Section 4.1.3: with offloading
  * only the current and the next, prefetched, microbatch stay on the GPU).  Must be called once, before the

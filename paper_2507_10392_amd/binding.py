@@ -44,8 +44,8 @@ class MinistagesConfigC(C.Structure):
 
 class MinistagesMemoryC(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("per_stage_host", "host_bytes", "off_params", "off_master", "off_m", "off_v",
-                                         "param_slot", "state_slot", "grad", "workspace_each", "device_bytes",
-                                         "resident_bytes")]
+                                         "off_stash", "param_slot", "state_slot", "grad", "workspace_each", "scratch",
+                                         "device_bytes", "resident_bytes")]
 
 
 class StageLinearFitC(C.Structure):
@@ -76,6 +76,7 @@ def lib():
         L.stage_query.argtypes = [C.POINTER(StageConfigC), C.POINTER(i64), C.POINTER(StageMemoryC), C.POINTER(i32)]
         L.stage_layout.argtypes = [C.POINTER(StageConfigC), C.POINTER(StageSegmentC), i32]
         L.stage_init.argtypes = [C.POINTER(StageConfigC), vp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(vp)]
+        L.stage_init_split.argtypes = [C.POINTER(StageConfigC), vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, C.POINTER(vp)]
         L.stage_attach_host_stash.argtypes = [vp, vp, i64]
         L.stage_forward.argtypes = [vp, i32, vp, vp, vp, vp]
         L.stage_backward.argtypes = [vp, i32, vp, vp, f32]

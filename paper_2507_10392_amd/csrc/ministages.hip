@@ -31,7 +31,6 @@ struct Sizes {
 int sizes_of(const ministages_config* c, Sizes& z, std::string& err) {
   if (!c) { err = "config is NULL"; return STAGE_ERR_ARG; }
   if (c->n_ministages < 1 || c->n_ministages > 4096) { err = "n_ministages must be in 1..4096"; return STAGE_ERR_ARG; }
-  if (c->stage.offload_acts) { err = "offload_acts is not supported for ministages"; return STAGE_ERR_ARG; }
   const int rc = stage_query(&c->stage, &z.P, &z.smem, nullptr);
   if (rc != STAGE_OK) { err = stage_last_error(nullptr); return rc; }
   const int K = c->n_ministages;
@@ -44,6 +43,8 @@ int sizes_of(const ministages_config* c, Sizes& z, std::string& err) {
   if (bf) { m.off_master = o; o = up256(o + z.shard * 4); } else m.off_master = -1;
   m.off_m = o; o = up256(o + z.shard * 4);
   m.off_v = o; o = up256(o + z.shard * 4);
+  m.off_stash = z.smem.host_stash ? o : -1;              // offload_acts: the ministage's boundary activations
+  o = up256(o + z.smem.host_stash);
   m.per_stage_host = o;
   m.host_bytes = o * K;
   m.param_slot = up256(z.P * z.E);
@@ -53,8 +54,9 @@ int sizes_of(const ministages_config* c, Sizes& z, std::string& err) {
   z.st_v = s; s = up256(s + z.shard * 4);
   m.state_slot = s;
   m.grad = up256(z.P * 4);
-  m.workspace_each = up256(z.smem.workspace);
-  m.device_bytes = param_slots(K) * m.param_slot + state_slots(K) * m.state_slot + m.grad + (int64_t)K * m.workspace_each;
+  m.workspace_each = up256(z.smem.activations);          // what waits for the ministage's backward
+  m.scratch = z.smem.workspace - m.workspace_each;       // call-local, shared by all ministages
+  m.device_bytes = param_slots(K) * m.param_slot + state_slots(K) * m.state_slot + m.grad + (int64_t)K * m.workspace_each + m.scratch;
   m.resident_bytes = (int64_t)K * (z.smem.params + z.smem.grads + z.smem.optim + z.smem.workspace);
   return STAGE_OK;
 }
@@ -234,6 +236,7 @@ int ministages_init(const ministages_config* cfg, void* hip_stream, void* host_s
   for (int i = 0; i < ms->np; ++i) { ms->pslot[i] = p; p += z.m.param_slot; }
   for (int i = 0; i < ms->ns; ++i) { ms->sslot[i] = p; p += z.m.state_slot; }
   ms->grad = (float*)p; p += z.m.grad;
+  char* scratch = p; p += z.m.scratch;                    // one call-local scratch buffer for all ministages
   auto bail = [&](int code, const std::string& msg) {
     ministages_destroy(ms);
     return fail(nullptr, code, msg);
@@ -250,11 +253,16 @@ int ministages_init(const ministages_config* cfg, void* hip_stream, void* host_s
   for (int k = 0; k < ms->K; ++k) {
     char* sd = ms->sslot[k % ms->ns];
     stage_t* s = nullptr;
-    rc = stage_init(&cfg->stage, hip_stream, ms->pslot[k % ms->np], z.st_master >= 0 && z.shard > 0 ? (float*)(sd + z.st_master) : nullptr,
-                    ms->grad, z.shard > 0 ? (float*)(sd + z.st_m) : nullptr, z.shard > 0 ? (float*)(sd + z.st_v) : nullptr, p,
-                    z.m.workspace_each, &s);
+    rc = stage_init_split(&cfg->stage, hip_stream, ms->pslot[k % ms->np],
+                          z.st_master >= 0 && z.shard > 0 ? (float*)(sd + z.st_master) : nullptr, ms->grad,
+                          z.shard > 0 ? (float*)(sd + z.st_m) : nullptr, z.shard > 0 ? (float*)(sd + z.st_v) : nullptr, p,
+                          z.m.workspace_each, scratch, z.m.scratch, &s);
     if (rc != STAGE_OK) return bail(rc, std::string("stage_init of ministage ") + std::to_string(k) + ": " + stage_last_error(nullptr));
     ms->stages.push_back(s);
+    if (z.m.off_stash >= 0) {
+      rc = stage_attach_host_stash(s, host_of(ms, k, z.m.off_stash), z.smem.host_stash);
+      if (rc != STAGE_OK) return bail(rc, std::string("host stash of ministage ") + std::to_string(k) + ": " + stage_last_error(s));
+    }
     p += z.m.workspace_each;
   }
   if (!load_params(ms, 0)) { const std::string m2 = ms->err; return bail(STAGE_ERR_DEVICE, m2); }

@@ -175,7 +175,9 @@ int64_t vector_widths_per_layer(const Shape& s) {   // summed widths of a layer'
 }
 
 // One routine both sizes (base == NULL) and assigns the workspace, so the two can never disagree.
-void make_plan(const stage_config& c, char* base, Plan& p) {
+// scratch_base != NULL: the call-local part is carved from a buffer of its own (stages of one shape that never
+// run at the same time may share it); its layout is the one it has behind the activations.
+void make_plan(const stage_config& c, char* base, Plan& p, char* scratch_base = nullptr) {
   const Shape s = shape_of(c);
   const int64_t TH = (int64_t)s.T * s.H * s.E;
   Bump b(base);
@@ -212,6 +214,8 @@ void make_plan(const stage_config& c, char* base, Plan& p) {
   if (s.embed) { p.ids.resize(s.M); for (auto& q : p.ids) q = b.take<int32_t>(4ll * s.T); }
   if (s.head) { p.targets.resize(s.M); for (auto& q : p.targets) q = b.take<int32_t>(4ll * s.T); }
   p.act_bytes = b.off;
+  const int64_t act_end = (b.off + 255) & ~(int64_t)255;
+  if (scratch_base) b = Bump(scratch_base);
   // ---- scratch live inside one call
   if (s.recompute) {
     p.acts.resize(1);
@@ -235,7 +239,7 @@ void make_plan(const stage_config& c, char* base, Plan& p) {
   p.partials = b.take<float>(4 * p.partial_floats);
   p.njobs_cap = s.L * 8 + 1;
   p.jobs = b.take<ReduceJob>((int64_t)sizeof(ReduceJob) * p.njobs_cap);
-  p.total = (b.off + 255) & ~(int64_t)255;
+  p.total = ((b.off + 255) & ~(int64_t)255) + (scratch_base ? act_end : 0);
   p.scratch_bytes = p.total - p.act_bytes;
 }
 
@@ -701,6 +705,12 @@ int stage_layout(const stage_config* cfg, stage_segment* out, int32_t n_segments
 
 int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* master, float* grad_acc, float* adam_m,
                float* adam_v, void* workspace, int64_t workspace_bytes, stage_t** out) {
+  return stage_init_split(cfg, hip_stream, params, master, grad_acc, adam_m, adam_v, workspace, workspace_bytes, nullptr, 0, out);
+}
+
+int stage_init_split(const stage_config* cfg, void* hip_stream, void* params, float* master, float* grad_acc, float* adam_m,
+                     float* adam_v, void* workspace, int64_t workspace_bytes, void* scratch, int64_t scratch_bytes,
+                     stage_t** out) {
   if (out) *out = nullptr;
   if (!out) return fail(nullptr, STAGE_ERR_ARG, "out is NULL");
   stage_memory mem;
@@ -714,16 +724,20 @@ int stage_init(const stage_config* cfg, void* hip_stream, void* params, float* m
   if (((uintptr_t)params | (uintptr_t)grad_acc | (uintptr_t)master | (uintptr_t)adam_m | (uintptr_t)adam_v) & 15)
     return fail(nullptr, STAGE_ERR_ARG, "params, master, grad_acc, adam_m, adam_v must be 16-byte aligned");
   if (!workspace || ((uintptr_t)workspace & 255)) return fail(nullptr, STAGE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
-  if (workspace_bytes < mem.workspace)
+  const int64_t act_part = (mem.activations + 255) & ~(int64_t)255;   // with a scratch buffer of its own: the two parts
+  const int64_t need_ws = scratch ? act_part : mem.workspace, need_scratch = mem.workspace - act_part;
+  if (workspace_bytes < need_ws)
     return fail(nullptr, STAGE_ERR_WORKSPACE, "workspace has " + std::to_string(workspace_bytes) + " bytes, " +
-                                                  std::to_string(mem.workspace) + " needed");
+                                                  std::to_string(need_ws) + " needed");
+  if (scratch && (((uintptr_t)scratch & 255) || scratch_bytes < need_scratch))
+    return fail(nullptr, STAGE_ERR_WORKSPACE, "scratch is not 256-byte aligned or has fewer than " + std::to_string(need_scratch) + " bytes");
   stage_t* s = new stage();
   s->cfg = *cfg;
   s->sh = shape_of(*cfg);
   s->st = (hipStream_t)hip_stream;
   s->params = (char*)params; s->master = master; s->grad = grad_acc; s->m = adam_m; s->v = adam_v;
   s->layout = make_layout(*cfg);
-  make_plan(*cfg, (char*)workspace, s->plan);
+  make_plan(*cfg, (char*)workspace, s->plan, (char*)scratch);
   s->slot.assign(s->sh.M, 0);
   s->where.assign(s->sh.M, -1);
 

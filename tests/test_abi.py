@@ -94,15 +94,20 @@ def test_ministages_memory_report():
         up = lambda n: (n + 255) // 256 * 256
         assert m["off_params"] == 0 and m["off_master"] == up(2 * P) and m["off_m"] == m["off_master"] + up(4 * sh)
         assert m["per_stage_host"] == up(2 * P) + 3 * up(4 * sh) and m["host_bytes"] == K * m["per_stage_host"]
-        assert m["device_bytes"] == min(K, 2) * up(2 * P) + min(K, 3) * 3 * up(4 * sh) + up(4 * P) + K * up(mem["workspace"])
+        act, scratch = up(mem["activations"]), mem["workspace"] - up(mem["activations"])
+        assert m["workspace_each"] == act and m["scratch"] == scratch and m["off_stash"] == -1
+        assert m["device_bytes"] == min(K, 2) * up(2 * P) + min(K, 3) * 3 * up(4 * sh) + up(4 * P) + scratch + K * act
         assert m["resident_bytes"] == K * (mem["params"] + mem["grads"] + mem["optim"] + mem["workspace"])
     assert "ministages_forward" in declared_symbols() and "ministages_destroy" in declared_symbols()
     with pytest.raises(zs.StageError) as ei:
         zs.ministages_query(cc, 0)
     assert ei.value.code == zs.STAGE_ERR_ARG
-    with pytest.raises(zs.StageError) as ei:
-        zs.ministages_query(zs.make_config(cfg.with_(recompute=1, offload_acts=1)), 2)
-    assert ei.value.code == zs.STAGE_ERR_ARG
+    # with the boundary activations offloaded each ministage keeps two microbatch slots, its stash joins the host block
+    oc = zs.make_config(cfg.with_(recompute=1, offload_acts=1))
+    _, omem, _ = zs.query(oc)
+    m = zs.ministages_query(oc, 4)
+    assert m["off_stash"] == m["off_v"] + up(4 * sh) and m["per_stage_host"] == m["off_stash"] + up(omem["host_stash"])
+    assert m["workspace_each"] == up(omem["activations"]) and omem["host_stash"] == 16 * 2 * 4096 * 4096 * 2
 
 
 def test_library_line_fit_matches_oracle():

@@ -147,6 +147,46 @@ def test_ministages_equal_resident_stages_over_two_steps(gpu_device):
     G.ms.close()
 
 
+@pytest.mark.parametrize("recompute,offload,group", [(1, 0, 0), (1, 1, 0), (0, 0, 4)])
+def test_ministages_with_recompute_offload_and_grouped_gradients(gpu_device, recompute, offload, group):
+    """The options of a stage pass through to the ministages: per-layer recompute, boundary activations in the host
+    block (two microbatch slots per ministage on the device), weight gradients in groups.  All ministages share
+    one scratch buffer.  Same bits as resident stages with the same options, over two steps."""
+    K, L, M = 3, 2, 4
+    cfg = get_config("C3t").with_(layers=L, num_microbatches=M, recompute=recompute, offload_acts=offload, pair_wgrad=group)
+    full = cfg.with_(layers=K * L)
+    print(f"[case] ministages recompute={recompute} offload={offload} group={group}", flush=True)
+    inp = make_inputs(full, perturbed=True)
+    td, T, H = tdtype(cfg), cfg.tokens, cfg.hidden
+    xs = [dev(inp.x[i], td) for i in range(M)]
+    dys = [dev(inp.dy[i], td) for i in range(M)]
+    G = Group(cfg, K, inp)
+    P = G.P
+    assert (G.mem["off_stash"] >= 0) == bool(offload)
+    res = [GpuStage(cfg, types.SimpleNamespace(params=inp.params[k * P:(k + 1) * P], master=inp.master[k * P:(k + 1) * P]))
+           for k in range(K)]
+    for t in (1, 2):
+        a = gpipe_step(G.ms.forward, G.ms.backward, G.ms.accumulate, G.ms.optimizer_step, K, M, xs, dys, T, H, td, t)
+        r = gpipe_step(lambda k, i, x, y: res[k].stage.forward(i, x, y), lambda k, i, dy, dx, ls: res[k].stage.backward(i, dy, dx, ls),
+                       lambda k, i: res[k].stage.accumulate(i), lambda k, tt: res[k].stage.optimizer_step(tt), K, M, xs, dys, T, H, td, t)
+        for u, v in zip(a[0] + a[1], r[0] + r[1]):
+            assert torch.equal(u, v), f"step {t}"
+    b, e = G.b, G.e
+    for k in range(K):
+        assert torch.equal(G.params(k)[b:e], res[k].params[b:e].cpu())
+        assert torch.equal(G.state(k, "m"), res[k].m.cpu()) and torch.equal(G.state(k, "v"), res[k].v.cpu())
+        res[k].stage.close()
+    # against the oracle too: one more step from the same state is not needed, the first step's outputs are
+    ora = so.stage_step(hp32(full), inp.params, inp.x[:M], inp.dy[:M])
+    G2 = Group(cfg, K, inp)
+    ys, dxs, _ = gpipe_step(G2.ms.forward, G2.ms.backward, G2.ms.accumulate, G2.ms.optimizer_step, K, M, xs, dys, T, H, td, 1)
+    for i in range(M):
+        assert rel_err(ys[i].float().cpu().numpy(), ora["y"][i]) <= TOL[cfg.dtype]
+        assert rel_err(dxs[i].float().cpu().numpy(), ora["dx"][i]) <= TOL[cfg.dtype]
+    G.ms.close()
+    G2.ms.close()
+
+
 def test_ministages_state_and_argument_errors(gpu_device):
     print("[case] ministages errors", flush=True)
     K, M = 2, 1
