@@ -134,11 +134,11 @@ def oracle_step(cfg, inp, M=None, loss_scale=None):
 
 
 def log_report(title, rows):
-    """Appends error figures to gpurun_out/parity_report.txt when that folder exists (GPU machine runs)."""
+    """Appends error figures to the text file named by the environment variable STAGE_PARITY_REPORT, if it is set."""
     import os
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "parity_report.txt"), "a") as f:
+    path = os.environ.get("STAGE_PARITY_REPORT")
+    if path:
+        with open(path, "a") as f:
             f.write(title + "\n")
             for name, e in rows:
                 f.write(f"    {name:28s} {e:.3e}\n")
