@@ -53,6 +53,19 @@ int stage_op_wgrad_parts(void* stream, int32_t dtype, int32_t M, int32_t N, int3
                          const void* const* A_parts, int64_t lda, const void* const* B_parts, int64_t ldb, float* C,
                          int64_t ldc, int32_t batch, int64_t sA, int64_t sB, int64_t sC, int32_t impl);
 
+/* The gated FFN unit of the Llama-style layer fused into the store of a product (the layer the paper's Llama
+ * workloads are built from, Section 6.1); gu is dense [M, 2N] = [gate | up], a dense [M, N].
+ * mode 1 (forward): gate = A Wg and up = A Wu are written, rounded, to gu and silu(gate) * up of the ROUNDED values
+ *   to a: exactly what the batched product followed by stage_op_swiglu leaves.  A = x [M,K] (row stride lda); Wg and
+ *   Wu are stored [K,N] (row stride ldb), Wu lying sB elements behind Wg (B = Wg).
+ * mode 2 (backward): da = A B^T with A = dy [M,K] and B = Wd stored [N,K] (row stride ldb; sB ignored); (gate, up)
+ *   in gu are replaced by (dgate, dup) = (da * up * silu'(gate), da * silu(gate)).  a is scratch of M*N elements whose
+ *   content is unspecified afterwards (the MFMA kernel keeps da in fp32 and never stores it).
+ * impl as for stage_op_gemm; implementations other than the MFMA kernel run the plain product(s) and then the
+ * activation kernel.  STAGE_ERR_ARG when a forced MFMA kernel does not take the arguments. */
+int stage_op_gemm_glu(void* stream, int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void* A, int64_t lda,
+                      const void* B, int64_t ldb, int64_t sB, void* a, void* gu, int32_t impl);
+
 /* kind 0: LayerNorm n = (x-mean)/sqrt(var+eps)*g + b (biased variance), saves rstd[T], mean[T].
  * kind 1: RMSNorm n = x/sqrt(mean(x^2)+eps)*g, saves rstd[T].  x, n: [T,H]. */
 int stage_op_norm_fwd(void* stream, int32_t dtype, int32_t kind, int32_t T, int32_t H, const void* x, const void* g,

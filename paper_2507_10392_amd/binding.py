@@ -109,6 +109,7 @@ def lib():
         L.stage_op_gemm.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, i64, vp, i64, vp, i64, i32, vp, vp, i64, i32,
                                     i64, i64, i64, i64, i32, i64, i32]
         L.stage_op_gemm_rope.argtypes = L.stage_op_gemm.argtypes + [vp, i32, i32, i32]
+        L.stage_op_gemm_glu.argtypes = [vp, i32, i32, i32, i32, i32, vp, i64, vp, i64, i64, vp, vp, i32]
         L.stage_op_rope_table.argtypes = [vp, i32, i32, f32, vp]
         L.stage_op_wgrad_pair.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, vp, i64, vp, i64, i32, i64, i64, i64, i32]
         L.stage_op_wgrad_parts.argtypes = [vp, i32, i32, i32, i32, i32, i32, C.POINTER(vp), i64, C.POINTER(vp), i64, vp, i64, i32,

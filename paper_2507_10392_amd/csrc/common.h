@@ -58,6 +58,16 @@ template <int NW> __device__ __forceinline__ float block_sum(float v, float* red
   return t;
 }
 
+// Gated FFN unit of the Llama-style layer: a = silu(gate) * up, and (dgate, dup) from da.  One definition, so that
+// the stand-alone kernels and the GEMM epilogues that fuse them produce the same bits.
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + expf(-z)); }
+__device__ __forceinline__ float glu_f(float g, float u) { return g * sigmoid_f(g) * u; }
+__device__ __forceinline__ void glu_df(float d, float g, float u, float& dg, float& du) {
+  const float s = sigmoid_f(g);
+  du = d * g * s;
+  dg = d * u * s * (1.0f + g * (1.0f - s));
+}
+
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 }  // namespace zs

@@ -427,7 +427,6 @@ __device__ __forceinline__ float gelu_df(float z) {
   const float phi = 0.39894228040143268f * expf(-0.5f * z * z);
   return Phi + z * phi;
 }
-__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + expf(-z)); }
 
 template <typename T, int MODE>  // 0: a = gelu(z); 1: dz = da * gelu'(z)
 __global__ __launch_bounds__(256) void gelu_kernel(int64_t nvec, const T* __restrict__ z, const T* __restrict__ da,
@@ -473,17 +472,13 @@ __global__ __launch_bounds__(256) void swiglu_kernel(int Trows, int F, const T* 
   if (MODE == 0) {
     float o[V];
 #pragma unroll
-    for (int k = 0; k < V; ++k) o[k] = g[k] * sigmoid_f(g[k]) * u[k];
+    for (int k = 0; k < V; ++k) o[k] = glu_f(g[k], u[k]);
     store_vec(out + (int64_t)t * F + c, o);
   } else {
     float d[V], dg[V], du[V];
     load_vec(da + (int64_t)t * F + c, d);
 #pragma unroll
-    for (int k = 0; k < V; ++k) {
-      const float s = sigmoid_f(g[k]);
-      du[k] = d[k] * g[k] * s;
-      dg[k] = d[k] * u[k] * s * (1.0f + g[k] * (1.0f - s));
-    }
+    for (int k = 0; k < V; ++k) glu_df(d[k], g[k], u[k], dg[k], du[k]);
     store_vec(out + (int64_t)t * 2 * F + c, dg);
     store_vec(out + (int64_t)t * 2 * F + F + c, du);
   }

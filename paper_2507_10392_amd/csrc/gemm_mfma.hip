@@ -25,6 +25,13 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
   if (g.K % 8) return false;                       // k-contiguous operands are read 8 k at a time; tails are zero-filled
   if (g.transA && g.M % 8) return false;           // row-contiguous operands are read 8 rows at a time
   if (!g.transB && g.N % 8) return false;
+  if (g.glu) {   // gated unit fused into the store
+    if (g.glu != 1 && g.glu != 2) return false;
+    if (g.transA || (g.glu == 1) == (g.transB != 0)) return false;   // 1: y = x [Wg | Wu]; 2: da = dy Wd^T
+    if (g.c_f32_accum || g.batch != 1 || g.bias || g.resid || g.rope || g.kseg || g.nx) return false;
+    if (!g.gu || !aligned16(g.gu) || g.gu_ld % 8 || g.gu_up % 8 || g.N % 8) return false;
+    if (g.glu == 1 && g.sB <= 0) return false;
+  }
   if (g.nx) {   // multi-part K range of an accumulating product
     if (g.nx < 0 || g.nx >= GEMM_MAX_PARTS) return false;
     // the K loop takes two slabs of 64 rows per step, and a step must lie inside one part
@@ -54,7 +61,7 @@ bool gemm_mfma_supported(DType dt, const Gemm& g) {
   const int64_t extA = (g.transA ? rowsA * g.lda : (int64_t)g.M * g.lda) * 2;
   const int64_t nseg = g.kseg ? g.K / g.kseg : 1;
   const int64_t nsegB = g.nx ? 1 : nseg;
-  const int64_t extB = (g.transB ? (nsegB - 1) * g.segB + (int64_t)g.N * g.ldb : rowsA * g.ldb) * 2;
+  const int64_t extB = (g.transB ? (nsegB - 1) * g.segB + (int64_t)g.N * g.ldb : rowsA * g.ldb + (g.glu == 1 ? g.sB : 0)) * 2;
   if (extA >= (1ll << 30) || extB >= (1ll << 30)) return false;
   return true;
 }
@@ -71,12 +78,14 @@ double small_rounds(int64_t small) {
   const int64_t rem = small % 512;
   return ((double)(small / 512) * 2.0 + (rem == 0 ? 0.0 : rem <= 256 ? 1.0 : 2.0)) * 0.25 / 0.8;
 }
+// Tile columns of a grid of tiles `width` wide: a gate|up tile (glu = 1) covers width/2 columns of each matrix.
+int64_t tile_cols(const Gemm& g, int width) { return cdiv(g.N, g.glu == 1 ? width / 2 : width); }
 }  // namespace
 
 int gemm_mfma_pick_tile(const Gemm& g) {
   if (g_force_tile) return g_force_tile;
-  const int64_t big = cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
-  const int64_t small = cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch;
+  const int64_t big = cdiv(g.M, 256) * tile_cols(g, 256) * g.batch;
+  const int64_t small = cdiv(g.M, 128) * tile_cols(g, 128) * g.batch;
   return small_rounds(small) < (double)cdiv(big, 256) ? 2 : 1;
 }
 
@@ -94,14 +103,14 @@ hipError_t run_tile(hipStream_t st, DType dt, const Gemm& g, bool small) {
 // those columns run on big tiles, the remaining ones on 128x128 tiles, which fill the chip (two workgroups per CU)
 // and take about 0.625 of a big round.  Returns false when the shape does not ask for it.
 bool split_tail(DType dt, const Gemm& g, Gemm& head, Gemm& tail) {
-  const int64_t tm = cdiv(g.M, 256), tn = cdiv(g.N, 256);
+  const int64_t tm = cdiv(g.M, 256), tn = tile_cols(g, 256);
   const int64_t tiles = tm * tn * g.batch, rem = tiles % 256;
   if (tiles < 256 || rem == 0 || rem > 128) return false;   // up to 128 big tiles make one round of small ones
   const int64_t col = tm * g.batch;                       // tiles per tile column
   if (rem % col) return false;
   const int64_t c1 = tn - rem / col;                      // leading columns: (tiles - rem) tiles, whole rounds
   if (c1 < 1) return false;
-  const int64_t n1 = c1 * 256;
+  const int64_t n1 = c1 * (g.glu == 1 ? 128 : 256);
   if (g.rope && n1 % g.rope_d) return false;
   head = g; tail = g;
   head.N = (int)n1;
@@ -110,6 +119,7 @@ bool split_tail(DType dt, const Gemm& g, Gemm& head, Gemm& tail) {
   tail.C = (char*)g.C + n1 * cb;
   if (g.bias) tail.bias = (const char*)g.bias + n1 * 2;
   if (g.resid) tail.resid = (const char*)g.resid + n1 * 2;
+  if (g.gu) tail.gu = (char*)g.gu + n1 * 2;
   const int64_t boff = (g.transB ? n1 * g.ldb : n1) * 2;
   tail.B = (const char*)g.B + boff;
   for (int p = 0; p < g.nx; ++p) tail.Bx[p] = (const char*)g.Bx[p] + boff;
@@ -123,9 +133,9 @@ hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g) {
   Gemm head, tail;
   if (!g_force_tile && split_tail(dt, g, head, tail)) {
     // whole rounds of big tiles + the rest on small ones, against the better of the two uniform grids
-    const int64_t big = cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
-    const double t_split = (double)(big / 256) + small_rounds(cdiv(tail.M, 128) * cdiv(tail.N, 128) * tail.batch);
-    const double t_uniform = small ? small_rounds(cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch) : (double)cdiv(big, 256);
+    const int64_t big = cdiv(g.M, 256) * tile_cols(g, 256) * g.batch;
+    const double t_split = (double)(big / 256) + small_rounds(cdiv(tail.M, 128) * tile_cols(tail, 128) * tail.batch);
+    const double t_uniform = small ? small_rounds(cdiv(g.M, 128) * tile_cols(g, 128) * g.batch) : (double)cdiv(big, 256);
     if (t_split < t_uniform) {
       const hipError_t e = run_tile(st, dt, head, false);
       return e != hipSuccess ? e : run_tile(st, dt, tail, true);

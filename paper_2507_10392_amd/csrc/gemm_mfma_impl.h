@@ -73,6 +73,13 @@ __device__ __forceinline__ void store_kmajor(const Frag<R, NT>& f, bf16* lds, in
 template <int R> __device__ __forceinline__ int voff_rmajor(int ld, int tid, int row0, int nrows) {
   return row0 + (tid % (R / 8)) * 8 >= nrows ? DEAD : ((tid / (R / 8)) * ld + (tid % (R / 8)) * 8) * 2;
 }
+// The same for a tile whose first R/2 rows come from one matrix (rows row0 .. of `nrows`) and whose last R/2 rows
+// are the same rows of a second matrix lying `second` elements behind the first: gate and up projections side by side.
+template <int R> __device__ __forceinline__ int voff_rmajor_two(int ld, int tid, int row0, int nrows, int second) {
+  constexpr int PER = R / 8, HALF = PER / 2;
+  const int j = tid % PER, jj = j % HALF;
+  return row0 + jj * 8 >= nrows ? DEAD : ((tid / PER) * ld + jj * 8 + (j >= HALF ? second : 0)) * 2;
+}
 template <int R, int NT>
 __device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int k0) {
   constexpr int KSTEP = NT / (R / 8);             // k-lines covered by one pass of the NT threads
@@ -198,7 +205,7 @@ template <> __device__ __forceinline__ f32x16 mfma_32x32x16<f16>(bf16x8 a, bf16x
 // Epilogue for 16-bit output (E = bf16 or IEEE half): after staging, ALL threads read rows back 8 columns at a time, add bias and
 // residual in fp32, round once to bf16 and store 16 bytes per lane, consecutive lanes covering
 // consecutive 16-byte pieces of a row of C.
-template <typename E, int BM, int BN, int NT, int MI, int NJ>
+template <typename E, int BM, int BN, int NT, int MI, int NJ, int GLU>
 __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
                                                int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
@@ -224,6 +231,21 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
       const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + (v % VPR) * 8);
       const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + (v % VPR) * 8 + 4);
       float x[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+      if (GLU == 2) {   // x is da: (gate, up) of these 8 columns become (dgate, dup) in place (N is a multiple of 8)
+        E* pg = (E*)g.gu + (int64_t)row * g.gu_ld + col;
+        const E8 gg = *reinterpret_cast<const E8*>(pg), uu = *reinterpret_cast<const E8*>(pg + g.gu_up);
+        E8 og, ou;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float dg, du;
+          glu_df(x[e], (float)gg[e], (float)uu[e], dg, du);
+          og[e] = (E)dg;
+          ou[e] = (E)du;
+        }
+        *reinterpret_cast<E8*>(pg) = og;
+        *reinterpret_cast<E8*>(pg + g.gu_up) = ou;
+        continue;
+      }
       if (col + 8 <= g.N) {
         if (bias) {
           const E8 bb = *reinterpret_cast<const E8*>(bias + col);
@@ -262,9 +284,48 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
   }
 }
 
+// Epilogue of the gate|up projection (GLU = 1): the tile's first BN/2 columns are gate columns c0 .. and its last
+// BN/2 the up columns of the same index.  Both are rounded and stored into gu, and silu(gate) * up of the rounded
+// values goes to C: the three arrays the batched product followed by the activation kernel would leave.
+template <typename E, int BM, int BN, int NT, int MI, int NJ>
+__device__ __forceinline__ void epilogue_glu(const Gemm& g, f32x16 (&acc)[MI][NJ], int m0, int c0, int wave_m, int wn, int tid,
+                                             float* stage) {
+  constexpr int LDW = Staging<BN>::LDW;
+  typedef typename Vec<E>::type E8;
+  const int lane = tid & 63;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    __syncthreads();
+    if (wave_m == half) stage_quads<BN, MI, NJ>(stage, acc, wn, lane);
+    __syncthreads();
+    constexpr int VPR = BN / 16;                           // 8-column pieces of each matrix per row
+#pragma unroll
+    for (int it = 0; it < (BM / 2) * VPR / NT; ++it) {
+      const int v = tid + NT * it;
+      const int lr = v / VPR, cv = (v % VPR) * 8, col = c0 + cv;
+      const int row = m0 + half * (BM / 2) + lr;
+      if (row >= g.M || col >= g.N) continue;              // N is a multiple of 8
+      const float* sp = stage + lr * LDW + cv;
+      const f32x4 g0 = *reinterpret_cast<const f32x4*>(sp), g1 = *reinterpret_cast<const f32x4*>(sp + 4);
+      const f32x4 u0 = *reinterpret_cast<const f32x4*>(sp + BN / 2), u1 = *reinterpret_cast<const f32x4*>(sp + BN / 2 + 4);
+      E8 og, ou, oa;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        og[e] = (E)(e < 4 ? g0[e & 3] : g1[e & 3]);
+        ou[e] = (E)(e < 4 ? u0[e & 3] : u1[e & 3]);
+        oa[e] = (E)glu_f((float)og[e], (float)ou[e]);
+      }
+      E* pg = (E*)g.gu + (int64_t)row * g.gu_ld + col;
+      *reinterpret_cast<E8*>(pg) = og;
+      *reinterpret_cast<E8*>(pg + g.gu_up) = ou;
+      *reinterpret_cast<E8*>((E*)g.C + (int64_t)row * g.ldc + col) = oa;
+    }
+  }
+}
+
 // NW wavefronts: 4 as a 2 x 2 grid, or 8 as 2 (m) x 4 (n), in which case two waves share each SIMD and one
 // wave's loads, LDS traffic and barrier waits overlap the other's MFMAs.
-template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG, int ACC>
+template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG, int ACC, int GLU>
 __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma_kernel(Gemm g, int tiles_m,
                                                                                                         int tiles_n) {
   constexpr int NT = 64 * NW, WN = NW / 2;               // threads; waves along n (2 along m)
@@ -282,6 +343,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / WN) * (BM / 2), wn = (wave % WN) * (BN / WN);
+  static_assert(GLU == 0 || (GLU == 1 && !TA && !TB && !SEG && !ACC) || (GLU == 2 && !TA && TB && !SEG && !ACC), "fused gated unit");
+  const int nb0 = GLU == 1 ? n0 / 2 : n0;                // first column of the tile inside B (GLU = 1: inside each of the two)
 
   f32x16 acc[MI][NJ];
 #pragma unroll
@@ -307,7 +370,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   const int nseg = (SEG && !PAIR) ? g.K / g.kseg : 1;
   const __amdgpu_buffer_rsrc_t rsB = make_rsrc(
       B, (uint32_t)(TB == 1 ? ((int64_t)(nseg - 1) * g.segB + (int64_t)(g.N - 1) * ldb + (SEG ? g.kseg : g.K))
-                            : ((int64_t)(K1 - 1) * ldb + g.N)) * 2u);
+                            : ((int64_t)(K1 - 1) * ldb + g.N + (GLU == 1 ? g.sB : 0))) * 2u);
   // Descriptors of part p >= 1 (the last part has the rows that remain); a part past the last one gets an empty
   // range, so a surplus slab reads zeros.
   auto part_a = [&](int p) {
@@ -322,7 +385,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   };
   __amdgpu_buffer_rsrc_t curA = rsA, curB = rsB;         // PAIR: descriptors of the part whose slabs are being loaded
   const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : voff_rmajor<BM>(lda, tid, m0, g.M);
-  const int voffB = TB == 1 ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2 : voff_rmajor<BN>(ldb, tid, n0, g.N);
+  const int voffB = TB == 1     ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2
+                    : GLU == 1 ? voff_rmajor_two<BN>(ldb, tid, nb0, g.N, (int)g.sB)
+                               : voff_rmajor<BN>(ldb, tid, n0, g.N);
 
   auto fetch = [&](int kt, Frag<BM, NT>& fa0, Frag<BN, NT>& fb0) {
     const int k0 = kt * BK;
@@ -336,7 +401,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       }
       load_kmajor<BN, NT>(fb0, rsB, vo, ldb, n0, k0, g.K, tid);
     } else {
-      load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, n0, k0);
+      load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, nb0, k0);
     }
   };
   constexpr int VA = BM * 8 / NT, VB = BN * 8 / NT;        // 16-byte vectors per thread and slab
@@ -421,19 +486,21 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   }
 
   if (ACC) epilogue_accum<BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
-  else epilogue_store<E, BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
+  else if (GLU == 1) epilogue_glu<E, BM, BN, NT, MI, NJ>(g, acc, m0, nb0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
+  else epilogue_store<E, BM, BN, NT, MI, NJ, GLU>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
 }
 
-template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG, int ACC> hipError_t launch2(hipStream_t st, const Gemm& g) {
+template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG, int ACC, int GLU = 0>
+hipError_t launch2(hipStream_t st, const Gemm& g) {
   constexpr size_t SMEM_BYTES = 2 * (slab_elems(BM) + slab_elems(BN)) * sizeof(bf16);
   static bool configured = false;
-  auto kern = gemm_mfma_kernel<E, BM, BN, NW, TA, TB, SEG, ACC>;
+  auto kern = gemm_mfma_kernel<E, BM, BN, NW, TA, TB, SEG, ACC, GLU>;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int tiles_m = (int)cdiv(g.M, BM), tiles_n = (int)cdiv(g.N, BN);
+  const int tiles_m = (int)cdiv(g.M, BM), tiles_n = (int)cdiv(g.N, GLU == 1 ? BN / 2 : BN);   // a gate|up tile holds BN/2 columns of each
   dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)g.batch), blk(64 * NW);
   hipLaunchKernelGGL(kern, grid, blk, SMEM_BYTES, st, g, tiles_m, tiles_n);
   return hipGetLastError();
@@ -444,6 +511,8 @@ template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG> hipError_
 }
 
 template <typename E, int BM, int BN, int NW> hipError_t gemm_mfma_tile(hipStream_t st, const Gemm& g) {
+  if (g.glu == 1) return launch2<E, BM, BN, NW, 0, 0, 0, 0, 1>(st, g);
+  if (g.glu == 2) return launch2<E, BM, BN, NW, 0, 1, 0, 0, 2>(st, g);
   if (g.nx) return launch<E, BM, BN, NW, 1, 0, 1>(st, g);
   if (g.kseg) return g.transA ? launch<E, BM, BN, NW, 1, 1, 1>(st, g) : launch<E, BM, BN, NW, 0, 1, 1>(st, g);
   if (!g.transA && !g.transB) return launch<E, BM, BN, NW, 0, 0, 0>(st, g);

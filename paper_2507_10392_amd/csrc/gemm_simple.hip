@@ -123,6 +123,14 @@ Gemm part_of(const Gemm& g, int p) {
 // two-part K range done in extra passes).
 hipError_t gemm_one(hipStream_t st, DType dt, const Gemm& g, int force) {
   if (gemm_select(dt, g, force) == GEMM_MFMA) return gemm_mfma(st, dt, g);   // rotation fused into its epilogue
+  if (g.glu) {   // gated unit: the plain product(s), then the activation kernel over the dense [gate | up] rows
+    Gemm p = g;
+    p.glu = 0; p.gu = nullptr;
+    if (g.glu == 1) { p.batch = 2; p.C = g.gu; p.ldc = g.gu_ld; p.sC = g.gu_up; }
+    const hipError_t e = gemm_one(st, dt, p, force);
+    if (e != hipSuccess) return e;
+    return g.glu == 1 ? swiglu_fwd(st, dt, g.M, g.N, g.gu, g.C) : swiglu_bwd(st, dt, g.M, g.N, g.gu, g.C, g.gu);
+  }
   if (g.nx) {   // multi-part K range: one plain product per part
     for (int p = 0; p <= g.nx; ++p) {
       const hipError_t e = gemm_simple(st, dt, part_of(g, p));
@@ -163,6 +171,7 @@ bool split_rows(const Gemm& g, std::vector<Gemm>& parts) {
     p.A = (const char*)g.A + r0 * g.lda * 2;
     p.C = (char*)g.C + r0 * g.ldc * (g.c_f32_accum ? 4 : 2);
     if (g.resid) p.resid = (const char*)g.resid + r0 * g.ldr * 2;
+    if (g.gu) p.gu = (char*)g.gu + r0 * g.gu_ld * 2;
     parts.push_back(p);
   }
   return true;
@@ -196,6 +205,11 @@ bool gemm_splits(DType dt, const Gemm& g) {
 }
 
 hipError_t gemm(hipStream_t st, DType dt, const Gemm& g, int force) {
+  if (g.glu) {   // the fall-back's activation kernel walks dense rows
+    if ((g.glu != 1 && g.glu != 2) || !g.gu || !g.C || g.batch != 1 || g.transA || (g.glu == 1) == (g.transB != 0) ||
+        g.c_f32_accum || g.bias || g.resid || g.rope || g.kseg || g.nx || g.ldc != g.N || g.gu_ld != 2ll * g.N || g.gu_up != g.N)
+      return hipErrorInvalidValue;
+  }
   if (dt != F32 && force != GEMM_SIMPLE && !gemm_mfma_supported(dt, g)) {
     std::vector<Gemm> parts;
     if (g.nx) {   // the parts of a multi-part weight gradient on their own, each cut further if it has to be

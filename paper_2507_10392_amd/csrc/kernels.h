@@ -20,6 +20,16 @@ namespace zs {
 //   rope != NULL (c_f32_accum = 0 only): for batch indices z < rope_batches the adjacent column pairs of
 //             every head (rope_d columns wide) of C are rotated, after bias and residual and before the
 //             result is rounded, by the angle table[(row % rope_S) * rope_d/2 + pair] (cos, sin).
+//   glu != 0 (16-bit or float, transA = 0, batch = 1, c_f32_accum = 0, no bias / residual / rotation / segments):
+//             the gated FFN unit fused into the product.  gu is [M, 2N] = [gate | up] with row stride gu_ld and the
+//             up half gu_up columns after the gate half; the dispatcher gemm() takes the dense layout only
+//             (gu_ld = 2N, gu_up = N, ldc = N).
+//             glu = 1 (transB = 0): B and B + sB are the gate and up projections [K,N]; the call writes both
+//               products, rounded, to gu and silu(gate) * up of the ROUNDED values to C[M,N]: what the batched
+//               product followed by swiglu_fwd leaves.
+//             glu = 2 (transB = 1): the product is da[M,N]; the call replaces (gate, up) in gu by (dgate, dup).
+//               C is scratch of [M,N] elements whose content is unspecified afterwards (the fused kernel leaves it
+//               alone and uses da unrounded).
 constexpr int GEMM_MAX_PARTS = 16;   // parts of a multi-part K range
 struct Gemm {
   int M = 0, N = 0, K = 0, transA = 0, transB = 0;
@@ -33,6 +43,7 @@ struct Gemm {
   int kseg = 0; int64_t segB = 0;
   int nx = 0; const void* Ax[GEMM_MAX_PARTS - 1] = {}; const void* Bx[GEMM_MAX_PARTS - 1] = {};
   const float2* rope = nullptr; int rope_S = 0, rope_d = 0, rope_batches = 0;
+  int glu = 0; void* gu = nullptr; int64_t gu_ld = 0, gu_up = 0;
 };
 enum GemmImpl { GEMM_AUTO = 0, GEMM_SIMPLE = 1, GEMM_MFMA = 2 };
 // Returns which implementation a call with these arguments runs (GEMM_SIMPLE or GEMM_MFMA).

@@ -77,6 +77,20 @@ int stage_op_wgrad_parts(void* stream, int32_t dtype, int32_t M, int32_t N, int3
   return rc(e);
 }
 
+int stage_op_gemm_glu(void* stream, int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void* A, int64_t lda,
+                      const void* B, int64_t ldb, int64_t sB, void* a, void* gu, int32_t impl) {
+  if (!dt_ok(dtype) || (mode != 1 && mode != 2) || M < 1 || N < 1 || K < 1 || !A || !B || !a || !gu) return STAGE_ERR_ARG;
+  if (impl < 0 || impl > 4) return STAGE_ERR_ARG;
+  Gemm g;
+  g.M = M; g.N = N; g.K = K; g.transB = mode == 2; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.sB = mode == 1 ? sB : 0;
+  g.C = a; g.ldc = N; g.glu = mode; g.gu = gu; g.gu_ld = 2ll * N; g.gu_up = N;
+  if (impl >= GEMM_MFMA && !gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
+  if (impl > GEMM_MFMA) gemm_mfma_force_tile(impl - GEMM_MFMA);
+  const hipError_t e = gemm((hipStream_t)stream, (DType)dtype, g, impl > GEMM_MFMA ? GEMM_MFMA : impl);
+  gemm_mfma_force_tile(0);
+  return rc(e);
+}
+
 int stage_op_gemm(void* stream, int32_t dtype, int32_t transA, int32_t transB, int32_t M, int32_t N, int32_t K,
                   const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32_accum,
                   const void* bias, const void* resid, int64_t ldr, int32_t batch, int64_t sA, int64_t sB, int64_t sC,

@@ -404,8 +404,10 @@ bool do_gemm(stage_t* s, const Gemm& g) {
   const int impl = gemm_select(dt_of(s), g, GEMM_AUTO);
   static const char* names[2][4] = {{"gemm_simple_nn", "gemm_simple_nt", "gemm_simple_tn", "gemm_simple_tt"},
                                     {"gemm_mfma_nn", "gemm_mfma_nt", "gemm_mfma_tn", "gemm_mfma_tt"}};
-  const char* cls = names[impl == GEMM_MFMA || gemm_splits(dt_of(s), g)][g.transA * 2 + g.transB];
-  const double flops = 2.0 * g.M * g.N * g.K * g.batch;
+  const bool mfma = impl == GEMM_MFMA || gemm_splits(dt_of(s), g);
+  // the products that apply the gated unit in their store are kernels of their own and are timed as such
+  const char* cls = mfma && g.glu == 1 ? "gemm_mfma_nn_glu" : mfma && g.glu == 2 ? "gemm_mfma_nt_glu" : names[mfma][g.transA * 2 + g.transB];
+  const double flops = 2.0 * g.M * g.N * g.K * (g.glu == 1 ? 2 : g.batch);
   return run(s, cls, flops, 0.0, [&] { return gemm(s->st, dt_of(s), g, GEMM_AUTO); });
 }
 
@@ -446,14 +448,14 @@ bool layer_forward(stage_t* s, int l, const char* x_in, LayerActs& A, char* y) {
                    : norm_fwd(s->st, dt, 1, T, H, A.x2, W("rms2.g"), nullptr, s->cfg.norm_eps, A.n2, A.rstd2, nullptr); }))
     return false;
   g = Gemm();
-  g.M = T; g.K = H; g.A = A.n2; g.lda = H; g.C = A.ff;
-  if (gpt) { g.N = F; g.B = W("W1"); g.ldb = F; g.ldc = F; g.bias = W("b1"); }
-  else { g.N = F; g.B = W("Wg"); g.ldb = F; g.ldc = 2 * F; g.batch = 2; g.sB = (int64_t)H * F; g.sC = F; }
+  g.M = T; g.K = H; g.A = A.n2; g.lda = H; g.N = F; g.ldb = F;
+  if (gpt) { g.B = W("W1"); g.C = A.ff; g.ldc = F; g.bias = W("b1"); }
+  else {   // gate and up projections in one product whose store applies the gated unit: ff = [gate | up], a = silu(gate) * up
+    g.B = W("Wg"); g.sB = (int64_t)H * F; g.C = A.a; g.ldc = F; g.glu = 1; g.gu = A.ff; g.gu_ld = 2 * F; g.gu_up = F;
+  }
   if (!do_gemm(s, g)) return false;
   const double tfb = (double)T * F * h.E;
-  if (!run(s, "activation", 0, gpt ? 2 * tfb : 3 * tfb, [&] {
-        return gpt ? gelu_fwd(s->st, dt, (int64_t)T * F, A.ff, A.a) : swiglu_fwd(s->st, dt, T, F, A.ff, A.a); }))
-    return false;
+  if (gpt && !run(s, "activation", 0, 2 * tfb, [&] { return gelu_fwd(s->st, dt, (int64_t)T * F, A.ff, A.a); })) return false;
   if (!y) return true;
   g = Gemm();
   g.M = T; g.N = H; g.K = F; g.A = A.a; g.lda = F; g.B = gpt ? W("W2") : W("Wd"); g.ldb = H; g.C = y; g.ldc = H;
@@ -513,6 +515,8 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   // FFN down projection: da = dy Wd^T ; dWd += a^T dy
   g.M = T; g.N = F; g.K = H; g.A = dy; g.lda = H; g.B = gpt ? W("W2") : W("Wd"); g.ldb = H; g.transB = 1;
   g.C = pl.gF1; g.ldc = F;
+  // Llama: the store turns (gate, up), saved in ff, into (dgate, dup) in place; da itself is not kept
+  if (!gpt) { g.glu = 2; g.gu = A.ff; g.gu_ld = 2 * F; g.gu_up = F; }
   if (!do_gemm(s, g)) return false;
   g = Gemm();
   g.M = F; g.N = H; g.K = T; g.A = A.a; g.lda = F; g.transA = 1; g.B = dy; g.ldb = H;
@@ -520,10 +524,8 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
   if (!wgrad(g, &LayerActs::a, [&](int i) { return wg.dy_x[i]; })) return false;
   if (gpt && !colsum(s, p + "b2", H, dy, H, nullptr, nullptr, nullptr)) return false;
 
-  // activation backward, in place over the saved pre-activations
-  if (!run(s, "activation", 0, gpt ? 3 * tfb : 5 * tfb, [&] {
-        return gpt ? gelu_bwd(s->st, dt, (int64_t)T * F, A.ff, pl.gF1, A.ff)
-                   : swiglu_bwd(s->st, dt, T, F, A.ff, pl.gF1, A.ff); }))
+  // GELU backward, in place over the saved pre-activations
+  if (gpt && !run(s, "activation", 0, 3 * tfb, [&] { return gelu_bwd(s->st, dt, (int64_t)T * F, A.ff, pl.gF1, A.ff); }))
     return false;
   const char* dff = A.ff;   // dz [T,F] or [dgate | dup] [T,2F]
 

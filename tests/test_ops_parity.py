@@ -324,6 +324,56 @@ def test_gelu_and_swiglu(gpu_device, dtype):
     assert rel_err(back(dgu), want) <= TOL[dtype]
 
 
+GLU_CASES = [(264, 136, 72), (512, 384, 128), (300, 1376, 200), (64, 8, 8), (2048, 8704, 64)]   # (M, N, K); the last: whole rounds of big tiles + a tail of small ones
+
+
+@pytest.mark.parametrize("impl", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
+@pytest.mark.parametrize("case", GLU_CASES, ids=lambda c: "x".join(str(v) for v in c))
+def test_gemm_with_fused_gated_unit(gpu_device, dtype, impl, case):
+    """Gate and up projections with the gated unit in the store, and the down projection's input gradient turned into
+    (dgate, dup) in the store, against the fp64 formulas of the Llama-style FFN; the forward must also leave exactly
+    the bits of the batched product followed by the activation kernel."""
+    M, N, K = case
+    print(f"[case] gemm_glu dtype={dtype} impl={impl} M={M} N={N} K={K}", flush=True)
+    if dtype == 0 and impl >= 2:
+        pytest.skip("the MFMA kernel is 16-bit")
+    rng = np.random.default_rng(97)
+    td = TD[dtype]
+    x = draw(rng, (M, K), dtype)
+    W = draw(rng, (2, K, N), dtype, K ** -0.5 * 2.0)          # pre-activations of order 2: the sigmoid is far from linear
+    x_d, W_d = dev(x, td), dev(W, td)
+    a = torch.full((M, N), 7.0, dtype=td, device="cuda")
+    gu = torch.full((M, 2 * N), 7.0, dtype=td, device="cuda")
+    zs.ops.gemm_glu(st(), dtype, 1, M, N, K, x_d, K, W_d, N, K * N, a, gu, impl)
+    g64, u64 = x.astype(np.float64) @ W[0].astype(np.float64), x.astype(np.float64) @ W[1].astype(np.float64)
+    assert rel_err(back(gu)[:, :N], g64) <= TOL[dtype] and rel_err(back(gu)[:, N:], u64) <= TOL[dtype]
+    assert rel_err(back(a), g64 * so.sigmoid(g64) * u64) <= 2 * TOL[dtype]
+    # the unfused route: batched product into [gate | up], then the activation kernel
+    gu2 = torch.empty_like(gu)
+    a2 = torch.empty_like(a)
+    zs.ops.gemm(st(), dtype, 0, 0, M, N, K, x_d, K, W_d, N, gu2, 2 * N, 0, None, None, 0, 2, 0, K * N, N, 0, 0, 0, min(impl, 2))
+    zs.ops.swiglu(st(), dtype, M, N, gu2, None, a2, 0)
+    torch.cuda.synchronize()
+    if dtype != 0:
+        assert torch.equal(gu.view(torch.int16), gu2.view(torch.int16)) and torch.equal(a.view(torch.int16), a2.view(torch.int16))
+    else:
+        assert torch.equal(gu, gu2) and torch.equal(a, a2)
+
+    # backward: dy [M, K2] through Wd stored [N, K2]
+    K2 = K
+    dy = draw(rng, (M, K2), dtype)
+    Wd = draw(rng, (N, K2), dtype, K2 ** -0.5)
+    gu0 = back(gu)                                              # the saved (rounded) pre-activations
+    scratch = torch.empty(M, N, dtype=td, device="cuda")
+    zs.ops.gemm_glu(st(), dtype, 2, M, N, K2, dev(dy, td), K2, dev(Wd, td), K2, 0, scratch, gu, impl)
+    da = dy.astype(np.float64) @ Wd.astype(np.float64).T
+    gt, up = gu0[:, :N], gu0[:, N:]
+    sg = so.sigmoid(gt)
+    want = np.concatenate([da * up * sg * (1.0 + gt * (1.0 - sg)), da * gt * sg], axis=1)
+    assert rel_err(back(gu), want) <= 2 * TOL[dtype]
+
+
 # ----------------------------------------------------------------------------- attention
 
 ATTN_CASES = [(2, 128, 4, 64), (1, 256, 4, 128), (2, 200, 3, 128), (1, 1, 2, 128), (1, 65, 1, 128), (1, 576, 2, 128)]
