@@ -27,13 +27,14 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (256 CUs x 4 SIMDs x 1024 flop/clk x 2.4 GHz)
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per launch of a workload's large kernel classes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# HBM-side bytes per call of the GEMM dispatcher (one or two kernel launches) of a workload's large kernel classes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # each counter scaled by what it reads for a copy of known size (profiles/gemm_wgrad_C3_hbm_traffic.txt: the
 # unpaired weight-gradient launches, `bench.py --traffic-probe`; profiles/stage_step_C3_mfma_busy_hbm_bytes.txt: one
 # step of this file).  Keys: workload, kernel class, weight-gradient group size (None: does not depend on it).
 # Anything that was not measured reports null.
-MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6, ("C3", "gemm_mfma_tn", 8): 5947.6e6,
-                    ("C3", "gemm_mfma_nn", None): 782.9e6, ("C3", "gemm_mfma_nt", None): 682.1e6}
+MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6, ("C3", "gemm_mfma_tn", 8): 5924.6e6,
+                    ("C3", "gemm_mfma_nn", None): 533.2e6, ("C3", "gemm_mfma_nt", None): 665.7e6,
+                    ("C3", "gemm_mfma_nn_glu", None): 1407.6e6, ("C3", "gemm_mfma_nt_glu", None): 984.7e6}
 
 
 def measured_traffic(workload, kernel, cfg):
