@@ -20,6 +20,9 @@ TOL = {0: 1e-4, 1: 2e-2, 2: 3e-3}   # fp16 rounds 8 times finer than bf16
 def rel_err(a, o):
     a = np.asarray(a, dtype=np.float64)
     o = np.asarray(o, dtype=np.float64)
+    if o.size == 0:                       # an empty optimizer shard: nothing to differ
+        assert a.size == 0
+        return 0.0
     den = np.abs(o).max()
     if den == 0.0:
         return float(np.abs(a).max())
@@ -34,6 +37,8 @@ def update_err(a, o, p_new, nsteps=1):
     an update of 1e-4), once per optimizer step taken.  That floor is subtracted before the relative
     error is formed.
     """
+    if np.size(o) == 0:
+        return 0.0
     floor = nsteps * 0.5 * np.spacing(np.abs(p_new).astype(np.float32)).astype(np.float64) * 1.01
     d = np.maximum(np.abs(a - o) - floor, 0.0)
     return float(d.max() / np.abs(o).max())
@@ -144,8 +149,12 @@ def log_report(title, rows):
                 f.write(f"    {name:28s} {e:.3e}\n")
 
 
-def compare_step(cfg, gpu, ora, tol, report=None):
-    """Checks outputs, input gradients, loss and every gradient segment; returns the worst error."""
+def compare_step(cfg, gpu, ora, tol, report=None, zero_scale=None):
+    """Checks outputs, input gradients, loss and every gradient segment; returns the worst error.
+
+    A segment whose oracle gradient is exactly zero must be exactly zero on the GPU, unless zero_scale is given:
+    then the zero comes from a cancellation that only exact arithmetic makes complete (softmax over a single key:
+    dS = P (dP - sum P dP) with P = 1), and the GPU's values must stay below tol * zero_scale."""
     worst = 0.0
 
     def chk(name, a, o):
@@ -169,7 +178,10 @@ def compare_step(cfg, gpu, ora, tol, report=None):
         o = ora["grad"][off:off + r * c]
         a = gpu["grad"][off:off + r * c]
         if np.abs(o).max() == 0.0:
-            assert np.abs(a).max() == 0.0, f"{name}: oracle gradient is exactly zero, GPU's is not"
+            if zero_scale is None:
+                assert np.abs(a).max() == 0.0, f"{name}: oracle gradient is exactly zero, GPU's is not"
+            else:
+                assert np.abs(a).max() <= tol * zero_scale, f"{name}: {np.abs(a).max():.3e} where the oracle has zero"
             continue
         chk("grad " + name, a, o)
     return worst

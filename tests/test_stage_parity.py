@@ -162,3 +162,40 @@ def test_second_step_and_determinism(gpu_device):
     q2, n2, w2 = so.stage_optimizer_step(cfg, q1, runs[0][2], n1, w1, 2, (b, e))
     assert rel_err(runs[0][4], n2) <= 1e-6 and rel_err(runs[0][5], w2) <= 1e-6
     assert update_err(runs[0][3].astype(np.float64) - p0, q2 - p0, q2, nsteps=2) <= 2e-5
+
+
+@pytest.mark.parametrize("name", ["C3t", "C1", "C5t"])
+@pytest.mark.parametrize("shard", ["empty", "whole", "odd"])
+def test_optimizer_shard_edges(gpu_device, name, shard):
+    """Degenerate optimizer ranges: an empty shard (the rank owns nothing of this stage: the step only drops the
+    gradients), the whole parameter vector, and a range whose ends are not multiples of the kernels' vector width."""
+    cfg = get_config(name).with_(num_microbatches=2)
+    from oracle import stage_oracle as so
+    P = so.n_params(cfg)
+    b, e = {"empty": (1000, 1000), "whole": (0, P), "odd": (5, P - 3)}[shard]
+    print(f"[case] shard edge {name} [{b}, {e})", flush=True)
+    inp = make_inputs(cfg, perturbed=True)
+    g = GpuStage(cfg, inp, shard=(b, e))
+    gpu = g.run_microbatches(inp)
+    res = g.step(1)
+    g.stage.close()
+    ora = oracle_step(cfg, inp)
+    compare_step(cfg, gpu, ora, TOL[cfg.dtype])
+    compare_optimizer(cfg, inp, (b, e), gpu["grad"], res, ora["grad"], TOL[cfg.dtype])
+
+
+@pytest.mark.parametrize("name,seq,mb,M", [("C3t", 1, 1, 1), ("C1", 1, 1, 2), ("C5t", 1, 8, 1), ("L1", 3, 1, 1), ("C2t", 8, 1, 1)])
+def test_stage_step_with_the_shortest_sequences(gpu_device, name, seq, mb, M):
+    """One token per sequence (the attention of a token with itself only), one token per microbatch (products with a
+    single row, norms and column sums over one row), and a single microbatch."""
+    cfg = get_config(name).with_(seq=seq, microbatch=mb, num_microbatches=M)
+    print(f"[case] shortest sequences {name} S={seq} mb={mb} M={M}", flush=True)
+    inp = make_inputs(cfg, perturbed=True)
+    g = GpuStage(cfg, inp)
+    gpu = g.run_microbatches(inp)
+    res = g.step(1)
+    g.stage.close()
+    ora = oracle_step(cfg, inp)
+    # S = 1: the gradients of the Q and K projections vanish by an exact cancellation in the oracle
+    compare_step(cfg, gpu, ora, TOL[cfg.dtype], zero_scale=np.abs(ora["grad"]).max() if seq == 1 else None)
+    compare_optimizer(cfg, inp, g.shard, gpu["grad"], res, ora["grad"], TOL[cfg.dtype])
