@@ -338,9 +338,118 @@ hipError_t colsum_partial(hipStream_t st, DType dt, int T, int N, const void* a,
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ norm backward + partial sums, row in registers
+// norm_bwd_reg_kernel and the two colsum_kernel passes over the same rows in one kernel: dn and x are read once.
+// One workgroup per row block (the blocks of colsum_partial); wave q walks rows r0+q, r0+q+4, ... of the block,
+// computes dx of each row as norm_bwd_reg_kernel does and keeps the running column sums of dn*xhat (and dn) of
+// its rows in registers; the four waves' sums are then added in the order 0..3 through LDS.  That is colsum_kernel's
+// order of additions per column, so the partial sums do not depend on which of the two routes ran.
+template <typename T, int KIND, int J>
+__global__ __launch_bounds__(256) void norm_bwd_partials_reg_kernel(int Trows, const T* __restrict__ dn, const T* __restrict__ x,
+                                                                    const T* __restrict__ g, const float* __restrict__ rstd,
+                                                                    const float* __restrict__ mean, const T* dres, T* dx,
+                                                                    float* __restrict__ part_g, float* __restrict__ part_b,
+                                                                    int rows_per_blk) {
+  constexpr int V = Vec<T>::N, H = 64 * V * J;
+  extern __shared__ float red[];            // [3][H]: the sums of waves 1..3, used for part_g and then for part_b
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int r0 = blockIdx.x * rows_per_blk;
+  const int r1 = min(Trows, r0 + rows_per_blk);
+  float pg[J][V], pb[KIND == 0 ? J : 1][V];
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+#pragma unroll
+    for (int i = 0; i < V; ++i) { pg[j][i] = 0.f; if (KIND == 0) pb[j][i] = 0.f; }
+  for (int row = r0 + q; row < r1; row += 4) {
+    const float r = rstd[row];
+    const float mu = (KIND == 0) ? mean[row] : 0.f;
+    const int64_t off = (int64_t)row * H;
+    typename Vec<T>::type xv[J], dv[J], rv[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int c = (j * 64 + lane) * V;
+      xv[j] = *reinterpret_cast<const typename Vec<T>::type*>(x + off + c);
+      dv[j] = *reinterpret_cast<const typename Vec<T>::type*>(dn + off + c);
+      if (dres) rv[j] = *reinterpret_cast<const typename Vec<T>::type*>(dres + off + c);
+    }
+    float su = 0.f, sux = 0.f;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int c = (j * 64 + lane) * V;
+      float gg[V];
+      load_vec(g + c, gg);
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        const float d = to_f(dv[j][i]), xx = to_f(xv[j][i]);
+        const float u = d * gg[i];
+        su += u;
+        sux += u * (xx - mu) * r;
+        pg[j][i] += d * ((xx - mu) * r);
+        if (KIND == 0) pb[j][i] += d;
+      }
+    }
+    const float mu_u = (KIND == 0) ? wave_sum(su) / (float)H : 0.f;
+    const float mu_ux = wave_sum(sux) / (float)H;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int c = (j * 64 + lane) * V;
+      float o[V], gg[V];
+      load_vec(g + c, gg);
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        const float u = to_f(dv[j][i]) * gg[i];
+        o[i] = r * (u - mu_u - (to_f(xv[j][i]) - mu) * r * mu_ux) + (dres ? to_f(rv[j][i]) : 0.f);
+      }
+      store_vec(dx + off + c, o);
+    }
+  }
+  // cross-wave sums in the order 0..3, first of dn*xhat, then (LayerNorm) of dn
+#pragma unroll
+  for (int pass = 0; pass < (KIND == 0 ? 2 : 1); ++pass) {
+    if (pass) __syncthreads();
+    if (q > 0) {
+#pragma unroll
+      for (int j = 0; j < J; ++j)
+#pragma unroll
+        for (int i = 0; i < V; ++i) red[(q - 1) * H + (j * 64 + lane) * V + i] = pass ? pb[j][i] : pg[j][i];
+    }
+    __syncthreads();
+    if (q == 0) {
+      float* p = (pass ? part_b : part_g) + (int64_t)blockIdx.x * H;
+#pragma unroll
+      for (int j = 0; j < J; ++j) {
+        const int c = (j * 64 + lane) * V;
+        float o[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+          o[i] = (((pass ? pb[j][i] : pg[j][i]) + red[c + i]) + red[H + c + i]) + red[2 * H + c + i];
+#pragma unroll
+        for (int i = 0; i < V; ++i) p[c + i] = o[i];
+      }
+    }
+  }
+}
+
 hipError_t norm_bwd_partials(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x, const void* g,
                              const float* rstd, const float* mean, const void* dres, void* dx, float* part_g,
                              float* part_b, int nblk) {
+  const int J = reg_chunks(dt, H);
+  if (J && nblk >= 1 && part_g && (kind != 0 || part_b)) {   // one pass over the rows
+    const int rows_per_blk = (int)cdiv(T, nblk);
+    dim3 grid((unsigned)nblk), blk(256);
+    const size_t smem = 3 * (size_t)H * sizeof(float);
+#define LR(TT, KK, JJ) \
+  hipLaunchKernelGGL((norm_bwd_partials_reg_kernel<TT, KK, JJ>), grid, blk, smem, st, T, (const TT*)dn, (const TT*)x, (const TT*)g, rstd, mean, (const TT*)dres, (TT*)dx, part_g, part_b, rows_per_blk)
+#define LJ(TT, KK) \
+  switch (J) { case 1: LR(TT, KK, 1); break; case 2: LR(TT, KK, 2); break; case 4: LR(TT, KK, 4); break; \
+               case 8: LR(TT, KK, 8); break; default: LR(TT, KK, 10); break; }
+    if (dt == F32) { if (kind == 0) { LJ(float, 0) } else { LJ(float, 1) } }
+    else if (dt == BF16) { if (kind == 0) { LJ(bf16, 0) } else { LJ(bf16, 1) } }
+    else { if (kind == 0) { LJ(f16, 0) } else { LJ(f16, 1) } }
+#undef LJ
+#undef LR
+    return hipGetLastError();
+  }
   hipError_t e = colsum_partial(st, dt, T, H, dn, H, x, H, rstd, kind == 0 ? mean : nullptr, part_g, nblk);
   if (e == hipSuccess && kind == 0) e = colsum_partial(st, dt, T, H, dn, H, nullptr, H, nullptr, nullptr, part_b, nblk);
   if (e == hipSuccess) e = norm_bwd(st, dt, kind, T, H, dn, x, g, rstd, mean, dres, dx);

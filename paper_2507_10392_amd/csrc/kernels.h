@@ -66,7 +66,8 @@ hipError_t norm_bwd(hipStream_t st, DType dt, int kind, int T, int H, const void
                     const float* rstd, const float* mean, const void* dres, void* dx);
 // norm_bwd plus the partial column sums of the gain (and, for LayerNorm, bias) gradient over row blocks of
 // cdiv(T, nblk) rows: part_g[blk, c] = sum_t dn * xhat, part_b[blk, c] = sum_t dn (part_b may be NULL for
-// RMSNorm): colsum_partial and norm_bwd one after the other.
+// RMSNorm).  For the row lengths of the register-resident kernels this is ONE kernel that reads dn and x once (a
+// workgroup per row block); otherwise colsum_partial and norm_bwd one after the other.  Same sums either way.
 hipError_t norm_bwd_partials(hipStream_t st, DType dt, int kind, int T, int H, const void* dn, const void* x,
                              const void* g, const float* rstd, const float* mean, const void* dres, void* dx,
                              float* part_g, float* part_b, int nblk);

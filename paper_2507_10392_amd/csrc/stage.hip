@@ -124,7 +124,7 @@ struct Bump {
 
 
 
-constexpr int MAX_NBLK = 128;
+constexpr int MAX_NBLK = 256;   // row blocks of the vector-gradient partial sums: one workgroup each in the fused norm backward, 256 CUs
 struct Plan {
   std::vector<LayerActs> acts;      // recompute ? 1 : M*L   (index mb*L + l)
   std::vector<char*> stash;         // recompute: M*L layer inputs; offload: 2*L (index device_slot*L + l)
