@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0
 # unpaired weight-gradient launches, `bench.py --traffic-probe`; profiles/stage_step_C3_mfma_busy_hbm_bytes.txt: one
 # step of this file).  Keys: workload, kernel class, weight-gradient group size (None: does not depend on it).
 # Anything that was not measured reports null.
-MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6, ("C3", "gemm_mfma_tn", 8): 5924.6e6,
-                    ("C3", "gemm_mfma_nn", None): 533.2e6, ("C3", "gemm_mfma_nt", None): 665.7e6,
-                    ("C3", "gemm_mfma_nn_glu", None): 1407.6e6, ("C3", "gemm_mfma_nt_glu", None): 984.7e6}
+MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6, ("C3", "gemm_mfma_tn", 8): 5866.1e6,
+                    ("C3", "gemm_mfma_nn", None): 533.2e6, ("C3", "gemm_mfma_nt", None): 665.2e6,
+                    ("C3", "gemm_mfma_nn_glu", None): 1413.0e6, ("C3", "gemm_mfma_nt_glu", None): 983.7e6}
 
 
 def measured_traffic(workload, kernel, cfg):
