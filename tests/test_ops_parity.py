@@ -276,6 +276,15 @@ def test_norm_fwd_bwd(gpu_device, dtype, kind, T, H, nblk):
     assert rel_err(back(pg).sum(axis=0), dg_o) <= 2e-5
     if kind == 0:
         assert rel_err(back(pb).sum(axis=0), db_o) <= 2e-5
+    # every row block on its own: block k holds the rows [k*rpb, (k+1)*rpb) and nothing else
+    rpb = -(-T // nblk)
+    prod = dn.astype(np.float64) * cache[0]
+    scale = max(np.abs(dg_o).max(), 1e-30)
+    for k in range(nblk):
+        rows = slice(k * rpb, min(T, (k + 1) * rpb))
+        assert np.abs(back(pg)[k] - prod[rows].sum(axis=0)).max() <= 2e-5 * scale
+        if kind == 0:
+            assert np.abs(back(pb)[k] - dn[rows].astype(np.float64).sum(axis=0)).max() <= 2e-5 * max(np.abs(db_o).max(), 1e-30)
 
 
 # ----------------------------------------------------------------------------- RoPE, activations
