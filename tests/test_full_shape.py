@@ -1,7 +1,8 @@
 """GPU checks at the benchmark's full shapes, in the launch configuration bench.py times.
 
-One decoder layer and one microbatch of the 7B-class (C3) and 1.3B-class (C2) stages are compared
-with the oracle element by element (the oracle needs about ten seconds per layer on the host);
+One decoder layer and one microbatch of the 7B-class (C3), 1.3B-class (C2) and 13B-class (C4a) stages, and of
+the last stage with its embedding, LM head and loss (C5), are compared with the oracle element by element (the
+oracle needs ten to thirty seconds per case on the host);
 whole heads of the full-size attention are compared with the oracle's attention; and properties
 that hold at any size (bit-identical repeats, recompute neutrality, two equal microbatches
 accumulate to exactly twice one) are checked on a full-shape stage.
@@ -18,7 +19,7 @@ from workloads import get_config, make_inputs, round_bf16
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,dtype", [("C3", 1), ("C2", 1), ("C3", 2)])
+@pytest.mark.parametrize("name,dtype", [("C3", 1), ("C2", 1), ("C3", 2), ("C4a", 1), ("C5", 1)])
 def test_one_layer_one_microbatch_at_full_shape(gpu_device, name, dtype):
     cfg = get_config(name).with_(layers=1, num_microbatches=1, shard_num=1, shard_den=1, dtype=dtype)
     print(f"[case] full-shape single layer {name} dtype={dtype}: T={cfg.tokens} H={cfg.hidden} F={cfg.ffn}", flush=True)
