@@ -194,3 +194,10 @@ def test_ops_reject_bad_arguments_on_the_host():
     assert L.stage_op_adamw(None, 0, 8, 0, fake, None, fake, fake, fake, 1e-4, 0.9, 0.999, 1e-8, 0.01, 0, 1.0) == zs.STAGE_ERR_ARG
     assert L.stage_op_norm_fwd(None, 1, 1, 4, 12, fake, fake, None, 1e-5, fake, fake, None) == zs.STAGE_ERR_ARG
     assert L.stage_op_attention_fwd(None, 1, 1, 16, 1, 12, fake, fake, fake, 12, fake, 12, fake, 0) == zs.STAGE_ERR_ARG
+    # fused gated unit: unknown mode, missing buffer, and a forced MFMA kernel with float or unaligned arguments
+    glu = L.stage_op_gemm_glu
+    assert glu(None, 1, 3, 8, 8, 8, fake, 8, fake, 8, 64, fake, fake, 0) == zs.STAGE_ERR_ARG
+    assert glu(None, 1, 1, 8, 8, 8, fake, 8, fake, 8, 64, fake, None, 0) == zs.STAGE_ERR_ARG
+    assert glu(None, 0, 1, 8, 8, 8, fake, 8, fake, 8, 64, fake, fake, 2) == zs.STAGE_ERR_ARG
+    assert glu(None, 1, 1, 8, 12, 8, fake, 8, fake, 12, 96, fake, fake, 2) == zs.STAGE_ERR_ARG
+    assert glu(None, 1, 2, 8, 8, 8, fake, 8, fake, 8, 0, fake, fake, 5) == zs.STAGE_ERR_ARG
