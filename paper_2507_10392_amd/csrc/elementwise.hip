@@ -351,7 +351,7 @@ __global__ __launch_bounds__(256) void norm_bwd_partials_reg_kernel(int Trows, c
                                                                     float* __restrict__ part_g, float* __restrict__ part_b,
                                                                     int rows_per_blk) {
   constexpr int V = Vec<T>::N, H = 64 * V * J;
-  extern __shared__ float red[];            // [3][H]: the sums of waves 1..3, used for part_g and then for part_b
+  extern __shared__ __align__(16) float red[];   // [3][H]: the sums of waves 1..3, used for part_g and then for part_b
   const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
   const int r0 = blockIdx.x * rows_per_blk;
   const int r1 = min(Trows, r0 + rows_per_blk);
@@ -407,11 +407,19 @@ __global__ __launch_bounds__(256) void norm_bwd_partials_reg_kernel(int Trows, c
 #pragma unroll
   for (int pass = 0; pass < (KIND == 0 ? 2 : 1); ++pass) {
     if (pass) __syncthreads();
+    // LDS layout [wave][j][quad of 4 columns][lane]: consecutive lanes 16 bytes apart, no bank conflicts
+    constexpr int Q4 = V / 4;
+    f32x4* red4 = reinterpret_cast<f32x4*>(red);
     if (q > 0) {
 #pragma unroll
       for (int j = 0; j < J; ++j)
 #pragma unroll
-        for (int i = 0; i < V; ++i) red[(q - 1) * H + (j * 64 + lane) * V + i] = pass ? pb[j][i] : pg[j][i];
+        for (int h = 0; h < Q4; ++h) {
+          f32x4 t;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) t[e] = pass ? pb[j][4 * h + e] : pg[j][4 * h + e];
+          red4[(((q - 1) * J + j) * Q4 + h) * 64 + lane] = t;
+        }
     }
     __syncthreads();
     if (q == 0) {
@@ -419,12 +427,15 @@ __global__ __launch_bounds__(256) void norm_bwd_partials_reg_kernel(int Trows, c
 #pragma unroll
       for (int j = 0; j < J; ++j) {
         const int c = (j * 64 + lane) * V;
-        float o[V];
 #pragma unroll
-        for (int i = 0; i < V; ++i)
-          o[i] = (((pass ? pb[j][i] : pg[j][i]) + red[c + i]) + red[H + c + i]) + red[2 * H + c + i];
+        for (int h = 0; h < Q4; ++h) {
+          const f32x4 r1 = red4[((0 * J + j) * Q4 + h) * 64 + lane], r2 = red4[((1 * J + j) * Q4 + h) * 64 + lane],
+                      r3 = red4[((2 * J + j) * Q4 + h) * 64 + lane];
+          f32x4 o;
 #pragma unroll
-        for (int i = 0; i < V; ++i) p[c + i] = o[i];
+          for (int e = 0; e < 4; ++e) o[e] = (((pass ? pb[j][4 * h + e] : pg[j][4 * h + e]) + r1[e]) + r2[e]) + r3[e];
+          *reinterpret_cast<f32x4*>(p + c + 4 * h) = o;
+        }
       }
     }
   }
