@@ -20,7 +20,10 @@ parameter segment and on the stage input; an independent torch float64 autograd
 model; torch.optim.AdamW and the first-step / constant-gradient closed forms;
 k accumulated microbatches == one concatenated batch; causality; RoPE relative
 position property; cross-entropy = ln V at zero head weights; L-layer stage ==
-L chained one-layer stages.  No function here is "parity unpinned".
+L chained one-layer stages; the least-squares line against numpy.polyfit; the
+half-precision overflow criterion against numpy's float16 conversion at the
+boundary values; the loss-scale rule against a hand-written trace.  No function
+here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -453,6 +456,13 @@ def loss_scale_update(scale, good_steps, found_inf, backoff=0.5, growth=2.0, gro
 
 
 def gradients_overflow_fp16(dy_scaled_max):
-    """Whether an upstream gradient of that magnitude is representable in IEEE half (largest finite value
-    65504): the seed itself becomes inf when it is not, and every gradient downstream of it non-finite."""
-    return not (dy_scaled_max <= 65504.0)
+    """Whether an upstream gradient of that magnitude turns into inf (or is nan) when it is rounded to IEEE half
+    with round-to-nearest-even, the precision the paper trains in (Section 6.1): then the seed itself is not
+    finite and every gradient downstream of it is not either.  The largest finite half is
+    (2 - 2**-10) * 2**15 = 65504 and the spacing in its binade is 32, so everything below the midpoint
+    65504 + 16 = 65520 still rounds to a finite half; the midpoint itself is a tie between 65504 (odd last
+    mantissa bit) and 2**16 (even), goes to the even side and overflows."""
+    x = abs(float(dy_scaled_max))
+    largest_finite = (2.0 - 2.0 ** -10) * 2.0 ** 15
+    half_spacing = 2.0 ** (15 - 10) / 2.0
+    return not (x < largest_finite + half_spacing)      # also true for nan

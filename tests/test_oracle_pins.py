@@ -462,3 +462,38 @@ def test_linear_fit_recovers_lines_and_matches_library_least_squares():
     a, b, r2 = so.linear_fit([2.0, 5.0], [1.0, 7.0])              # two points: the line through them
     assert abs(b - 2.0) < 1e-12 and abs(a + 3.0) < 1e-12 and abs(r2 - 1.0) < 1e-12
     assert so.linear_fit([1.0, 2.0, 3.0], [4.0, 4.0, 4.0]) == (4.0, 0.0, 1.0)
+
+
+def test_half_overflow_criterion_is_round_to_nearest_even():
+    """The overflow criterion of fp16 training (the paper's precision, Section 6.1) against the library's own
+    conversion to IEEE half: a magnitude overflows exactly when numpy's round-to-nearest-even float16 of it is
+    not finite.  65504 is the largest finite half; values up to just below 65520 still round down to it; the
+    tie 65520 goes to the even side, which is 2**16 = inf."""
+    with np.errstate(over="ignore", invalid="ignore"):
+        for x in (0.0, 1.0, 65503.9, 65504.0, 65504.1, 65519.9, np.nextafter(65520.0, 0.0), 65520.0,
+                  np.nextafter(65520.0, 1e9), 65536.0, 1e30, float("inf"), float("nan"), -65519.9, -65520.0):
+            finite_as_half = bool(np.isfinite(np.float64(x).astype(np.float16)))
+            assert so.gradients_overflow_fp16(x) == (not finite_as_half), x
+    # the hand-derived boundary, independent of the library: largest finite + half a spacing of 32
+    assert not so.gradients_overflow_fp16(65504.0 + 15.999) and so.gradients_overflow_fp16(65504.0 + 16.0)
+
+
+def test_loss_scale_rule_hand_traced():
+    """Dynamic loss scaling (fp16 mixed precision, Section 6.1; the rule is the reading stated in the oracle) over a
+    scripted run with growth interval 3, every (scale, good-step count) written out by hand: an overflow halves the
+    scale and restarts the count; the third good step in a row doubles the scale and restarts the count."""
+    script = [  # found_inf, scale after, count after
+        (0, 65536.0, 1), (0, 65536.0, 2), (1, 32768.0, 0), (0, 32768.0, 1), (0, 32768.0, 2),
+        (0, 65536.0, 0), (0, 65536.0, 1), (1, 32768.0, 0), (1, 16384.0, 0), (0, 16384.0, 1),
+        (0, 16384.0, 2), (0, 32768.0, 0), (0, 32768.0, 1), (0, 32768.0, 2), (0, 65536.0, 0)]
+    scale, good = 65536.0, 0
+    for found, want_scale, want_good in script:
+        scale, good = so.loss_scale_update(scale, good, found, 0.5, 2.0, 3)
+        assert (scale, good) == (want_scale, want_good), (found, scale, good)
+    # the defaults: halving, doubling, 2000 good steps between doublings
+    assert so.loss_scale_update(8.0, 5, 1) == (4.0, 0)
+    assert so.loss_scale_update(8.0, 1998, 0) == (8.0, 1999)
+    assert so.loss_scale_update(8.0, 1999, 0) == (16.0, 0)
+    # other factors are honoured as given
+    assert so.loss_scale_update(8.0, 0, 1, backoff=0.25) == (2.0, 0)
+    assert so.loss_scale_update(8.0, 0, 0, growth=4.0, growth_interval=1) == (32.0, 0)
