@@ -27,19 +27,41 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak (256 CUs x 4 SIMDs x 1024 flop/clk x 2.4 GHz)
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per call of the GEMM dispatcher (one or two kernel launches) of a workload's large kernel classes, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# each counter scaled by what it reads for a copy of known size (profiles/gemm_wgrad_C3_hbm_traffic.txt: the
-# unpaired weight-gradient launches, `bench.py --traffic-probe`; profiles/stage_step_C3_mfma_busy_hbm_bytes.txt: one
-# step of this file).  Keys: workload, kernel class, weight-gradient group size (None: does not depend on it).
-# Anything that was not measured reports null.
-MEASURED_TRAFFIC = {("C3", "gemm_mfma_tn", 0): 1092.8e6, ("C3", "gemm_mfma_tn", 2): 1781.2e6, ("C3", "gemm_mfma_tn", 8): 5866.1e6,
-                    ("C3", "gemm_mfma_nn", None): 533.2e6, ("C3", "gemm_mfma_nt", None): 665.2e6,
-                    ("C3", "gemm_mfma_nn_glu", None): 1413.0e6, ("C3", "gemm_mfma_nt_glu", None): 983.7e6}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "stage_step_C3_hbm_traffic.txt")
+
+
+def kernel_sources_digest():
+    """sha256 over the HIP sources the library is built from (file names and contents, sorted): the counter summary
+    under profiles/ names the digest it was measured at, and a figure measured at other sources is not reported."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2507_10392_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def measured_traffic(workload, kernel, cfg):
+    """HBM-side bytes per launch of a kernel class from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under
+    profiles/ (lines `traffic <workload> <kernel class> <wgrad group> <bytes per launch>` after a line
+    `sources <digest>`).  This run measures no counters itself, so the figure is given only when the summary was
+    made from the kernel sources this run uses; otherwise null."""
     group = 0 if not cfg.pair_wgrad else min(max(cfg.pair_wgrad, 2), 16, cfg.num_microbatches)
-    return MEASURED_TRAFFIC.get((workload, kernel, group), MEASURED_TRAFFIC.get((workload, kernel, None)))
+    try:
+        with open(TRAFFIC_FILE) as f:
+            lines = [ln.split() for ln in f]
+    except OSError:
+        return None
+    digest = next((ln[1] for ln in lines if len(ln) >= 2 and ln[0] == "sources"), None)
+    if digest != kernel_sources_digest():
+        return None
+    for ln in lines:
+        if len(ln) >= 5 and ln[0] == "traffic" and ln[1] == workload and ln[2] == kernel and ln[3] in (str(group), "any"):
+            return float(ln[4])
+    return None
 
 
 def model_flops_per_step(cfg):
@@ -205,33 +227,202 @@ def planner_profile(cfg):
     print(json.dumps({"planner_profile": out}))
 
 
-def traffic_probe(cfg):
-    """For rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs: launches a plain copy of known size (1 GiB read,
-    1 GiB written, torch's elementwise copy kernel) and then the weight-gradient GEMMs of one decoder
-    layer of the workload (the dominant kernel class of the step), each three times."""
-    import torch
-    import paper_2507_10392_amd as zs
+def describe(cfg, M, shard_elems, P, ministages=0):
+    return (f"{cfg.name}: {cfg.layers} layers, hidden {cfg.hidden}, heads {cfg.heads}, ffn {cfg.ffn}, "
+            f"seq {cfg.seq}, microbatch {cfg.microbatch} x {M} microbatches, "
+            f"{'Llama' if cfg.arch else 'GPT'}-style"
+            + (f", embedding + LM head over {cfg.vocab} tokens" if cfg.has_head else "")
+            + f", AdamW shard {shard_elems} of {P} params, "
+            f"recompute {cfg.recompute}, pair_wgrad {cfg.pair_wgrad}, offload_acts {cfg.offload_acts}"
+            + (f", activation budget {cfg.act_budget_bytes} B" if cfg.act_budget_bytes else "")
+            + (f", {ministages} ministages of {cfg.layers // ministages} layers time-multiplexed" if ministages else ""))
+
+
+def run_workload(torch, zs, cfg, steps, warmup, *, kernel_events=True, graph_mode=False, ministages=0, loss_scale=1.0,
+                 fp16_flag=False, workload_key=None):
+    """Allocates one workload's buffers, runs `warmup` untimed and `steps` timed stage steps and returns the
+    figures of the run; everything it allocated is released when it returns."""
     dev = torch.device("cuda:0")
-    n = 1 << 28
-    a = torch.randn(n, device=dev)
-    b = torch.empty_like(a)
-    for _ in range(3):
-        b.copy_(a)
-    T, H, F = cfg.tokens, cfg.hidden, cfg.ffn
-    st = torch.cuda.current_stream().cuda_stream
-    nup = 2 if cfg.arch == 1 else 1
-    nqkv = 3 if cfg.arch == 1 else 1
-    shapes = [("w_down", F, H, 1), ("w_up", H, F * (1 if cfg.arch == 1 else 1), nup), ("w_out", H, H, 1),
-              ("w_qkv", H, H if cfg.arch == 1 else 3 * H, nqkv)]
-    for name, M, N, batch in shapes:
-        X = torch.randn(T, M, device=dev).to(torch.bfloat16)
-        dY = (torch.randn(T, N * batch, device=dev) * 0.01).to(torch.bfloat16)
-        dW = torch.zeros(batch * M * N, device=dev)
-        for _ in range(3):
-            zs.ops.gemm(st, 1, 1, 0, M, N, T, X, M, dY, N * batch, dW, N, 1, None, None, 0, batch, 0, N, M * N, 0, 0, 0, 2)
+    torch.manual_seed(cfg.seed)
+    cc = zs.make_config(cfg)
+    P, mem, _ = zs.query(cc)
+    b, e = cc.shard_begin, cc.shard_end
+    bf = cfg.dtype != 0
+    td = torch.bfloat16 if cfg.dtype == 1 else torch.float16 if cfg.dtype == 2 else torch.float32
+    M, T, H = cfg.num_microbatches, cfg.tokens, cfg.hidden
+
+    if not ministages:
+        params = torch.empty(P, dtype=td, device=dev)
+        fill_params(cfg, params, torch)
+        master = params[b:e].float() if bf else None
+        grad = torch.zeros(P, dtype=torch.float32, device=dev)
+        m = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
+        v = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
+        ws = torch.empty(mem["workspace"], dtype=torch.uint8, device=dev)
+    if cfg.has_embed:
+        xs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)]
+    else:
+        xs = [torch.randn(T, H, device=dev).to(td) for _ in range(M)]
+    tgs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
+    losses = [torch.zeros(1, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
+    dys = [None] * M if cfg.has_head else [(torch.randn(T, H, device=dev) * (0.01 * loss_scale)).to(td) for _ in range(M)]
+    ys = [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
+    dxs = [None] * M if cfg.has_embed else [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
+    if ministages:
+        stage = MinistageRunner(torch, zs, cfg, ministages, xs, dys)
+        params, mem, shard_elems = stage.probe, stage.mem, stage.shard_elems
+    else:
+        stage = zs.Stage(cc, params, master, grad, m, v, ws)
+        shard_elems = e - b
+    if cfg.offload_acts and not ministages:
+        stage.attach_host_stash(torch.empty(mem["host_stash"], dtype=torch.uint8, pin_memory=True))
+
+    def microbatches():
+        for i in range(M):
+            stage.forward(i, xs[i], ys[i], tgs[i], losses[i])
+        for i in reversed(range(M)):
+            stage.backward(i, dys[i], dxs[i], loss_scale / M)
+            stage.accumulate(i)
+
+    graph = None
+    overflow = None
+    if fp16_flag:
+        overflow = torch.zeros(1, dtype=torch.int32, device=dev)
+        zs.lib().stage_set_overflow_flag(stage.h, overflow.data_ptr())
+
+    def step(t):
+        if ministages:
+            return stage.step(t)
+        if graph is not None:
+            graph.replay()
+            stage.graph_replayed(M)
+        else:
+            microbatches()
+        stage.optimizer_step(t, 1.0 / loss_scale)
+
+    t = 0
+    main_stream = torch.cuda.current_stream()
+    if graph_mode:
+        # one eager step configures every kernel; then the loop is captured on a side stream the stage is bound to
+        kernel_events = False
+        stage.close()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            stage = zs.Stage(cc, params, master, grad, m, v, ws, stream=side)
+            t += 1
+            step(t)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                microbatches()
+            graph = g
+        torch.cuda.set_stream(side)
+    for _ in range(warmup):
+        t += 1
+        step(t)
     torch.cuda.synchronize()
-    print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": 4 * n,
-                      "gemm_shapes": [(nm, M, N, T, bt) for nm, M, N, bt in shapes]}))
+    # Per-kernel HIP events bracket every launch of the LAST timed step only: two event records per
+    # launch leave small gaps in the queue (2-3 % of a C3 step), which one step in K keeps out of `value`
+    # almost entirely while the kernel figures still come from inside the timed region.
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # on the stage's stream
+    t0 = time.perf_counter()
+    marks[0].record()
+    enqueue_ms = []          # host time to enqueue each step (no synchronisation inside): must stay below the step time
+    for i in range(steps):
+        t += 1
+        if i == steps - 1 and kernel_events:
+            stage.profile(True)
+        h0 = time.perf_counter()
+        step(t)
+        enqueue_ms.append((time.perf_counter() - h0) * 1e3)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    in_order_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    per_step_ms = sorted(in_order_ms)
+    stats = stage.profile_read() if kernel_events else {}
+    stage.profile(False)
+    finite = bool(torch.isfinite(params.float().sum()).item())
+
+    ms_per_step = dt * 1e3 / steps
+    tokens = T * M
+    value = tokens / (dt / steps)
+    mflops = model_flops_per_step(cfg)
+    mfu = mflops / (dt / steps) / (PEAK_BF16_TFLOPS * 1e12)
+
+    kernels = {}
+    for name, st in stats.items():
+        if st["launches"] == 0:
+            continue
+        avg_ms = st["ms"] / st["launches"]
+        k = {"launches_per_step": st["launches"], "avg_ms": avg_ms, "ms_per_step": st["ms"]}
+        if st["flops"] > 0:
+            k["tflops"] = st["flops"] / st["ms"] / 1e9
+        if st["bytes"] > 0:
+            k["gbs"] = st["bytes"] / st["ms"] / 1e6
+        kernels[name] = k
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
+        k = kernels[dom]
+        if "tflops" in k:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS}
+        else:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": k.get("gbs", 0.0), "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": k.get("gbs", 0.0) / PEAK_HBM_GBS}
+        roofline["avg_launch_ms"] = k["avg_ms"]
+        roofline["traffic"] = measured_traffic(workload_key or cfg.name, dom, cfg)
+
+    out = {
+        "value": value, "ms_per_step": ms_per_step,
+        "dtype": {0: "f32", 1: "bf16", 2: "f16"}[cfg.dtype],
+        "config": {"workload": describe(cfg, M, shard_elems, P, ministages), "tokens_per_step": tokens,
+                   "shard_elems": shard_elems},
+        "ms_each_step": [round(x, 2) for x in in_order_ms], "enqueue_ms_each_step": [round(x, 2) for x in enqueue_ms],
+        "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
+        "mfu_model_flops": mfu, "hfu_executed_flops": mfu * (4.0 / 3.0 if cfg.recompute else 1.0),
+        "model_tflop_per_step": mflops / 1e12, "finite": finite,
+        "roofline": roofline, "kernels": kernels, "hip_graph": bool(graph_mode),
+        "memory_bytes": mem,
+    }
+    if overflow is not None:
+        out["fp16"] = {"loss_scale": loss_scale, "overflow_flag": int(overflow.item())}
+    if "adamw" in kernels and "gbs" in kernels["adamw"]:
+        # the class's bytes are the algorithmic ones (30 B per element, 28 B in fp32); the kernel also zeroes the
+        # gradient it has read (4 B per element more), which is what it actually moves
+        alg = 30.0 if bf else 28.0
+        out["adamw_hbm_frac"] = kernels["adamw"]["gbs"] / PEAK_HBM_GBS
+        out["adamw_hbm_frac_moved"] = kernels["adamw"]["gbs"] * (alg + 4.0) / alg / PEAK_HBM_GBS
+    if ministages:
+        h2d, d2h = stage.ms.traffic()
+        nsteps = steps + warmup
+        out["ministages"] = {"K": ministages, "device_arena_bytes": mem["device_bytes"], "resident_bytes": mem["resident_bytes"],
+                             "host_bytes": mem["host_bytes"], "h2d_bytes_per_step": h2d / nsteps, "d2h_bytes_per_step": d2h / nsteps}
+    stage.close()
+    if graph_mode:
+        torch.cuda.set_stream(main_stream)
+    out["_shard_elems"] = shard_elems
+    return out
+
+
+OTHER_WORKLOADS = ("C1", "C2", "C4a", "C4b", "C5")
+
+
+def brief(r):
+    """What the line carries for each of the other workloads."""
+    d = {"workload": r["config"]["workload"], "tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+         "ms_per_step_min": r["ms_per_step_min"], "steps": len(r["ms_each_step"]), "dtype": r["dtype"],
+         "mfu_model_flops": r["mfu_model_flops"], "hfu_executed_flops": r["hfu_executed_flops"],
+         "model_tflop_per_step": r["model_tflop_per_step"], "finite": r["finite"]}
+    if r["roofline"]:
+        rf = r["roofline"]
+        d["dominant_kernel"] = {"kernel": rf["kernel"], "bound": rf["bound"], "achieved": rf["achieved"], "unit": rf["unit"],
+                                "frac": rf["frac"], "avg_launch_ms": rf["avg_launch_ms"]}
+    if "adamw_hbm_frac" in r:
+        d["adamw_hbm_frac"] = r["adamw_hbm_frac"]
+    d["activation_bytes"] = r["memory_bytes"].get("activations")
+    return d
 
 
 def main():
@@ -239,7 +430,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--workload", default=None,
+                    help="C1 | C2 | C3 | C4a | C4b | C5: time that workload alone.  Without it the headline workload C3 is "
+                         "timed with --steps / --warmup and then each of the others for 3 steps after 1 warm-up step "
+                         "(block other_workloads of the same line)")
+    ap.add_argument("--no-other-workloads", action="store_true", help="headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket launches with HIP events")
     ap.add_argument("--no-pair-wgrad", action="store_true",
@@ -261,8 +456,6 @@ def main():
                          "waiting in pinned host memory (include/ministages.h); interior stages only")
     ap.add_argument("--planner-profile", action="store_true",
                     help="time one layer at small microbatch sizes, fit the runtime lines and print them with the memory terms")
-    ap.add_argument("--traffic-probe", action="store_true",
-                    help="launch a 1 GiB copy and the workload's weight-gradient GEMMs only (for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the stage step on ONE GPU only (no collectives, no sharding across GPUs); "
@@ -276,7 +469,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    cfg = get_config(args.workload).with_(pair_wgrad=0 if args.no_pair_wgrad else max(args.wgrad_group, 1))
+    headline = args.workload or "C3"
+    variant = bool(args.workload or args.recompute or args.offload or args.fp16 or args.ministages or args.graph
+                   or args.no_pair_wgrad or args.planner_profile)
+
+    def configured(name):
+        return get_config(name).with_(pair_wgrad=0 if args.no_pair_wgrad else max(args.wgrad_group, 1))
+
+    cfg = configured(headline)
     if args.recompute or args.offload:
         cfg = cfg.with_(recompute=1, offload_acts=1 if args.offload else 0)
     loss_scale = 1.0
@@ -292,173 +492,32 @@ def main():
         print("bench.py: --ministages K needs an interior stage whose layer count K divides, and no --graph",
               file=sys.stderr)
         sys.exit(2)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    if args.traffic_probe:
-        traffic_probe(cfg)
-        return
+    torch.cuda.set_device(torch.device("cuda:0"))
     if args.planner_profile:
         planner_profile(cfg)
         return
-    torch.manual_seed(cfg.seed)
-    cc = zs.make_config(cfg)
-    P, mem, _ = zs.query(cc)
-    b, e = cc.shard_begin, cc.shard_end
-    bf = cfg.dtype != 0
-    td = torch.bfloat16 if cfg.dtype == 1 else torch.float16 if cfg.dtype == 2 else torch.float32
-    M, T, H = cfg.num_microbatches, cfg.tokens, cfg.hidden
 
-    if not args.ministages:
-        params = torch.empty(P, dtype=td, device=dev)
-        fill_params(cfg, params, torch)
-        master = params[b:e].float() if bf else None
-        grad = torch.zeros(P, dtype=torch.float32, device=dev)
-        m = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
-        v = torch.zeros(max(e - b, 1), dtype=torch.float32, device=dev)
-        ws = torch.empty(mem["workspace"], dtype=torch.uint8, device=dev)
-    if cfg.has_embed:
-        xs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)]
-    else:
-        xs = [torch.randn(T, H, device=dev).to(td) for _ in range(M)]
-    tgs = [torch.randint(0, cfg.vocab, (T,), dtype=torch.int32, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
-    losses = [torch.zeros(1, device=dev) for _ in range(M)] if cfg.has_head else [None] * M
-    dys = [None] * M if cfg.has_head else [(torch.randn(T, H, device=dev) * (0.01 * loss_scale)).to(td) for _ in range(M)]
-    ys = [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
-    dxs = [None] * M if cfg.has_embed else [torch.empty(T, H, dtype=td, device=dev) for _ in range(M)]
-    if args.ministages:
-        stage = MinistageRunner(torch, zs, cfg, args.ministages, xs, dys)
-        params, mem, shard_elems = stage.probe, stage.mem, stage.shard_elems
-    else:
-        stage = zs.Stage(cc, params, master, grad, m, v, ws)
-        shard_elems = e - b
-    if cfg.offload_acts and not args.ministages:
-        stage.attach_host_stash(torch.empty(mem["host_stash"], dtype=torch.uint8, pin_memory=True))
-
-    def microbatches():
-        for i in range(M):
-            stage.forward(i, xs[i], ys[i], tgs[i], losses[i])
-        for i in reversed(range(M)):
-            stage.backward(i, dys[i], dxs[i], loss_scale / M)
-            stage.accumulate(i)
-
-    graph = None
-    overflow = None
-    if args.fp16:
-        overflow = torch.zeros(1, dtype=torch.int32, device=dev)
-        zs.lib().stage_set_overflow_flag(stage.h, overflow.data_ptr())
-
-    def step(t):
-        if args.ministages:
-            return stage.step(t)
-        if graph is not None:
-            graph.replay()
-            stage.graph_replayed(M)
-        else:
-            microbatches()
-        stage.optimizer_step(t, 1.0 / loss_scale)
-
-    t = 0
-    if args.graph:
-        # one eager step configures every kernel; then the loop is captured on a side stream the stage is bound to
-        args.no_kernel_events = True
-        stage.close()
-        side = torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            stage = zs.Stage(cc, params, master, grad, m, v, ws, stream=side)
-            t += 1
-            step(t)
-            side.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
-                microbatches()
-            graph = g
-        torch.cuda.set_stream(side)
-    for _ in range(args.warmup):
-        t += 1
-        step(t)
-    torch.cuda.synchronize()
-    # Per-kernel HIP events bracket every launch of the LAST timed step only: two event records per
-    # launch leave small gaps in the queue (2-3 % of a C3 step), which one step in K keeps out of `value`
-    # almost entirely while the kernel figures still come from inside the timed region.
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the stage's stream
-    t0 = time.perf_counter()
-    marks[0].record()
-    enqueue_ms = []          # host time to enqueue each step (no synchronisation inside): must stay below the step time
-    for i in range(args.steps):
-        t += 1
-        if i == args.steps - 1 and not args.no_kernel_events:
-            stage.profile(True)
-        h0 = time.perf_counter()
-        step(t)
-        enqueue_ms.append((time.perf_counter() - h0) * 1e3)
-        marks[i + 1].record()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof_steps = 1
-    in_order_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
-    per_step_ms = sorted(in_order_ms)
-    stats = stage.profile_read() if not args.no_kernel_events else {}
-    stage.profile(False)
-    finite = bool(torch.isfinite(params.float().sum()).item())
-
-    ms_per_step = dt * 1e3 / args.steps
-    tokens = T * M
-    value = tokens / (dt / args.steps)
-    mflops = model_flops_per_step(cfg)
-    mfu = mflops / (dt / args.steps) / (PEAK_BF16_TFLOPS * 1e12)
-
-    kernels = {}
-    for name, s in stats.items():
-        if s["launches"] == 0:
-            continue
-        avg_ms = s["ms"] / s["launches"]
-        k = {"launches_per_step": s["launches"] / prof_steps, "avg_ms": avg_ms, "ms_per_step": s["ms"] / prof_steps}
-        if s["flops"] > 0:
-            k["tflops"] = s["flops"] / s["ms"] / 1e9
-        if s["bytes"] > 0:
-            k["gbs"] = s["bytes"] / s["ms"] / 1e6
-        kernels[name] = k
-    roofline = None
-    if kernels:
-        dom = max(kernels, key=lambda n: kernels[n]["ms_per_step"])
-        k = kernels[dom]
-        if "tflops" in k:
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": PEAK_BF16_TFLOPS,
-                        "unit": "TFLOP/s", "frac": k["tflops"] / PEAK_BF16_TFLOPS}
-        else:
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": k.get("gbs", 0.0), "peak": PEAK_HBM_GBS,
-                        "unit": "GB/s", "frac": k.get("gbs", 0.0) / PEAK_HBM_GBS}
-        roofline["avg_launch_ms"] = k["avg_ms"]
-        roofline["traffic"] = measured_traffic(args.workload, dom, cfg)
-
-    out = {
-        "metric": "stage train tokens/s on 1 MI355X (fwd+bwd+AdamW); MFMA util % of bf16 peak",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {0: "f32", 1: "bf16", 2: "f16"}[cfg.dtype], "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.layers} layers, hidden {cfg.hidden}, heads {cfg.heads}, ffn {cfg.ffn}, "
-                               f"seq {cfg.seq}, microbatch {cfg.microbatch} x {M} microbatches, "
-                               f"{'Llama' if cfg.arch else 'GPT'}-style, AdamW shard {shard_elems} of {P} params, "
-                               f"recompute {cfg.recompute}, pair_wgrad {cfg.pair_wgrad}, offload_acts {cfg.offload_acts}"
-                               + (f", {args.ministages} ministages of {cfg.layers // args.ministages} layers time-multiplexed"
-                                  if args.ministages else ""),
-                   "tokens_per_step": tokens, "shard_elems": shard_elems},
-        "ms_each_step": [round(x, 2) for x in in_order_ms], "enqueue_ms_each_step": [round(x, 2) for x in enqueue_ms], "ms_per_step_min": per_step_ms[0], "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
-        "mfu_model_flops": mfu, "hfu_executed_flops": mfu * (4.0 / 3.0 if cfg.recompute else 1.0),
-        "model_tflop_per_step": mflops / 1e12, "finite": finite,
-        "roofline": roofline, "kernels": kernels, "hip_graph": bool(args.graph),
-        "memory_bytes": mem,
-    }
-    if overflow is not None:
-        out["fp16"] = {"loss_scale": loss_scale, "overflow_flag": int(overflow.item())}
-    if "adamw" in kernels:
-        out["adamw_hbm_frac"] = kernels["adamw"].get("gbs", 0.0) / PEAK_HBM_GBS
-    if args.ministages:
-        h2d, d2h = stage.ms.traffic()
-        nsteps = args.steps + args.warmup
-        out["ministages"] = {"K": args.ministages, "device_arena_bytes": mem["device_bytes"], "resident_bytes": mem["resident_bytes"],
-                             "host_bytes": mem["host_bytes"], "h2d_bytes_per_step": h2d / nsteps, "d2h_bytes_per_step": d2h / nsteps}
-    stage.close()
+    r = run_workload(torch, zs, cfg, args.steps, args.warmup, kernel_events=not args.no_kernel_events, graph_mode=args.graph,
+                     ministages=args.ministages, loss_scale=loss_scale, fp16_flag=args.fp16, workload_key=headline)
+    shard_elems = r.pop("_shard_elems")
+    out = {"metric": "stage train tokens/s on 1 MI355X (fwd+bwd+AdamW); MFMA util % of bf16 peak",
+           "value": r.pop("value"), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": r.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": r.pop("dtype"), "data": "synthetic"}
+    out.update(r)
+    if not variant and not args.no_other_workloads:
+        # The other benchmark stages, each as configured (C4b: 12 layers, full recompute, inside its activation budget),
+        # one after the other with their buffers released in between; 1 warm-up step and 3 timed steps each.
+        others = {}
+        for name in OTHER_WORKLOADS:
+            torch.cuda.empty_cache()
+            try:
+                o = run_workload(torch, zs, configured(name), 3, 1, kernel_events=True, workload_key=name)
+                others[name] = brief(o)
+            except Exception as ex:      # reported, never hidden: a workload that does not run says so in the line
+                others[name] = {"error": f"{type(ex).__name__}: {ex}"}
+        out["other_workloads"] = others
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, shard_elems)
     print(json.dumps(out))

@@ -157,8 +157,13 @@ int stage_attach_host_stash(stage_t* s, void* host_pinned, int64_t bytes);
 /* Forward of microbatch slot mb in [0, max_microbatches).
  *   x_or_ids  elem[T,H] stage input, or int32[T] token ids when has_embed
  *   y_out     elem[T,H] stage output; may be NULL when has_head
- *   targets   int32[T] (has_head only, else NULL); read again by stage_backward, so it must stay valid
+ *   targets   int32[T] (has_head only, else NULL); copied into the stage's workspace by this call, so the caller's
+ *             buffer is free again once the call's work on the stream is done
  *   loss_out  device float: the microbatch's mean cross entropy (has_head only, else NULL)
+ * Indices are never checked on the host (they live in device memory).  A token id outside [0, vocab) reads as an
+ * all-zero embedding row and contributes nothing to the embedding's gradient; a target outside [0, vocab) makes its
+ * row an ignored one: it adds 0 to the loss sum (the mean still divides by T) and its logits get a zero gradient,
+ * so loss and gradient stay consistent with each other.
  * STAGE_ERR_STATE if slot mb already holds a forward that has not been backpropagated, if a
  * backward of this step is still waiting for its stage_accumulate, or if offload_acts = 1 and no host
  * buffer was attached. */

@@ -722,16 +722,22 @@ hipError_t ce_fwd(hipStream_t st, DType dt, int T, int V, const void* z, int64_t
 template <typename T>
 __global__ __launch_bounds__(256) void ce_bwd_kernel(int V, T* z, int64_t ldz, const int32_t* __restrict__ targets,
                                                      const float* __restrict__ lse, float scale) {
-  const int t = blockIdx.y;
-  const int c = blockIdx.x * 256 + threadIdx.x;
+  // rows on grid.x (no 65535 limit on the number of tokens), column blocks on grid.y
+  const int t = blockIdx.x;
+  const int c = blockIdx.y * 256 + threadIdx.x;
   if (c >= V) return;
   T* p = z + (int64_t)t * ldz + c;
+  const int tg = targets[t];
+  if (tg < 0 || tg >= V) {   // a row without a valid target has no loss term (ce_fwd gives it 0), hence no gradient
+    *p = from_f<T>(0.f);
+    return;
+  }
   const float pr = expf(to_f(*p) - lse[t]);
-  *p = from_f<T>(scale * (pr - (c == targets[t] ? 1.f : 0.f)));
+  *p = from_f<T>(scale * (pr - (c == tg ? 1.f : 0.f)));
 }
 hipError_t ce_bwd(hipStream_t st, DType dt, int T, int V, void* z, int64_t ldz, const int32_t* targets,
                   const float* lse, float scale) {
-  dim3 grid((unsigned)cdiv(V, 256), (unsigned)T), blk(256);
+  dim3 grid((unsigned)T, (unsigned)cdiv(V, 256)), blk(256);
   if (dt == F32) hipLaunchKernelGGL(ce_bwd_kernel<float>, grid, blk, 0, st, V, (float*)z, ldz, targets, lse, scale);
   else if (dt == BF16) hipLaunchKernelGGL(ce_bwd_kernel<bf16>, grid, blk, 0, st, V, (bf16*)z, ldz, targets, lse, scale);
   else hipLaunchKernelGGL(ce_bwd_kernel<f16>, grid, blk, 0, st, V, (f16*)z, ldz, targets, lse, scale);

@@ -33,6 +33,82 @@ def test_one_layer_one_microbatch_at_full_shape(gpu_device, name, dtype):
     log_report(f"full-shape single layer {name} dtype={dtype}", sorted(rep, key=lambda r: -r[1])[:8])
 
 
+def test_c4b_recompute_under_budget(gpu_device):
+    """The 13B-class stage as the benchmark configures its 12-layer run: microbatches of 2 x 2048 tokens, per-layer
+    checkpoints with recompute (Section 4.1.3) and a fixed activation budget of 96e9 bytes.
+    - The stash is exactly M * L * T * H * D bytes and stash + scratch fit the budget, for the full 12-layer,
+      8-microbatch configuration and for the cuts run here; a budget the stash cannot meet is refused on the host.
+    - One of the 12 layers, two microbatches, recompute and budget as configured: outputs, input gradients and every
+      gradient segment against the oracle (about a minute on the host).
+    - Two layers, two microbatches: bit for bit the same stage without recompute, and bit for bit two chained
+      one-layer stages (the property the oracle is pinned by), which carries the one-layer comparison to depth.
+    The oracle comparison stays one layer deep on purpose: with N(0,1) inputs at this width the attention scores have
+    a standard deviation of 2, so the bf16 rounding of q and k alone moves the softmax weights by half a per cent, and
+    the measured max-norm error of a gain gradient is 1.1e-2 after one layer and 2.2e-2 after two against the 2e-2 bar;
+    whole steps of full depth are compared with the oracle on the scaled twins (C4bt)."""
+    full = get_config("C4b")
+    assert full.recompute == 1 and full.act_budget_bytes == 96 * 10**9 and full.layers == 12
+    _, mem_full, _ = zs.query(zs.make_config(full))
+    assert mem_full["activations"] == full.num_microbatches * full.layers * full.tokens * full.hidden * 2
+    assert mem_full["activations"] + mem_full["scratch"] <= full.act_budget_bytes
+    with pytest.raises(zs.StageError) as ei:
+        zs.query(zs.make_config(full.with_(act_budget_bytes=4 * 10**9)))       # below the 4.03 GB stash
+    assert ei.value.code == zs.STAGE_ERR_BUDGET
+
+    one = full.with_(layers=1, num_microbatches=2, shard_num=1, shard_den=1)
+    print(f"[case] C4b cut: L=1 M=2 T={one.tokens} H={one.hidden} F={one.ffn} recompute=1 budget={one.act_budget_bytes}", flush=True)
+    inp = make_inputs(one, perturbed=True)
+    g = GpuStage(one, inp)
+    assert g.mem["activations"] == one.num_microbatches * one.layers * one.tokens * one.hidden * 2
+    gpu = g.run_microbatches(inp)
+    g.stage.close()
+    del g
+    ora = oracle_step(one, inp)
+    rep = []
+    compare_step(one, gpu, ora, TOL[one.dtype], rep)
+    log_report("C4b cut (1 layer, 2 microbatches, recompute, 96e9 B budget)", sorted(rep, key=lambda r: -r[1])[:8])
+    del inp, ora, gpu
+
+    two = full.with_(layers=2, num_microbatches=2, shard_num=1, shard_den=1)
+    print("[case] C4b cut: L=2 M=2, recompute on/off and chained one-layer stages", flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    P, T, H, ppl = two.n_params, two.tokens, two.hidden, two.params_per_layer
+    params = (torch.randn(P, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+    xs = [torch.randn(T, H, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(2)]
+    dys = [(torch.randn(T, H, device="cuda", generator=gen) * 0.01).to(torch.bfloat16) for _ in range(2)]
+
+    def run(c, par, x_in, dy_in):
+        cc = zs.make_config(c)
+        n, mem, _ = zs.query(cc)
+        if c.recompute:
+            assert mem["activations"] == c.num_microbatches * c.layers * T * H * 2
+        grad = torch.zeros(n, device="cuda")
+        m, v = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+        ws = torch.empty(mem["workspace"], dtype=torch.uint8, device="cuda")
+        stage = zs.Stage(cc, par.clone(), par.float(), grad, m, v, ws)
+        ys = [torch.empty(T, H, dtype=torch.bfloat16, device="cuda") for _ in x_in]
+        dxs = [torch.empty(T, H, dtype=torch.bfloat16, device="cuda") for _ in x_in]
+        for i, x in enumerate(x_in):
+            stage.forward(i, x, ys[i])
+        for i in reversed(range(len(x_in))):
+            stage.backward(i, dy_in[i], dxs[i])
+            stage.accumulate(i)
+        torch.cuda.synchronize()
+        stage.close()
+        return ys, dxs, grad
+
+    y_r, dx_r, g_r = run(two, params, xs, dys)
+    y_p, dx_p, g_p = run(two.with_(recompute=0, act_budget_bytes=0), params, xs, dys)
+    assert torch.equal(g_r, g_p) and all(torch.equal(a, b) for a, b in zip(y_r + dx_r, y_p + dx_p))
+    lay = two.with_(layers=1)
+    y0, _, _ = run(lay, params[:ppl], xs, dys)                       # layer 0 forward gives layer 1's input
+    y1, dx1, g1 = run(lay, params[ppl:], y0, dys)
+    _, dx0, g0 = run(lay, params[:ppl], xs, dx1)
+    assert all(torch.equal(a, b) for a, b in zip(y1 + dx0, y_r + dx_r))
+    assert torch.equal(torch.cat([g0, g1]), g_r)
+    assert bool(torch.isfinite(g_r).all()) and float(g_r.abs().max()) > 0
+
+
 def test_attention_full_size_heads_match_oracle(gpu_device):
     """S = 4096, 32 heads of 128: every row of the first and the last head, forward and backward."""
     mb, S, nh, d = 1, 4096, 32, 128
@@ -69,9 +145,9 @@ def test_attention_full_size_heads_match_oracle(gpu_device):
 
 
 def test_full_shape_stage_properties(gpu_device):
-    """C3's shape with 2 layers: a repeat is bit-identical (fixed reduction orders, one atomic add per
-    element and launch), recompute changes nothing, and accumulating the same microbatch twice gives
-    exactly twice the gradient of one (fp32 x + x is exact)."""
+    """C3's shape with 2 layers: a repeat is bit-identical (fixed reduction orders; every element of the gradient
+    accumulator has one owner workgroup per launch and launches are stream-ordered), recompute changes nothing, and
+    accumulating the same microbatch twice gives exactly twice the gradient of one (fp32 x + x is exact)."""
     cfg = get_config("C3").with_(layers=2, num_microbatches=2, shard_num=1, shard_den=1)
     print("[case] full-shape stage properties", flush=True)
     g = torch.Generator(device="cuda").manual_seed(3)

@@ -598,6 +598,35 @@ def test_cross_entropy(gpu_device, dtype):
     assert rel_err(back(zd), want * scale) <= (4e-3 if dtype else 1e-5)
 
 
+def test_cross_entropy_rows_without_a_valid_target(gpu_device):
+    """The boundary's rule for indices it cannot check on the host: a target outside [0, V) makes its row an ignored
+    one, 0 in the loss sum (the mean still divides by T) and an exactly zero gradient row, so that loss and gradient
+    agree; the other rows are those of the definition."""
+    print("[case] cross entropy with out-of-range targets", flush=True)
+    rng = np.random.default_rng(18)
+    T, V = 33, 700
+    z = draw(rng, (T, V), 0, 3.0)
+    tg = rng.integers(0, V, T).astype(np.int32)
+    bad = np.array([0, 7, 32])
+    tg[bad] = [-1, V, 2**31 - 1]
+    ok = np.setdiff1d(np.arange(T), bad)
+    z64 = z.astype(np.float64)
+    mx = z64.max(axis=1, keepdims=True)
+    lse_o = (mx + np.log(np.exp(z64 - mx).sum(axis=1, keepdims=True)))[:, 0]
+    loss_o = (lse_o[ok] - z64[ok, tg[ok]]).sum() / T
+    zd = dev(z)
+    lse, rowloss, loss = torch.empty(T, device="cuda"), torch.empty(T, device="cuda"), torch.empty(1, device="cuda")
+    zs.ops.cross_entropy(st(), 0, T, V, zd, V, dev(tg), lse, rowloss, loss, 0.0, 0)
+    assert np.all(back(rowloss)[bad] == 0.0)
+    assert abs(back(loss)[0] - loss_o) <= 1e-5 * abs(loss_o)
+    zs.ops.cross_entropy(st(), 0, T, V, zd, V, dev(tg), lse, None, None, 1.0 / T, 1)
+    got = back(zd)
+    assert np.all(got[bad] == 0.0)
+    want = np.exp(z64 - lse_o[:, None])
+    want[ok, tg[ok]] -= 1
+    assert rel_err(got[ok], want[ok] / T) <= 1e-5
+
+
 @pytest.mark.parametrize("dtype", [0, 1, 2])
 @pytest.mark.parametrize("n,begin", [(1 << 16, 0), (100003, 8), (1001, 5), (3, 0), (0, 0)])
 def test_adamw_kernel_matches_oracle_for_t_1_2_10(gpu_device, dtype, n, begin):
