@@ -107,6 +107,19 @@ int stage_op_attention_bwd_rope(void* stream, int32_t dtype, int32_t mb, int32_t
                                 const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl,
                                 const float* rope_table);
 
+/* stage_op_attention_bwd for callers that cannot allocate device memory (code under HIP graph capture, serving
+ * loops, harnesses that forbid hipMalloc) and therefore have no delta buffer to pass: the row sums delta[mb, nh, S]
+ * live in a fixed device array inside the library (STAGE_OP_NOALLOC_MAX_ROWS floats = 4 MiB, held by every GPU the
+ * library runs on until the process ends).  Same kernels, same results bit for bit as stage_op_attention_bwd; all other
+ * arguments as there.  The call allocates and frees nothing.  The GPU that owns `stream` must be the current device.
+ * STAGE_ERR_WORKSPACE if mb * nh * S exceeds STAGE_OP_NOALLOC_MAX_ROWS (nothing is enqueued); STAGE_ERR_DEVICE if the
+ * array's device address cannot be obtained.  All calls on one GPU share the one array: calls whose work may overlap
+ * on that GPU (different streams without ordering between them) race on it; calls on one stream are safe. */
+#define STAGE_OP_NOALLOC_MAX_ROWS (1 << 20)
+int stage_op_attention_bwd_noalloc(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                                   const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
+                                   const float* lse, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl);
+
 /* x[t,:] = E[ids[t],:] ; dE[id,:] += sum of dx rows of the tokens carrying id (token order). */
 int stage_op_embed(void* stream, int32_t dtype, int32_t T, int32_t H, int32_t V, const int32_t* ids, const void* E,
                    void* x, const void* dx, float* dE, int32_t backward);

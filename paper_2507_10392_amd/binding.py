@@ -123,6 +123,8 @@ def lib():
         L.stage_op_attention_bwd.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp,
                                              vp, i64, i32]
         L.stage_op_attention_bwd_rope.argtypes = L.stage_op_attention_bwd.argtypes + [vp]
+        L.stage_op_attention_bwd_noalloc.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp,
+                                                     i64, i32]
         L.stage_op_embed.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
         L.stage_op_cross_entropy.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, vp, vp, f32, i32]
         L.stage_op_adamw.argtypes = [vp, i32, i64, i64, vp, vp, vp, vp, vp, f32, f32, f32, f32, f32, i64, f32]

@@ -4,6 +4,7 @@
 #include "kernels.h"
 
 #include <cmath>
+#include <mutex>
 
 using namespace zs;
 
@@ -11,6 +12,29 @@ namespace {
 int rc(hipError_t e) { return e == hipSuccess ? STAGE_OK : STAGE_ERR_DEVICE; }
 bool dt_ok(int d) { return d == 0 || d == 1 || d == 2; }
 int vec_of(int d) { return d == 0 ? 4 : 8; }
+
+// Scratch of stage_op_attention_bwd_noalloc: the row sums delta[mb, nh, S] that the dQ kernel leaves for the dK/dV
+// kernel.  A file-scope device array, so every GPU the library runs on holds one copy of it (4 MiB) from the moment
+// the code object is loaded until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress, not a device address: kernels are given the address that call returns for the CURRENT device,
+// looked up once per device and kept.
+static __device__ __align__(256) float scratch[STAGE_OP_NOALLOC_MAX_ROWS];
+constexpr int MAX_DEVICES = 64;
+float* scratch_ptr[MAX_DEVICES] = {};
+std::mutex scratch_mu;
+
+// Device address of `scratch` on the current device, or nullptr (no current device, or the lookup failed).
+float* scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_ptr[dev]) {
+    float* p = nullptr;
+    if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    scratch_ptr[dev] = p;
+  }
+  return scratch_ptr[dev];
+}
 }  // namespace
 
 extern "C" {
@@ -172,6 +196,19 @@ int stage_op_attention_bwd_rope(void* stream, int32_t dtype, int32_t mb, int32_t
 int stage_op_attention_bwd(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
                            const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
                            const float* lse, float* delta, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl) {
+  return stage_op_attention_bwd_rope(stream, dtype, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd,
+                                     impl, nullptr);
+}
+
+int stage_op_attention_bwd_noalloc(void* stream, int32_t dtype, int32_t mb, int32_t S, int32_t nh, int32_t d, const void* q,
+                                   const void* k, const void* v, int64_t ld, const void* o, const void* dout, int64_t ldo,
+                                   const float* lse, void* dq, void* dk, void* dv, int64_t ldd, int32_t impl) {
+  if (mb < 1 || S < 1 || nh < 1) return STAGE_ERR_ARG;
+  if ((int64_t)mb * nh * S > (int64_t)STAGE_OP_NOALLOC_MAX_ROWS) return STAGE_ERR_WORKSPACE;   // delta would not fit
+  float* delta = scratch_on_current_device();
+  if (!delta) return STAGE_ERR_DEVICE;
+  // Every row of delta that the dK/dV kernel reads is written by this call's dQ (or delta) kernel first, in stream
+  // order, so nothing of an earlier call's content needs clearing.
   return stage_op_attention_bwd_rope(stream, dtype, mb, S, nh, d, q, k, v, ld, o, dout, ldo, lse, delta, dq, dk, dv, ldd,
                                      impl, nullptr);
 }
