@@ -389,11 +389,14 @@ def run_workload(torch, zs, cfg, steps, warmup, *, kernel_events=True, graph_mod
     if overflow is not None:
         out["fp16"] = {"loss_scale": loss_scale, "overflow_flag": int(overflow.item())}
     if "adamw" in kernels and "gbs" in kernels["adamw"]:
-        # the class's bytes are the algorithmic ones (30 B per element, 28 B in fp32); the kernel also zeroes the
-        # gradient it has read (4 B per element more), which is what it actually moves
-        alg = 30.0 if bf else 28.0
+        # The update kernel reads p, g, m, v and writes p, m, v and the 16-bit copy: 30 B per shard element (28 B in
+        # fp32), exactly its algorithmic bytes.  Dropping the gradients (Section 4.1.2) is a fill over the whole
+        # accumulator right after it (class zero_grads, 4 B per stage parameter); optimizer_phase is both together.
         out["adamw_hbm_frac"] = kernels["adamw"]["gbs"] / PEAK_HBM_GBS
-        out["adamw_hbm_frac_moved"] = kernels["adamw"]["gbs"] * (alg + 4.0) / alg / PEAK_HBM_GBS
+        ph = [kernels[k] for k in ("adamw", "zero_grads", "overflow_check") if k in kernels]
+        ms = sum(k["ms_per_step"] for k in ph)
+        nbytes = sum(k.get("gbs", 0.0) * 1e6 * k["ms_per_step"] for k in ph)
+        out["optimizer_phase"] = {"ms": ms, "bytes": nbytes, "gbs": nbytes / ms / 1e6, "hbm_frac": nbytes / ms / 1e6 / PEAK_HBM_GBS}
     if ministages:
         h2d, d2h = stage.ms.traffic()
         nsteps = steps + warmup

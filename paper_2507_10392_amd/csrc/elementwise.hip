@@ -754,7 +754,7 @@ __device__ __forceinline__ float adamw_one(float p, float g, float& m, float& v,
   return p - h.lr * (mhat / (sqrtf(vhat) + h.eps) + h.wd * p);
 }
 
-// One float4 of p, g, m, v per lane; reads 16 B/element, writes 12 B (+2 B 16-bit copy, +4 B zeroed grad).
+// One float4 of p, g, m, v per lane; reads 16 B/element, writes 12 B (+2 B 16-bit copy; +4 B zeroed grad with h.zero_grad).
 // VEC=false is the scalar variant for ranges that are not 16-byte aligned and for the tail.
 // W is the element type of the working copy (float: params itself is the master).  With h.skip set and *h.skip
 // non-zero (a non-finite gradient was found, loss-scaled fp16 training) nothing but the zeroing of grad happens.
@@ -770,7 +770,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, vo
   if (VEC) {
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     if (skip) {
-      __builtin_nontemporal_store(zero, (f32x4*)(grad + begin + i));
+      if (h.zero_grad) __builtin_nontemporal_store(zero, (f32x4*)(grad + begin + i));
       return;
     }
     // every byte is touched once per step: non-temporal accesses keep the streams out of the caches
@@ -786,7 +786,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, vo
     __builtin_nontemporal_store(p4, (f32x4*)pm);
     __builtin_nontemporal_store(m4, (f32x4*)(m + i));
     __builtin_nontemporal_store(v4, (f32x4*)(v + i));
-    __builtin_nontemporal_store(zero, (f32x4*)(grad + begin + i));
+    if (h.zero_grad) __builtin_nontemporal_store(zero, (f32x4*)(grad + begin + i));
     if (LOW) {
       // The working copy is the rounding of the STORED fp32 value.  Without the barrier the compiler folds the
       // update's last fused multiply-add and the conversion into one mixed-precision instruction that rounds the
@@ -802,7 +802,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, vo
     }
   } else {
     if (skip) {
-      grad[begin + i] = 0.f;
+      if (h.zero_grad) grad[begin + i] = 0.f;
       return;
     }
     float mm = m[i], vv = v[i];
@@ -810,7 +810,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(int64_t n, int64_t begin, vo
     *pm = pn;
     m[i] = mm;
     v[i] = vv;
-    grad[begin + i] = 0.f;
+    if (h.zero_grad) grad[begin + i] = 0.f;
     if (LOW) {
       float q = pn;
       asm volatile("" : "+v"(q));   // as above: round the stored value

@@ -116,9 +116,11 @@ hipError_t ce_fwd(hipStream_t st, DType dt, int T, int V, const void* z, int64_t
 hipError_t ce_bwd(hipStream_t st, DType dt, int T, int V, void* z, int64_t ldz, const int32_t* targets,
                   const float* lse, float scale);
 
-struct AdamW { float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2, grad_scale; const int* skip = nullptr; };
+struct AdamW { float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2, grad_scale; const int* skip = nullptr; bool zero_grad = true; };
 // Elements i in [0,n): flat parameter index begin+i.  dtype BF16: master/m/v indexed by i, grad and
-// params_bf16 by begin+i.  dtype F32: params (float) indexed by begin+i is the master.  grad is zeroed.
+// params_bf16 by begin+i.  dtype F32: params (float) indexed by begin+i is the master.  grad[begin, begin+n) is
+// zeroed when h.zero_grad is set; a caller that clears the whole accumulator anyway leaves that to its fill, which
+// as a pure write stream runs at a higher rate than a fifth write stream inside this kernel.
 hipError_t adamw(hipStream_t st, DType dt, int64_t n, int64_t begin, void* params, float* master, float* grad,
                  float* m, float* v, const AdamW& h);
 hipError_t fill_zero(hipStream_t st, float* p, int64_t n);

@@ -966,6 +966,7 @@ int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale) {
   h.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)c.beta2, (double)t)));
   h.grad_scale = grad_scale;
   h.skip = s->overflow;
+  h.zero_grad = false;   // the whole accumulator is cleared by the fill below
   const int64_t P = count_params(c), b = c.shard_begin, e = c.shard_end, n = e - b;
   // loss-scaled training: a non-finite gradient anywhere in the shard raises the flag, and the update that reads
   // the flag then leaves parameters and moments alone
@@ -975,11 +976,9 @@ int stage_optimizer_step(stage_t* s, int64_t t, float grad_scale) {
   if (!run(s, "adamw", 0, per * n, [&] {
         return adamw(s->st, dt_of(s), n, b, s->params, s->master, s->grad, s->m, s->v, h); }))
     return STAGE_ERR_DEVICE;
-  // gradients outside the shard are dropped too (their owners are the data-parallel peers)
-  if (!run(s, "zero_grads", 0, 4.0 * (P - n), [&] {
-        hipError_t er = fill_zero(s->st, s->grad, b);
-        return er != hipSuccess ? er : fill_zero(s->st, s->grad + e, P - e); }))
-    return STAGE_ERR_DEVICE;
+  // The gradients are dropped after the update (Section 4.1.2), those outside the shard too (their owners are the
+  // data-parallel peers): one fill over the whole accumulator, after the update has read its range.
+  if (!run(s, "zero_grads", 0, 4.0 * P, [&] { return fill_zero(s->st, s->grad, P); })) return STAGE_ERR_DEVICE;
   s->accumulated = 0;
   return STAGE_OK;
 }
