@@ -681,21 +681,42 @@ hipError_t embed_bwd(hipStream_t st, DType dt, int T, int H, int V, const int32_
 }
 
 // ------------------------------------------------------------------ cross entropy
-template <typename T>
+// One workgroup per row, two passes over the row (maximum, then sum of exponentials; the second pass hits in L2).
+// VEC: 16-byte accesses (V and ldz multiples of the vector width, z 16-byte aligned), else element by element.
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void ce_fwd_kernel(int V, const T* __restrict__ z, int64_t ldz,
                                                      const int32_t* __restrict__ targets, float* __restrict__ lse,
                                                      float* __restrict__ rowloss) {
+  constexpr int VN = Vec<T>::N;
   __shared__ float red[4];
   const int t = blockIdx.x;
   const T* zr = z + (int64_t)t * ldz;
   float mx = -INFINITY;
-  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, to_f(zr[c]));
+  if (VEC) {
+    for (int c = threadIdx.x * VN; c < V; c += 256 * VN) {
+      float a[VN];
+      load_vec(zr + c, a);
+#pragma unroll
+      for (int i = 0; i < VN; ++i) mx = fmaxf(mx, a[i]);
+    }
+  } else {
+    for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, to_f(zr[c]));
+  }
   mx = wave_max(mx);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
   __syncthreads();
   mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
   float s = 0.f;
-  for (int c = threadIdx.x; c < V; c += 256) s += expf(to_f(zr[c]) - mx);
+  if (VEC) {
+    for (int c = threadIdx.x * VN; c < V; c += 256 * VN) {
+      float a[VN];
+      load_vec(zr + c, a);
+#pragma unroll
+      for (int i = 0; i < VN; ++i) s += expf(a[i] - mx);
+    }
+  } else {
+    for (int c = threadIdx.x; c < V; c += 256) s += expf(to_f(zr[c]) - mx);
+  }
   s = block_sum<4>(s, red);
   if (threadIdx.x == 0) {
     const float l = mx + logf(s);
@@ -713,34 +734,50 @@ __global__ __launch_bounds__(256) void mean_kernel(int n, const float* __restric
 }
 hipError_t ce_fwd(hipStream_t st, DType dt, int T, int V, const void* z, int64_t ldz, const int32_t* targets,
                   float* lse, float* rowloss, float* loss) {
-  if (dt == F32) hipLaunchKernelGGL(ce_fwd_kernel<float>, dim3(T), dim3(256), 0, st, V, (const float*)z, ldz, targets, lse, rowloss);
-  else if (dt == BF16) hipLaunchKernelGGL(ce_fwd_kernel<bf16>, dim3(T), dim3(256), 0, st, V, (const bf16*)z, ldz, targets, lse, rowloss);
-  else hipLaunchKernelGGL(ce_fwd_kernel<f16>, dim3(T), dim3(256), 0, st, V, (const f16*)z, ldz, targets, lse, rowloss);
+  const int VN = dt == F32 ? 4 : 8;
+  const bool vec = V % VN == 0 && ldz % VN == 0 && ((uintptr_t)z & 15) == 0;
+#define CE_FWD(TT) \
+  if (vec) hipLaunchKernelGGL((ce_fwd_kernel<TT, true>), dim3(T), dim3(256), 0, st, V, (const TT*)z, ldz, targets, lse, rowloss); \
+  else hipLaunchKernelGGL((ce_fwd_kernel<TT, false>), dim3(T), dim3(256), 0, st, V, (const TT*)z, ldz, targets, lse, rowloss)
+  if (dt == F32) { CE_FWD(float); } else if (dt == BF16) { CE_FWD(bf16); } else { CE_FWD(f16); }
+#undef CE_FWD
   hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, st, T, rowloss, loss);
   return hipGetLastError();
 }
-template <typename T>
+// Rows on grid.x (no 65535 limit on the number of tokens), column blocks on grid.y.  VEC as for the forward kernel:
+// a thread then owns one 16-byte vector of its row.  A row without a valid target has no loss term (ce_fwd gives it
+// 0), hence no gradient.
+template <typename T, bool VEC>
 __global__ __launch_bounds__(256) void ce_bwd_kernel(int V, T* z, int64_t ldz, const int32_t* __restrict__ targets,
                                                      const float* __restrict__ lse, float scale) {
-  // rows on grid.x (no 65535 limit on the number of tokens), column blocks on grid.y
+  constexpr int VN = VEC ? Vec<T>::N : 1;
   const int t = blockIdx.x;
-  const int c = blockIdx.y * 256 + threadIdx.x;
+  const int c = (blockIdx.y * 256 + threadIdx.x) * VN;
   if (c >= V) return;
   T* p = z + (int64_t)t * ldz + c;
   const int tg = targets[t];
-  if (tg < 0 || tg >= V) {   // a row without a valid target has no loss term (ce_fwd gives it 0), hence no gradient
-    *p = from_f<T>(0.f);
-    return;
+  const bool ok = tg >= 0 && tg < V;
+  const float l = lse[t];
+  if (VEC) {
+    float a[Vec<T>::N], o[Vec<T>::N];
+    load_vec(p, a);
+#pragma unroll
+    for (int i = 0; i < Vec<T>::N; ++i) o[i] = ok ? scale * (expf(a[i] - l) - (c + i == tg ? 1.f : 0.f)) : 0.f;
+    store_vec(p, o);
+  } else {
+    *p = from_f<T>(ok ? scale * (expf(to_f(*p) - l) - (c == tg ? 1.f : 0.f)) : 0.f);
   }
-  const float pr = expf(to_f(*p) - lse[t]);
-  *p = from_f<T>(scale * (pr - (c == tg ? 1.f : 0.f)));
 }
 hipError_t ce_bwd(hipStream_t st, DType dt, int T, int V, void* z, int64_t ldz, const int32_t* targets,
                   const float* lse, float scale) {
-  dim3 grid((unsigned)T, (unsigned)cdiv(V, 256)), blk(256);
-  if (dt == F32) hipLaunchKernelGGL(ce_bwd_kernel<float>, grid, blk, 0, st, V, (float*)z, ldz, targets, lse, scale);
-  else if (dt == BF16) hipLaunchKernelGGL(ce_bwd_kernel<bf16>, grid, blk, 0, st, V, (bf16*)z, ldz, targets, lse, scale);
-  else hipLaunchKernelGGL(ce_bwd_kernel<f16>, grid, blk, 0, st, V, (f16*)z, ldz, targets, lse, scale);
+  const int VN = dt == F32 ? 4 : 8;
+  const bool vec = V % VN == 0 && ldz % VN == 0 && ((uintptr_t)z & 15) == 0;
+  dim3 grid((unsigned)T, (unsigned)cdiv(V, 256 * (vec ? VN : 1))), blk(256);
+#define CE_BWD(TT) \
+  if (vec) hipLaunchKernelGGL((ce_bwd_kernel<TT, true>), grid, blk, 0, st, V, (TT*)z, ldz, targets, lse, scale); \
+  else hipLaunchKernelGGL((ce_bwd_kernel<TT, false>), grid, blk, 0, st, V, (TT*)z, ldz, targets, lse, scale)
+  if (dt == F32) { CE_BWD(float); } else if (dt == BF16) { CE_BWD(bf16); } else { CE_BWD(f16); }
+#undef CE_BWD
   return hipGetLastError();
 }
 

@@ -575,10 +575,11 @@ def test_embedding_is_bit_exact_and_scatter_matches(gpu_device, dtype):
 
 
 @pytest.mark.parametrize("dtype", [0, 1, 2])
-def test_cross_entropy(gpu_device, dtype):
-    print(f"[case] cross entropy dtype={dtype}", flush=True)
+@pytest.mark.parametrize("V", [2000, 1001])     # whole 16-byte vectors per row, and a width that needs the element-wise kernels
+def test_cross_entropy(gpu_device, dtype, V):
+    print(f"[case] cross entropy dtype={dtype} V={V}", flush=True)
     rng = np.random.default_rng(8)
-    T, V = 97, 2000
+    T = 97
     td = TD[dtype]
     z = draw(rng, (T, V), dtype, 3.0)
     tg = rng.integers(0, V, T).astype(np.int32)
