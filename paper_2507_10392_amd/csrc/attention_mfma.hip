@@ -147,8 +147,11 @@ __device__ __forceinline__ void unrotate4(float (&x)[4], const float2* __restric
 }
 
 // ------------------------------------------------------------------------------------------ forward
-// grid ceil(S/128)*nh*mb; wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const e16* __restrict__ q, const e16* __restrict__ k,
+// grid ceil(S/(32 NW))*nh*mb, NW waves; wave w owns queries q0 + 32w .. +31; heavy (late) blocks are launched first.
+// NW = 4: two workgroups per CU.  NW = 8: one workgroup per CU whose staged K/V tiles serve 256 queries, so a wave
+// issues half as many tile loads and LDS stores per key tile (used when that still gives every CU a workgroup).
+template <int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(int S, const e16* __restrict__ q, const e16* __restrict__ k,
                                                        const e16* __restrict__ v, int64_t ld, e16* __restrict__ o,
                                                        int64_t ldo, float* __restrict__ lse, float scale_log2, int nh,
                                                        int mb) {
@@ -156,13 +159,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const e16* __re
   e16* smem = reinterpret_cast<e16*>(smem_raw);            // [2][K tile | V tile]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const BlockId bid = block_id(nh, mb);
-  const int qb = (S + 127) / 128 - 1 - bid.rank, h = bid.h, b = bid.b;
+  const int qb = (S + 32 * NW - 1) / (32 * NW) - 1 - bid.rank, h = bid.h, b = bid.b;
   const int64_t tok0 = (int64_t)b * S;
   const e16* qh = q + tok0 * ld + h * D;
   const e16* kh = k + tok0 * ld + h * D;
   const e16* vh = v + tok0 * ld + h * D;
   const __amdgpu_buffer_rsrc_t rsk = head_rsrc(kh, ld, S), rsv = head_rsrc(vh, ld, S);
-  const int q0 = qb * 128, wq0 = q0 + wave * 32;
+  const int q0 = qb * 32 * NW, wq0 = q0 + wave * 32;
   const int my_q = wq0 + (lane & 31);
 
   e16x8 qf[8];
@@ -174,9 +177,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const e16* __re
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  const int last_q = min(q0 + 127, S - 1);
+  const int last_q = min(q0 + 32 * NW - 1, S - 1);
   const int ntiles = last_q / TR + 1;
-  TileRegs<256> kr, vr;
+  TileRegs<64 * NW> kr, vr;
   fetch_tile(kr, rsk, (int)ld, 0, tid);
   fetch_tile(vr, rsv, (int)ld, 0, tid);
   put_tile(kr, smem, tid);
@@ -272,9 +275,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int S, const e16* __re
 }
 
 // ------------------------------------------------------------------------------------------ dQ
-// grid ceil(S/128)*nh*mb; wave w owns queries q0+32w..; loops over K/V tiles up to the diagonal.
+// grid ceil(S/(32 NW))*nh*mb, NW waves (4 or 8 as in the forward kernel); wave w owns queries q0+32w..; loops over K/V
+// tiles up to the diagonal.
 // dQ^T[d][q] += K^T[d][key] dS^T[key][q],  dS^T = P^T o (dP^T - delta_q),  dP^T = V dO^T.
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const e16* __restrict__ q, const e16* __restrict__ k,
+template <int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_bwd_dq_kernel(int S, const e16* __restrict__ q, const e16* __restrict__ k,
                                                           const e16* __restrict__ v, int64_t ld,
                                                           const e16* __restrict__ o, const e16* __restrict__ dout,
                                                           int64_t ldo, const float* __restrict__ lse,
@@ -285,14 +290,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const e16* _
   e16* smem = reinterpret_cast<e16*>(smem_raw);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const BlockId bid = block_id(nh, mb);
-  const int qb = (S + 127) / 128 - 1 - bid.rank, h = bid.h, b = bid.b;
+  const int qb = (S + 32 * NW - 1) / (32 * NW) - 1 - bid.rank, h = bid.h, b = bid.b;
   const int64_t tok0 = (int64_t)b * S;
   const e16* qh = q + tok0 * ld + h * D;
   const e16* kh = k + tok0 * ld + h * D;
   const e16* vh = v + tok0 * ld + h * D;
   const e16* doh = dout + tok0 * ldo + h * D;
   const __amdgpu_buffer_rsrc_t rsk = head_rsrc(kh, ld, S), rsv = head_rsrc(vh, ld, S);
-  const int q0 = qb * 128, wq0 = q0 + wave * 32;
+  const int q0 = qb * 32 * NW, wq0 = q0 + wave * 32;
   const int my_q = wq0 + (lane & 31);
   const float scale_log2 = scale * LOG2E;
 
@@ -320,9 +325,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(int S, const e16* _
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-  const int last_q = min(q0 + 127, S - 1);
+  const int last_q = min(q0 + 32 * NW - 1, S - 1);
   const int ntiles = last_q / TR + 1;
-  TileRegs<256> kr, vr;
+  TileRegs<64 * NW> kr, vr;
   fetch_tile(kr, rsk, (int)ld, 0, tid);
   fetch_tile(vr, rsv, (int)ld, 0, tid);
   put_tile(kr, smem, tid);
@@ -534,6 +539,13 @@ __global__ __launch_bounds__(64 * NW) void attn_bwd_dkv_kernel(int S, const e16*
 constexpr size_t SMEM_FWD = 4 * TILE * sizeof(e16);                    // 77824
 constexpr size_t smem_dkv(int nw) { return 4 * TILE * sizeof(e16) + 256 * sizeof(float) + (size_t)nw * 32 * LDT * sizeof(e16); }
 
+// Blocks of 256 rows (8 waves) instead of 128 (4 waves): for the key blocks of the dK/dV kernel whenever that still
+// gives every CU a workgroup; for the query blocks of the forward and dQ kernels only from S = 4096 on (measured: 7 % and
+// 3 % faster at S = 4096 with 32 heads, 7 % slower at S = 2048 with 80 head-sequences, where a block has half the tiles to
+// amortise its idle waves on the diagonal).
+inline bool wide_blocks(int S, int nh, int mb) { return cdiv(S, 256) * nh * mb >= 256; }
+inline bool wide_query_blocks(int S, int nh, int mb) { return wide_blocks(S, nh, mb) && S >= 4096; }
+
 template <typename K> hipError_t set_smem(K kern, size_t bytes, bool& done) {
   if (done) return hipSuccess;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
@@ -550,12 +562,17 @@ bool attn_mfma_supported(DType dt, int S, int d) { return (dt == BF16 || dt == F
 hipError_t ZS_ATTN_NAME(attn_fwd_mfma)(hipStream_t st, int mb, int S, int nh, int d, const void* q, const void* k, const void* v,
                          int64_t ld, void* o, int64_t ldo, float* lse) {
   if ((int64_t)S * ld * 2 >= (1ll << 31)) return hipErrorInvalidValue;      // 32-bit buffer offsets
-  static bool cfg = false;
-  hipError_t e = set_smem(attn_fwd_kernel, SMEM_FWD, cfg);
+  static bool cfg4 = false, cfg8 = false;
+  hipError_t e = set_smem(attn_fwd_kernel<4>, SMEM_FWD, cfg4);
+  if (e == hipSuccess) e = set_smem(attn_fwd_kernel<8>, SMEM_FWD, cfg8);
   if (e != hipSuccess) return e;
-  dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
-  hipLaunchKernelGGL(attn_fwd_kernel, grid, blk, SMEM_FWD, st, S, (const e16*)q, (const e16*)k, (const e16*)v, ld,
-                     (e16*)o, ldo, lse, LOG2E / sqrtf((float)d), nh, mb);
+  // 256 queries per workgroup when that still gives every CU a workgroup, else 128
+  if (wide_query_blocks(S, nh, mb))
+    hipLaunchKernelGGL(attn_fwd_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), SMEM_FWD, st, S, (const e16*)q,
+                       (const e16*)k, (const e16*)v, ld, (e16*)o, ldo, lse, LOG2E / sqrtf((float)d), nh, mb);
+  else
+    hipLaunchKernelGGL(attn_fwd_kernel<4>, dim3((unsigned)(cdiv(S, 128) * nh * mb)), dim3(256), SMEM_FWD, st, S, (const e16*)q,
+                       (const e16*)k, (const e16*)v, ld, (e16*)o, ldo, lse, LOG2E / sqrtf((float)d), nh, mb);
   return hipGetLastError();
 }
 
@@ -563,17 +580,23 @@ hipError_t ZS_ATTN_NAME(attn_bwd_mfma)(hipStream_t st, int mb, int S, int nh, in
                          int64_t ld, const void* o, const void* dout, int64_t ldo, const float* lse, float* delta,
                          void* dq, void* dk, void* dv, int64_t ldd, const float2* rope) {
   if ((int64_t)S * (ld > ldo ? ld : ldo) * 2 >= (1ll << 31)) return hipErrorInvalidValue;   // 32-bit buffer offsets
-  static bool cfg1 = false, cfg2 = false, cfg3 = false;
-  hipError_t e = set_smem(attn_bwd_dq_kernel, SMEM_FWD, cfg1);
+  static bool cfg1 = false, cfg1b = false, cfg2 = false, cfg3 = false;
+  hipError_t e = set_smem(attn_bwd_dq_kernel<4>, SMEM_FWD, cfg1);
+  if (e == hipSuccess) e = set_smem(attn_bwd_dq_kernel<8>, SMEM_FWD, cfg1b);
   if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<4>, smem_dkv(4), cfg2);
   if (e == hipSuccess) e = set_smem(attn_bwd_dkv_kernel<8>, smem_dkv(8), cfg3);
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)d);
   dim3 grid((unsigned)(cdiv(S, 128) * nh * mb)), blk(256);
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, grid, blk, SMEM_FWD, st, S, (const e16*)q, (const e16*)k, (const e16*)v, ld,
-                     (const e16*)o, (const e16*)dout, ldo, lse, delta, (e16*)dq, ldd, scale, nh, mb, rope);
-  // 256 keys per workgroup when that still gives every CU a workgroup, else 128
-  if (cdiv(S, 256) * nh * mb >= 256) {
+  const bool wide = wide_blocks(S, nh, mb);
+  if (wide_query_blocks(S, nh, mb))
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), SMEM_FWD, st, S, (const e16*)q,
+                       (const e16*)k, (const e16*)v, ld, (const e16*)o, (const e16*)dout, ldo, lse, delta, (e16*)dq, ldd, scale, nh,
+                       mb, rope);
+  else
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<4>, grid, blk, SMEM_FWD, st, S, (const e16*)q, (const e16*)k, (const e16*)v, ld,
+                       (const e16*)o, (const e16*)dout, ldo, lse, delta, (e16*)dq, ldd, scale, nh, mb, rope);
+  if (wide) {
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<8>, dim3((unsigned)(cdiv(S, 256) * nh * mb)), dim3(512), smem_dkv(8), st,
                        S, (const e16*)q, (const e16*)k, (const e16*)v, ld, (const e16*)dout, ldo, lse, delta, (e16*)dk,
                        (e16*)dv, ldd, scale, nh, mb, rope);

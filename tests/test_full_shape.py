@@ -109,9 +109,11 @@ def test_c4b_recompute_under_budget(gpu_device):
     assert bool(torch.isfinite(g_r).all()) and float(g_r.abs().max()) > 0
 
 
-def test_attention_full_size_heads_match_oracle(gpu_device):
-    """S = 4096, 32 heads of 128: every row of the first and the last head, forward and backward."""
-    mb, S, nh, d = 1, 4096, 32, 128
+@pytest.mark.parametrize("S,nh", [(4096, 32), (4100, 16)], ids=["C3", "ragged"])
+def test_attention_full_size_heads_match_oracle(gpu_device, S, nh):
+    """32 heads of 128 at S = 4096, and a sequence length that is no multiple of any block (both take the kernels with
+    256-row blocks): every row of the first and the last head, forward and backward."""
+    mb, d = 1, 128
     H = nh * d
     print(f"[case] full-size attention S={S} nh={nh}", flush=True)
     rng = np.random.default_rng(21)
