@@ -541,10 +541,27 @@ hipError_t rope_apply(hipStream_t st, DType dt, int T, int S, int ncols, int d, 
 }
 
 // ------------------------------------------------------------------ activations
-__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+// GELU(z) = z Phi(z) with Phi the normal distribution function (the erf form) and its derivative Phi(z) + z phi(z).
+// erf comes from the rational approximation 7.1.26 of Abramowitz and Stegun, |error| <= 1.5e-7, i.e. fp32 rounding level:
+// erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p x), x >= 0.  With x = |z| / sqrt(2) its exponential is
+// exp(-z^2 / 2), the one the density phi needs as well, so value and derivative cost one hardware exp2 and one hardware
+// reciprocal instead of erff and expf (these kernels were bound by that arithmetic, not by memory).
+__device__ __forceinline__ void gelu_parts(float z, float& Phi, float& phi) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  Phi = 0.5f * (1.0f + copysignf(1.0f - poly * e, z));
+  phi = 0.39894228040143268f * e;
+}
+__device__ __forceinline__ float gelu_f(float z) {
+  float Phi, phi;
+  gelu_parts(z, Phi, phi);
+  return z * Phi;
+}
 __device__ __forceinline__ float gelu_df(float z) {
-  const float Phi = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
-  const float phi = 0.39894228040143268f * expf(-0.5f * z * z);
+  float Phi, phi;
+  gelu_parts(z, Phi, phi);
   return Phi + z * phi;
 }
 
