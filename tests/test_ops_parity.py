@@ -665,3 +665,27 @@ def test_adamw_kernel_matches_oracle_for_t_1_2_10(gpu_device, dtype, n, begin):
             assert np.array_equal(back(params)[:begin], rnd(p0)[:begin].astype(np.float64))
         po = got_p.copy()      # continue from the GPU's fp32 state so that only one step's rounding is compared
         mo, vo = back(m)[:n].copy(), back(v)[:n].copy()
+
+
+def test_cross_entropy_backward_beyond_65535_tokens(gpu_device):
+    """More tokens than a grid's y and z dimensions can count (65535): the rows ride on grid.x.  Sampled rows against the
+    definition, first and last row included."""
+    print("[case] cross entropy backward T=70001", flush=True)
+    rng = np.random.default_rng(28)
+    T, V = 70001, 24
+    z = draw(rng, (T, V), 0, 2.0)
+    tg = rng.integers(0, V, T).astype(np.int32)
+    zd = dev(z)
+    lse, rowloss, loss = torch.empty(T, device="cuda"), torch.empty(T, device="cuda"), torch.empty(1, device="cuda")
+    zs.ops.cross_entropy(st(), 0, T, V, zd, V, dev(tg), lse, rowloss, loss, 0.0, 0)
+    zs.ops.cross_entropy(st(), 0, T, V, zd, V, dev(tg), lse, None, None, 1.0, 1)
+    got = back(zd)
+    rows = np.concatenate([[0, 65534, 65535, 65536, T - 1], rng.integers(0, T, 200)])
+    z64 = z[rows].astype(np.float64)
+    p = np.exp(z64 - z64.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    p[np.arange(len(rows)), tg[rows]] -= 1
+    assert rel_err(got[rows], p) <= 1e-5
+    z_all = z.astype(np.float64)
+    lse_o = np.log(np.exp(z_all).sum(axis=1))
+    assert abs(back(loss)[0] - (lse_o - z_all[np.arange(T), tg]).mean()) <= 1e-5
