@@ -52,13 +52,13 @@ constexpr int DEAD = 0x40000000;
 // slabs past the end) would run into the next row and are sent out of range.
 template <int R, int NT>
 __device__ __forceinline__ void load_kmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int k0,
-                                            int K, int tid) {
+                                            int K, int tid, int i0 = 0, int i1 = R * 8 / NT) {
   const int vo = k0 + (tid & 7) * 8 >= K ? DEAD : voff;
 #pragma unroll
   for (int i = 0; i < R * 8 / NT; ++i)
-    f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, vo, ((row0 + (NT / 8) * i) * ld + k0) * 2, 0);
+    if (i >= i0 && i < i1) f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, vo, ((row0 + (NT / 8) * i) * ld + k0) * 2, 0);
 }
-// Stores vectors [i0, i1) of the thread's share.
+// (load_kmajor, like the other three, handles vectors [i0, i1) of the thread's share)
 template <int R, int NT>
 __device__ __forceinline__ void store_kmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
   bf16* p = lds + (tid >> 3) * LDK + (tid & 7) * 8;
@@ -81,11 +81,12 @@ template <int R> __device__ __forceinline__ int voff_rmajor_two(int ld, int tid,
   return row0 + jj * 8 >= nrows ? DEAD : ((tid / PER) * ld + jj * 8 + (j >= HALF ? second : 0)) * 2;
 }
 template <int R, int NT>
-__device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int k0) {
+__device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc_t rs, int voff, int ld, int row0, int k0,
+                                            int i0 = 0, int i1 = R * 8 / NT) {
   constexpr int KSTEP = NT / (R / 8);             // k-lines covered by one pass of the NT threads
 #pragma unroll
   for (int i = 0; i < R * 8 / NT; ++i)
-    f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((k0 + KSTEP * i) * ld + row0) * 2, 0);
+    if (i >= i0 && i < i1) f.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, ((k0 + KSTEP * i) * ld + row0) * 2, 0);
 }
 template <int R, int NT>
 __device__ __forceinline__ void store_rmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
@@ -389,23 +390,24 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
                     : GLU == 1 ? voff_rmajor_two<BN>(ldb, tid, nb0, g.N, (int)g.sB)
                                : voff_rmajor<BN>(ldb, tid, n0, g.N);
 
-  auto fetch = [&](int kt, Frag<BM, NT>& fa0, Frag<BN, NT>& fb0) {
+  constexpr int VA = BM * 8 / NT, VB = BN * 8 / NT;        // 16-byte vectors per thread and slab
+  static_assert(VA % 4 == 0 && VB % 4 == 0, "a quarter of the slab is stored per MFMA step");
+  // Loads vectors [i0, i1) of the thread's share of slab kt, counted over the A vectors followed by the B vectors.
+  auto fetch = [&](int kt, Frag<BM, NT>& fa0, Frag<BN, NT>& fb0, int i0 = 0, int i1 = 1 << 20) {
     const int k0 = kt * BK;
-    if (TA == 0) load_kmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0, g.K, tid);
-    else load_rmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0);
+    if (TA == 0) load_kmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0, g.K, tid, i0, i1);
+    else load_rmajor<BM, NT>(fa0, rsA, voffA, lda, m0, k0, i0, i1);
     if (TB == 1) {
       int vo = voffB;
       if (SEG && !PAIR) {  // the thread's k offset inside the slab is fixed, so one segment lookup per slab
         const int seg = (k0 + (tid & 7) * 8) / g.kseg;
         vo += seg * ((int)g.segB - g.kseg) * 2;          // element (n, k) of segment seg lies at seg*segB + n*ldb + k - seg*kseg
       }
-      load_kmajor<BN, NT>(fb0, rsB, vo, ldb, n0, k0, g.K, tid);
+      load_kmajor<BN, NT>(fb0, rsB, vo, ldb, n0, k0, g.K, tid, i0 - VA, i1 - VA);
     } else {
-      load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, nb0, k0);
+      load_rmajor<BN, NT>(fb0, rsB, voffB, ldb, nb0, k0, i0 - VA, i1 - VA);
     }
   };
-  constexpr int VA = BM * 8 / NT, VB = BN * 8 / NT;        // 16-byte vectors per thread and slab
-  static_assert(VA % 4 == 0 && VB % 4 == 0, "a quarter of the slab is stored per MFMA step");
   auto stash_a = [&](int buf, const Frag<BM, NT>& fa, int i0 = 0, int i1 = 64) {
     bf16* As = smem + buf * (SLAB_A + SLAB_B);
     if (TA == 0) store_kmajor<BM, NT>(fa, As, tid, i0, i1); else store_rmajor<BM, NT>(fa, As, tid, i0, i1);
@@ -415,8 +417,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     if (TB == 1) store_kmajor<BN, NT>(fb, Bs, tid, i0, i1); else store_rmajor<BN, NT>(fb, Bs, tid, i0, i1);
   };
   // multiplies the slab in LDS buffer `buf`; after each of the four MFMA steps it writes a quarter of the
-  // next slab (held in fa, fb) into the other buffer, which nobody reads now
-  auto multiply = [&](int buf, const Frag<BM, NT>& fa, const Frag<BN, NT>& fb) {
+  // next slab (held in fa, fb) into the other buffer, which nobody reads now.  The loads of the slab after that
+  // are issued an eighth at a time, after every half MFMA step (`load(i0, i1)` loads vectors [i0, i1) of the thread's
+  // share): the CU's load unit takes 16 cycles per 1 KB wave load, and a wave that issues its whole share at once
+  // (64 loads per workgroup and slab, all waves at the same point of the loop) waits in that unit's queue for
+  // hundreds of cycles in which it issues no MFMA.  The scheduling fences keep the compiler from gathering the loads
+  // at the end of the loop body again.
+  constexpr int VL = (VA + VB) / 8;                        // vectors per load group
+  auto multiply = [&](int buf, const Frag<BM, NT>& fa, const Frag<BN, NT>& fb, auto&& load) {
     const bf16* As = smem + buf * (SLAB_A + SLAB_B);
     const bf16* Bs = As + SLAB_A;
 #pragma unroll
@@ -429,12 +437,21 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       for (int j = 0; j < NJ; ++j)
         b[j] = TB == 1 ? frag_kmajor(Bs, wn + j * 32, ks * 16, lane) : frag_rmajor<BN>(Bs, wn + j * 32, ks * 16, lane);
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
+      for (int i = 0; i < MI; ++i) {
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = mfma_32x32x16<E>(b[j], a[i], acc[i][j]);
+        if (i == MI / 2 - 1) {
+          __builtin_amdgcn_sched_barrier(0);
+          load(2 * ks * VL, (2 * ks + 1) * VL);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
       stash_a(buf ^ 1, fa, ks * VA / 4, (ks + 1) * VA / 4);
       stash_b(buf ^ 1, fb, ks * VB / 4, (ks + 1) * VB / 4);
+      __builtin_amdgcn_sched_barrier(0);
+      load((2 * ks + 1) * VL, (2 * ks + 2) * VL);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
@@ -445,9 +462,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     // pair lies inside one part (kseg is a multiple of two slabs), and the descriptors change between the inner
     // loops, so the inner loop is that of the single-range kernel.  After the last part comes an empty one whose
     // single pair of loads returns zeros while the last real pair is multiplied.
-    auto fetch_part = [&](int kin, Frag<BM, NT>& fa, Frag<BN, NT>& fb) {
-      load_rmajor<BM, NT>(fa, curA, voffA, lda, m0, kin);
-      load_rmajor<BN, NT>(fb, curB, voffB, ldb, n0, kin);
+    auto fetch_part = [&](int kin, Frag<BM, NT>& fa, Frag<BN, NT>& fb, int i0 = 0, int i1 = 1 << 20) {
+      load_rmajor<BM, NT>(fa, curA, voffA, lda, m0, kin, i0, i1);
+      load_rmajor<BN, NT>(fb, curB, voffB, ldb, n0, kin, i0 - VA, i1 - VA);
     };
     const int full = K1 / (2 * BK);                                    // slab pairs of a part of kseg rows
     const int tail = (g.K - g.nx * K1 + 2 * BK - 1) / (2 * BK);        // of the last part (rows past its end read as zero)
@@ -459,11 +476,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     for (int p = 0; p <= g.nx + 1; ++p) {
       const int pairs = p < g.nx ? full : p == g.nx ? tail : 1;
       for (int j = p == 0 ? 1 : 0; j < pairs; ++j) {
-        fetch_part(j * 2 * BK, fa0, fb0);
-        multiply(0, fa1, fb1);
+        multiply(0, fa1, fb1, [&](int i0, int i1) { fetch_part(j * 2 * BK, fa0, fb0, i0, i1); });
         __syncthreads();
-        fetch_part(j * 2 * BK + BK, fa1, fb1);
-        multiply(1, fa0, fb0);
+        multiply(1, fa0, fb0, [&](int i0, int i1) { fetch_part(j * 2 * BK + BK, fa1, fb1, i0, i1); });
         __syncthreads();
       }
       curA = part_a(p + 1);
@@ -476,11 +491,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     fetch(1, fa1, fb1);
     __syncthreads();
     for (int kt = 0; kt < nk; kt += 2) {
-      fetch(kt + 2, fa0, fb0);
-      multiply(0, fa1, fb1);
+      multiply(0, fa1, fb1, [&](int i0, int i1) { fetch(kt + 2, fa0, fb0, i0, i1); });
       __syncthreads();
-      fetch(kt + 3, fa1, fb1);
-      multiply(1, fa0, fb0);
+      multiply(1, fa0, fb0, [&](int i0, int i1) { fetch(kt + 3, fa1, fb1, i0, i1); });
       __syncthreads();
     }
   }
