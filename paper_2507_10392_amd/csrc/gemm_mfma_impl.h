@@ -1,17 +1,19 @@
-// 16-bit (bf16 or IEEE half) GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16 / _f16), fp32 accumulation: the tile kernel,
+// 16-bit (bf16 or IEEE half) GEMM on the CDNA4 matrix cores (v_mfma_f32_16x16x32_bf16 / _f16), fp32 accumulation: the tile kernel,
 // templated on the workgroup tile BM x BN and the number of wavefronts.
 //
 // One workgroup of 4 (2 x 2) or 8 (2 x 4) wavefronts computes a BM x BN tile of C; each wavefront owns
-// its part as MFMA blocks of 32x32 (16 accumulator registers per block and lane).
+// its part as MFMA blocks of 16x16 (4 accumulator registers per block and lane).
 // The K loop walks 64-wide slabs.  A slab of each operand is fetched from HBM with 16-byte buffer
-// loads into registers one iteration ahead and stored into one of two LDS buffers exactly as it
-// lies in memory:
-//   * contraction index contiguous in memory  -> LDS [row][k], rows padded to 72 elements; an MFMA
-//     operand fragment (8 consecutive k of one row) is one ds_read_b128;
+// loads into registers one iteration ahead and stored into one of two LDS buffers:
+//   * contraction index contiguous in memory  -> LDS [row][k], 128-byte rows whose 16-byte pieces are
+//     permuted by the row index (piece p of row r at position p ^ r%8); an MFMA operand fragment
+//     (8 consecutive k of one row) is one ds_read_b128;
 //   * row index contiguous in memory (B of y = x W with W stored [in,out]; both operands of
-//     dW = x^T dy) -> LDS [k][row], rows padded by 16 elements; the fragment is two
-//     ds_read_b64_tr_b16, the LDS transpose read of gfx950, each returning 4 consecutive k.
-// The paddings put the 16 lanes that the LDS serves together on distinct banks.
+//     dW = x^T dy) -> LDS [k][row], k-lines padded by 32 elements, pairs of 16-row chunks swapped on
+//     the odd eights of k; the fragment is two ds_read_b64_tr_b16, the LDS transpose read of gfx950,
+//     each returning 4 consecutive k.
+// Permutation and padding keep slab stores and fragment reads free of bank conflicts (measured per
+// access pattern: the LDS does not serve a wave's 16-byte accesses in groups of 16 consecutive lanes).
 // Workgroup ids are remapped so that the 8 XCDs (ids are dealt round-robin to them) each work
 // on a compact patch of C and re-use their own L2's A rows and B columns.
 // The 256x256 tile runs 8 wavefronts (128 accumulator registers each, two waves per SIMD); the 128x128 tile
@@ -24,9 +26,12 @@ namespace zs {
 namespace gemm_impl {
 
 constexpr int BK = 64;
-constexpr int LDK = BK + 8;                       // [row][k] layout: padded row length (144 bytes)
+constexpr int LDK = BK;                           // [row][k] layout: 128-byte rows, no padding; the 16-byte piece p of row r sits at
+                                                  // position p ^ (r % 8), which keeps both the slab stores (8 rows x 8 pieces per wave)
+                                                  // and the fragment reads (16 rows x 4 pieces per wave) free of bank conflicts
 // [k][row] slabs: k-lines are padded by RPAD elements.  A transpose read serves 32 lanes per cycle, which
-// touch 4 k-lines x 64 bytes; with k-lines 16 banks apart (mod 64) those are 64 different banks.
+// touch 8 k-lines x 32 bytes; k-lines are 16 banks apart (mod 64) and the chunk swap of store_rmajor moves
+// the second four lines by 8 banks, so those are 64 different banks.
 constexpr int RPAD = 32;
 constexpr int slab_elems(int R) { return R * LDK > BK * (R + RPAD) ? R * LDK : BK * (R + RPAD); }
 
@@ -61,7 +66,8 @@ __device__ __forceinline__ void load_kmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc
 // (load_kmajor, like the other three, handles vectors [i0, i1) of the thread's share)
 template <int R, int NT>
 __device__ __forceinline__ void store_kmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
-  bf16* p = lds + (tid >> 3) * LDK + (tid & 7) * 8;
+  static_assert((NT / 8) % 8 == 0, "a thread's row keeps its value mod 8 over the passes");
+  bf16* p = lds + (tid >> 3) * LDK + (((tid & 7) ^ ((tid >> 3) & 7)) * 8);
 #pragma unroll
   for (int i = 0; i < R * 8 / NT; ++i)
     if (i >= i0 && i < i1) *reinterpret_cast<u32x4*>(p + (NT / 8) * i * LDK) = f.v[i];
@@ -91,22 +97,27 @@ __device__ __forceinline__ void load_rmajor(Frag<R, NT>& f, __amdgpu_buffer_rsrc
 template <int R, int NT>
 __device__ __forceinline__ void store_rmajor(const Frag<R, NT>& f, bf16* lds, int tid, int i0 = 0, int i1 = R * 8 / NT) {
   constexpr int KSTEP = NT / (R / 8), LDR = R + RPAD;
-  bf16* p = lds + (tid / (R / 8)) * LDR + (tid % (R / 8)) * 8;
+  static_assert(KSTEP % 16 == 0, "bit 3 of a thread's k-line must not depend on the pass");
+  const int kl = tid / (R / 8);                   // k-line of pass 0; passes add multiples of 16
+  bf16* p = lds + kl * LDR + (((tid % (R / 8)) ^ (((kl >> 3) & 1) << 1)) * 8);   // 16-row chunks swap in pairs on odd eights of k
 #pragma unroll
   for (int i = 0; i < R * 8 / NT; ++i)
     if (i >= i0 && i < i1) *reinterpret_cast<u32x4*>(p + KSTEP * i * LDR) = f.v[i];
 }
 
-// MFMA operand fragment for lane (row = lane%32, g = lane/32): the 8 values k = k16 + 8g .. +7 of that row.
-__device__ __forceinline__ bf16x8 frag_kmajor(const bf16* tile, int row0, int k16, int lane) {
-  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 31)) * LDK + k16 + 8 * (lane >> 5));
+// MFMA operand fragment for lane (row = lane%16, g = lane/16): the 8 values k = k32 + 8g .. +7 of that row
+// (row0 is a multiple of 16, so the row's value mod 8 is the lane's).
+__device__ __forceinline__ bf16x8 frag_kmajor(const bf16* tile, int row0, int k32, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 15)) * LDK + (((k32 >> 3) + (lane >> 4)) ^ (lane & 7)) * 8);
 }
 // Same fragment from a [k][row] tile.  One transpose read serves 16 lanes: lane r of the group points at
-// 4 consecutive rows of k-line (r/4) and receives the 4 k-lines' values of ONE row.
-template <int R> __device__ __forceinline__ bf16x8 frag_rmajor(const bf16* tile, int row0, int k16, int lane) {
+// 4 consecutive rows of k-line (r/4) and receives the 4 k-lines' values of ONE row; group g reads k-lines k32 + 8g ...
+// The LDS serves two groups per cycle, here the SAME 16 rows of k-lines 8 apart, i.e. the same banks; so the slab is
+// stored with each pair of 16-row chunks swapped on the odd eights of k (store_rmajor), and the read undoes it.
+template <int R> __device__ __forceinline__ bf16x8 frag_rmajor(const bf16* tile, int row0, int k32, int lane) {
   constexpr int LDR = R + RPAD;
   const int r = lane & 15, gi = lane >> 4;
-  const bf16* p = tile + (k16 + 8 * (gi >> 1) + (r >> 2)) * LDR + row0 + 16 * (gi & 1) + 4 * (r & 3);
+  const bf16* p = tile + (k32 + 8 * gi + (r >> 2)) * LDR + ((row0 + 4 * (r & 3)) ^ ((gi & 1) << 4));
   union { struct { s16x4 a, b; } s; bf16x8 v; } u;
   u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
   u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * LDR));
@@ -132,24 +143,18 @@ __device__ __forceinline__ void tile_origin(int pid, int tiles_m, int tiles_n, i
 
 // Both epilogues pass the tile through LDS (free after the K loop) as fp32, in two halves of BM/2 rows.
 // The MFMAs were issued with the operands swapped, mfma(B fragment, A fragment), which yields the
-// transposed block: acc[i][j][r] is C[row, col] with row = lane%32 and col = 8*(r/4) + 4*(lane/32) + r%4,
-// so a lane owns 4 consecutive columns per register quad and writes it as one float4.
+// transposed block: acc[i][j][r] is C[row, col] of 16x16 block (i, j) with row = lane%16 and col = 4*(lane/16) + r,
+// so a lane owns 4 consecutive columns per block and writes them as one float4.
 template <int BN> struct Staging { static constexpr int LDW = BN + 4; };   // padded row (floats)
 
 template <int BN, int MI, int NJ>
-__device__ __forceinline__ void stage_quads(float* stage, f32x16 (&acc)[MI][NJ], int wn, int lane) {
+__device__ __forceinline__ void stage_quads(float* stage, f32x4 (&acc)[MI][NJ], int wn, int lane) {
   constexpr int LDW = Staging<BN>::LDW;
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        f32x4 q;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) q[e] = acc[i][j][4 * c + e];
-        *reinterpret_cast<f32x4*>(stage + (i * 32 + (lane & 31)) * LDW + wn + j * 32 + 8 * c + 4 * (lane >> 5)) = q;
-      }
+      *reinterpret_cast<f32x4*>(stage + (i * 16 + (lane & 15)) * LDW + wn + j * 16 + 4 * (lane >> 4)) = acc[i][j];
 }
 
 // Epilogue for C (fp32) += product (no bias, no residual).  After staging, ALL threads walk the half tile
@@ -159,7 +164,7 @@ __device__ __forceinline__ void stage_quads(float* stage, f32x16 (&acc)[MI][NJ],
 // are sent there, so the ragged edge needs no branches.  A tile belongs to one workgroup and launches
 // are ordered by the stream, so the sum over microbatches is formed in a fixed order.
 template <int BM, int BN, int NT, int MI, int NJ>
-__device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
+__device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x4 (&acc)[MI][NJ], int m0, int n0, int wave_m,
                                                int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
   static_assert((BM / 2) * LDW * 4 <= 2 * (slab_elems(BM) + slab_elems(BN)) * 2, "staging tile must fit the K-loop buffers");
@@ -195,19 +200,22 @@ __device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x16 (&ac
 }
 
 // The matrix-core instruction for the element type E; fragments travel as 16-bit containers (bf16x8).
-template <typename E> __device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c);
-template <> __device__ __forceinline__ f32x16 mfma_32x32x16<bf16>(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+// 16x16x32 rather than 32x32x16: the same flops per cycle, but per flop it moves a fifth fewer register bytes (A, B, C
+// and D of one instruction), and the chip, which runs these kernels at its power limit, clocks higher for it: with random
+// operands in registers and no memory traffic 2.08 PFLOP/s are sustained against 1.79-1.85.
+template <typename E> __device__ __forceinline__ f32x4 mfma_16x16x32(bf16x8 a, bf16x8 b, f32x4 c);
+template <> __device__ __forceinline__ f32x4 mfma_16x16x32<bf16>(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-template <> __device__ __forceinline__ f32x16 mfma_32x32x16<f16>(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+template <> __device__ __forceinline__ f32x4 mfma_16x16x32<f16>(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
 // Epilogue for 16-bit output (E = bf16 or IEEE half): after staging, ALL threads read rows back 8 columns at a time, add bias and
 // residual in fp32, round once to bf16 and store 16 bytes per lane, consecutive lanes covering
 // consecutive 16-byte pieces of a row of C.
 template <typename E, int BM, int BN, int NT, int MI, int NJ, int GLU>
-__device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&acc)[MI][NJ], int m0, int n0, int wave_m,
+__device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x4 (&acc)[MI][NJ], int m0, int n0, int wave_m,
                                                int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
   static_assert((BM / 2) * LDW * 4 <= 2 * (slab_elems(BM) + slab_elems(BN)) * 2, "staging tile must fit the K-loop buffers");
@@ -289,7 +297,7 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x16 (&ac
 // BN/2 the up columns of the same index.  Both are rounded and stored into gu, and silu(gate) * up of the rounded
 // values goes to C: the three arrays the batched product followed by the activation kernel would leave.
 template <typename E, int BM, int BN, int NT, int MI, int NJ>
-__device__ __forceinline__ void epilogue_glu(const Gemm& g, f32x16 (&acc)[MI][NJ], int m0, int c0, int wave_m, int wn, int tid,
+__device__ __forceinline__ void epilogue_glu(const Gemm& g, f32x4 (&acc)[MI][NJ], int m0, int c0, int wave_m, int wn, int tid,
                                              float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
   typedef typename Vec<E>::type E8;
@@ -330,7 +338,7 @@ template <typename E, int BM, int BN, int NW, int TA, int TB, int SEG, int ACC, 
 __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_mfma_kernel(Gemm g, int tiles_m,
                                                                                                         int tiles_n) {
   constexpr int NT = 64 * NW, WN = NW / 2;               // threads; waves along n (2 along m)
-  constexpr int MI = BM / 64, NJ = BN / (32 * WN);       // 32x32 blocks per wave along m and n
+  constexpr int MI = BM / 32, NJ = BN / (16 * WN);       // 16x16 blocks per wave along m and n
   constexpr int SLAB_A = slab_elems(BM), SLAB_B = slab_elems(BN);   // LDS elements per operand slab, either layout
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);        // [2 buffers][A slab | B slab]
@@ -347,13 +355,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   static_assert(GLU == 0 || (GLU == 1 && !TA && !TB && !SEG && !ACC) || (GLU == 2 && !TA && TB && !SEG && !ACC), "fused gated unit");
   const int nb0 = GLU == 1 ? n0 / 2 : n0;                // first column of the tile inside B (GLU = 1: inside each of the two)
 
-  f32x16 acc[MI][NJ];
+  f32x4 acc[MI][NJ];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (g.K + BK - 1) / BK;
   // Two register stages.  While slab kt is multiplied out of one LDS buffer, slab kt+1 (loaded during the
@@ -424,33 +432,46 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   // hundreds of cycles in which it issues no MFMA.  The scheduling fences keep the compiler from gathering the loads
   // at the end of the loop body again.
   constexpr int VL = (VA + VB) / 8;                        // vectors per load group
+  static_assert(MI == 8 || MI == 4, "a load group and a stash quarter go out after every MI/4 rows of MFMA blocks");
+  // A slab is multiplied in 8 regions of MI/4 rows of blocks each.  The schedule is laid down by hand, with scheduling
+  // fences between its parts: a region first issues the LDS reads of the NEXT region's fragments, then its own MFMAs,
+  // then (every second region) a quarter of the next slab's stores, then its share of the global loads.
   auto multiply = [&](int buf, const Frag<BM, NT>& fa, const Frag<BN, NT>& fb, auto&& load) {
     const bf16* As = smem + buf * (SLAB_A + SLAB_B);
     const bf16* Bs = As + SLAB_A;
+    constexpr int RI = MI / 4;                             // rows of blocks per region
+    bf16x8 a[2][RI], b[2][NJ];
+    auto read_a = [&](int e) {                             // fragments of region e = 4 ks + q
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[MI], b[NJ];
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-        a[i] = TA == 0 ? frag_kmajor(As, wm + i * 32, ks * 16, lane) : frag_rmajor<BM>(As, wm + i * 32, ks * 16, lane);
+      for (int ii = 0; ii < RI; ++ii) {
+        const int row = wm + ((e & 3) * RI + ii) * 16, k32 = (e >> 2) * 32;
+        a[e & 1][ii] = TA == 0 ? frag_kmajor(As, row, k32, lane) : frag_rmajor<BM>(As, row, k32, lane);
+      }
+    };
+    auto read_b = [&](int ks) {
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
-        b[j] = TB == 1 ? frag_kmajor(Bs, wn + j * 32, ks * 16, lane) : frag_rmajor<BN>(Bs, wn + j * 32, ks * 16, lane);
+        b[ks][j] = TB == 1 ? frag_kmajor(Bs, wn + j * 16, ks * 32, lane) : frag_rmajor<BN>(Bs, wn + j * 16, ks * 32, lane);
+    };
+    read_b(0);
+    read_a(0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
+    for (int e = 0; e < 8; ++e) {
+      if (e == 3) read_b(1);
+      if (e < 7) read_a(e + 1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ii = 0; ii < RI; ++ii)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          acc[i][j] = mfma_32x32x16<E>(b[j], a[i], acc[i][j]);
-        if (i == MI / 2 - 1) {
-          __builtin_amdgcn_sched_barrier(0);
-          load(2 * ks * VL, (2 * ks + 1) * VL);
-          __builtin_amdgcn_sched_barrier(0);
-        }
+          acc[(e & 3) * RI + ii][j] = mfma_16x16x32<E>(b[e >> 2][j], a[e & 1][ii], acc[(e & 3) * RI + ii][j]);
+      if (e & 1) {
+        stash_a(buf ^ 1, fa, (e >> 1) * VA / 4, ((e >> 1) + 1) * VA / 4);
+        stash_b(buf ^ 1, fb, (e >> 1) * VB / 4, ((e >> 1) + 1) * VB / 4);
       }
-      stash_a(buf ^ 1, fa, ks * VA / 4, (ks + 1) * VA / 4);
-      stash_b(buf ^ 1, fb, ks * VB / 4, (ks + 1) * VB / 4);
       __builtin_amdgcn_sched_barrier(0);
-      load((2 * ks + 1) * VL, (2 * ks + 2) * VL);
+      load(e * VL, (e + 1) * VL);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
