@@ -184,6 +184,37 @@ class MinistageRunner:
         self.ms.close()
 
 
+def mfma_ceiling():
+    """What the matrix cores sustain with nothing else going on (stage_op_mfma_rate): the inner loop of the GEMM's wave tile
+    on random operands held in registers, no LDS and no memory traffic, for both bf16 MFMA shapes.  The MI355X runs such a
+    loop at its power limit, so this is the rate a bf16 GEMM can approach on it; 2.5 PFLOP/s stays the roofline's peak."""
+    import torch
+    import paper_2507_10392_amd as zs
+    dev = torch.device("cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    torch.manual_seed(0)
+    operands = torch.randn(32768, device=dev).to(torch.bfloat16)           # 64 KB
+    sink = torch.empty(256 * 512, device=dev, dtype=torch.float32)
+    flops_per_iter = 2.0 * 128 * 64 * 32 * 8 * 256                          # a 128 x 64 wave tile advances 32 columns of k per iteration
+    out = {}
+    for name, shape in (("32x32x16", 32), ("16x16x32", 16)):
+        zs.ops.mfma_rate(st, shape, 20000, operands, sink)                 # warm-up, and brings the clock down to its sustained value
+        runs = []
+        for _ in range(3):
+            iters = 60000
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            zs.ops.mfma_rate(st, shape, iters, operands, sink)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b)
+            runs.append({"ms": ms, "tflops": flops_per_iter * iters / ms / 1e9})
+        out[name] = {"tflops": sorted(r["tflops"] for r in runs)[1], "runs": runs, "frac_of_2500": sorted(r["tflops"] for r in runs)[1] / 2500.0}
+    print(json.dumps({"mfma_sustained": out, "unit": "TFLOP/s", "dtype": "bf16", "finite": bool(torch.isfinite(sink).all().item()),
+                      "note": "register-resident operands (random bf16), 128 accumulator registers per wave, 2 waves per SIMD, "
+                              "256 workgroups; median of 3 launches of about 35 ms each"}))
+
+
 def planner_profile(cfg):
     """What the paper's planner takes from a GPU (Section 4.3, "Profiling" and "Memory Model"): the stage timed at
     small microbatch sizes with stage_time_layers, the library's least-squares line per pass, the line's
@@ -457,6 +488,8 @@ def main():
     ap.add_argument("--ministages", type=int, default=0, metavar="K",
                     help="cut the workload's layers into K ministages that share two parameter slots on the GPU, the rest "
                          "waiting in pinned host memory (include/ministages.h); interior stages only")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="time a register-resident loop of bf16 MFMAs of both shapes: the matrix-core rate that the chip sustains")
     ap.add_argument("--planner-profile", action="store_true",
                     help="time one layer at small microbatch sizes, fit the runtime lines and print them with the memory terms")
     args = ap.parse_args()
@@ -496,6 +529,9 @@ def main():
               file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(torch.device("cuda:0"))
+    if args.mfma_ceiling:
+        mfma_ceiling()
+        return
     if args.planner_profile:
         planner_profile(cfg)
         return

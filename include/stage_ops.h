@@ -129,6 +129,17 @@ int stage_op_cross_entropy(void* stream, int32_t dtype, int32_t T, int32_t V, vo
                            const int32_t* targets, float* lse, float* rowloss, float* loss, float scale,
                            int32_t backward);
 
+/* Measurement aid, not a step of the path: what the matrix cores sustain when nothing else happens.  One workgroup of
+ * 8 waves per CU (256 workgroups) runs `iters` times the inner loop of the GEMM's 128 x 64 wave tile on operands held in
+ * registers - per wave and iteration 16 MFMAs of 32x32x16 (shape = 32) or 32 MFMAs of 16x16x32 (shape = 16), i.e.
+ * 2 * 128 * 64 * 32 flops - with no LDS or memory access inside the loop.  The MI355X runs such a loop at its power limit,
+ * so flops / time is the rate a bf16 GEMM can approach on it; `bench.py --mfma-ceiling` times it (profiles/mfma_sustained_rate.txt).
+ * operands: device, 65536 bytes of bf16 values (read once; random values give the operand switching of a real product);
+ * sink: device, 256 * 512 floats (one sum per thread, written once, so that the loop is not optimised away).
+ * Total flops of a call: iters * 2 * 128 * 64 * 32 * 8 waves * 256 workgroups.  Enqueues one kernel on `stream`;
+ * STAGE_ERR_ARG for another shape, iters < 1 or a null pointer. */
+int stage_op_mfma_rate(void* stream, int32_t shape, int32_t iters, const void* operands, float* sink);
+
 /* AdamW with decoupled weight decay, step t >= 1, on n elements starting at flat index `begin`
  * (formula in stage.h).  dtype 1: master/m/v are float[n], grad float[>=begin+n], params bf16;
  * dtype 0: master NULL, params float.  grad[begin..begin+n) is zeroed. */

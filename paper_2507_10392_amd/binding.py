@@ -128,6 +128,7 @@ def lib():
         L.stage_op_embed.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, i32]
         L.stage_op_cross_entropy.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, vp, vp, f32, i32]
         L.stage_op_adamw.argtypes = [vp, i32, i64, i64, vp, vp, vp, vp, vp, f32, f32, f32, f32, f32, i64, f32]
+        L.stage_op_mfma_rate.argtypes = [vp, i32, i32, vp, vp]
         _lib = L
     return _lib
 

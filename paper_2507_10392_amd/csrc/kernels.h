@@ -121,6 +121,11 @@ struct AdamW { float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2, grad_scale; co
 // params_bf16 by begin+i.  dtype F32: params (float) indexed by begin+i is the master.  grad[begin, begin+n) is
 // zeroed when h.zero_grad is set; a caller that clears the whole accumulator anyway leaves that to its fill, which
 // as a pure write stream runs at a higher rate than a fifth write stream inside this kernel.
+// Register-resident MFMA loop (mfma_rate.hip): `shape` 16 = 16x16x32, 32 = 32x32x16; one 512-thread workgroup per CU, every wave
+// issues iters * 32 columns of k on a 128 x 64 tile.  operands: 64 KB of bf16 values, sink: MFMA_RATE_BLOCKS * 512 floats.
+constexpr int MFMA_RATE_BLOCKS = 256;
+hipError_t mfma_rate(hipStream_t st, int shape, int iters, const void* operands, float* sink);
+
 hipError_t adamw(hipStream_t st, DType dt, int64_t n, int64_t begin, void* params, float* master, float* grad,
                  float* m, float* v, const AdamW& h);
 hipError_t fill_zero(hipStream_t st, float* p, int64_t n);

@@ -246,4 +246,9 @@ int stage_op_adamw(void* stream, int32_t dtype, int64_t n, int64_t begin, void* 
   return rc(adamw((hipStream_t)stream, (DType)dtype, n, begin, params, master, grad, m, v, h));
 }
 
+int stage_op_mfma_rate(void* stream, int32_t shape, int32_t iters, const void* operands, float* sink) {
+  if ((shape != 16 && shape != 32) || iters < 1 || !operands || !sink) return STAGE_ERR_ARG;
+  return rc(mfma_rate((hipStream_t)stream, shape, iters, operands, sink));
+}
+
 }  // extern "C"

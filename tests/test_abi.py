@@ -191,6 +191,9 @@ def test_ops_reject_bad_arguments_on_the_host():
     assert L.stage_op_gemm(None, 0, 0, 0, 8, 8, 8, None, 8, fake, 8, fake, 8, 0, None, None, 0, 1, 0, 0, 0, 0, 0, 0, 0) == zs.STAGE_ERR_ARG
     assert L.stage_op_gemm(None, 0, 0, 0, 8, 8, 8, fake, 8, fake, 8, fake, 8, 0, None, None, 0, 1, 0, 0, 0, 0, 3, 0, 0) == zs.STAGE_ERR_ARG
     assert L.stage_op_adamw(None, 1, 8, 0, fake, None, fake, fake, fake, 1e-4, 0.9, 0.999, 1e-8, 0.01, 1, 1.0) == zs.STAGE_ERR_ARG
+    assert L.stage_op_mfma_rate(None, 8, 10, fake, fake) == zs.STAGE_ERR_ARG      # only the shapes 16 and 32 exist
+    assert L.stage_op_mfma_rate(None, 16, 0, fake, fake) == zs.STAGE_ERR_ARG
+    assert L.stage_op_mfma_rate(None, 16, 10, None, fake) == zs.STAGE_ERR_ARG
     assert L.stage_op_adamw(None, 0, 8, 0, fake, None, fake, fake, fake, 1e-4, 0.9, 0.999, 1e-8, 0.01, 0, 1.0) == zs.STAGE_ERR_ARG
     assert L.stage_op_norm_fwd(None, 1, 1, 4, 12, fake, fake, None, 1e-5, fake, fake, None) == zs.STAGE_ERR_ARG
     assert L.stage_op_attention_fwd(None, 1, 1, 16, 1, 12, fake, fake, fake, 12, fake, 12, fake, 0) == zs.STAGE_ERR_ARG

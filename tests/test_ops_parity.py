@@ -689,3 +689,57 @@ def test_cross_entropy_backward_beyond_65535_tokens(gpu_device):
     z_all = z.astype(np.float64)
     lse_o = np.log(np.exp(z_all).sum(axis=1))
     assert abs(back(loss)[0] - (lse_o - z_all[np.arange(T), tg]).mean()) <= 1e-5
+
+
+@pytest.mark.gpu
+def test_mfma_rate_loop_matches_the_product_it_repeats(gpu_device):
+    """stage_op_mfma_rate is a measurement aid, but its loop is a real product: every thread's sum over its accumulators
+    must equal iters times what one pass of the wave tile gives on the operand fragments the kernel reads (fp32
+    accumulation of exact bf16 products, so a float64 reference applies)."""
+    import torch
+    st = torch.cuda.current_stream().cuda_stream
+    torch.manual_seed(5)
+    operands = (torch.randint(-4, 5, (32768,), device=gpu_device).float() / 4).to(torch.bfloat16)   # exact in fp32 sums
+    sink = torch.empty(256 * 512, device=gpu_device, dtype=torch.float32)
+    frags = operands.double().view(4096, 8).cpu()
+    lane = torch.arange(64)
+    for shape, iters in ((16, 3), (32, 3)):
+        zs.ops.mfma_rate(st, shape, iters, operands, sink)
+        torch.cuda.synchronize()
+        got = sink.view(256, 8, 64).double().cpu()
+        assert torch.equal(got[0], got[255])                      # every workgroup does the same work
+        for wave in (0, 5):
+            t = wave * 64 + lane
+            idx = lambda o: (t * 16 + o) % 4096                   # fragment index of thread t at offset o
+            if shape == 16:
+                # acc[i][j] = b_j (16 x 32, rows = lanes%16) times a_i^T per 16x16x32 instruction: D[r][c] = sum_k B[r][k] A[c][k]
+                A = [frags[idx(i)] for i in range(8)]             # [64 lanes, 8] each: lane l holds row l%16, k = 8*(l/16)..+7
+                B = [frags[idx(8 + j)] for j in range(4)]
+                def full(fr):                                      # [16 rows, 32 k]
+                    m = torch.zeros(16, 32, dtype=torch.float64)
+                    for l in range(64):
+                        m[l % 16, 8 * (l // 16):8 * (l // 16) + 8] = fr[l]
+                    return m
+                total = torch.zeros(64, dtype=torch.float64)
+                for i in range(8):
+                    for j in range(4):
+                        D = full(B[j]) @ full(A[i]).T             # lane l holds D[4*(l/16) + r][l%16], r = 0..3
+                        for l in range(64):
+                            total[l] += D[4 * (l // 16):4 * (l // 16) + 4, l % 16].sum()
+            else:
+                A = [[frags[idx(s * 4 + i)] for i in range(4)] for s in range(2)]
+                B = [[frags[idx(8 + s * 2 + j)] for j in range(2)] for s in range(2)]
+                def full(fr):                                      # [32 rows, 16 k]: lane l holds row l%32, k = 8*(l/32)..+7
+                    m = torch.zeros(32, 16, dtype=torch.float64)
+                    for l in range(64):
+                        m[l % 32, 8 * (l // 32):8 * (l // 32) + 8] = fr[l]
+                    return m
+                total = torch.zeros(64, dtype=torch.float64)
+                for s in range(2):
+                    for i in range(4):
+                        for j in range(2):
+                            D = full(B[s][j]) @ full(A[s][i]).T    # lane l holds rows 8*(r/4) + 4*(l/32) + r%4 of column l%32
+                            for l in range(64):
+                                rows = [8 * (r // 4) + 4 * (l // 32) + r % 4 for r in range(16)]
+                                total[l] += D[rows, l % 32].sum()
+            assert torch.allclose(got[0, wave], iters * total, rtol=0, atol=1e-3), (shape, wave)
