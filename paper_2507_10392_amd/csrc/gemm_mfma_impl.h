@@ -435,7 +435,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   static_assert(MI == 8 || MI == 4, "a load group and a stash quarter go out after every MI/4 rows of MFMA blocks");
   // A slab is multiplied in 8 regions of MI/4 rows of blocks each.  The schedule is laid down by hand, with scheduling
   // fences between its parts: a region first issues the LDS reads of the NEXT region's fragments, then its own MFMAs,
-  // then (every second region) a quarter of the next slab's stores, then its share of the global loads.
+  // then a quarter of one operand's share of the next slab's stores (A and B in turn), then its share of the global loads.
   auto multiply = [&](int buf, const Frag<BM, NT>& fa, const Frag<BN, NT>& fb, auto&& load) {
     const bf16* As = smem + buf * (SLAB_A + SLAB_B);
     const bf16* Bs = As + SLAB_A;
@@ -458,7 +458,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (e == 3) read_b(1);
+      if (e == 2) read_b(1);
       if (e < 7) read_a(e + 1);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -466,10 +466,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
           acc[(e & 3) * RI + ii][j] = mfma_16x16x32<E>(b[e >> 2][j], a[e & 1][ii], acc[(e & 3) * RI + ii][j]);
-      if (e & 1) {
-        stash_a(buf ^ 1, fa, (e >> 1) * VA / 4, ((e >> 1) + 1) * VA / 4);
-        stash_b(buf ^ 1, fb, (e >> 1) * VB / 4, ((e >> 1) + 1) * VB / 4);
-      }
+      if (e & 1) stash_b(buf ^ 1, fb, (e >> 1) * VB / 4, ((e >> 1) + 1) * VB / 4);
+      else stash_a(buf ^ 1, fa, (e >> 1) * VA / 4, ((e >> 1) + 1) * VA / 4);
       __builtin_amdgcn_sched_barrier(0);
       load(e * VL, (e + 1) * VL);
       __builtin_amdgcn_sched_barrier(0);
