@@ -215,6 +215,47 @@ def mfma_ceiling():
                               "256 workgroups; median of 3 launches of about 35 ms each"}))
 
 
+def lds_patterns():
+    """LDS time per wave read (stage_op_lds_probe) for the access patterns between which the GEMM's slab layouts were chosen:
+    fragment reads and slab stores of k-contiguous slabs with padded rows and with permuted unpadded rows, transposing
+    reads of row-contiguous slabs with and without the chunk swap, and the 32x32x16 fragment shapes for comparison."""
+    import ctypes
+    import torch
+    import paper_2507_10392_amd as zs
+    dev = torch.device("cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    LDR = 288   # elements per k-line of a 256-row [k][row] slab
+    pats = [
+        ("16-byte reads, lane l at 16 l (no pattern)", 0, lambda l: 16 * l),
+        ("k-contiguous slab, 32x32x16 fragment (row l%32, piece l/32), rows padded to 144 bytes", 0, lambda l: (l % 32) * 144 + (l // 32) * 16),
+        ("k-contiguous slab, 16x16x32 fragment (row l%16, piece l/16), rows padded to 144 bytes", 0, lambda l: (l % 16) * 144 + (l // 16) * 16),
+        ("k-contiguous slab, 16x16x32 fragment, 128-byte rows, piece p of row r at p ^ r%8 (in use)", 0, lambda l: (l % 16) * 128 + (((l // 16) ^ (l % 8)) * 16)),
+        ("k-contiguous slab, store of 8 rows x 8 pieces, rows padded to 144 bytes", 0, lambda l: (l // 8) * 144 + (l % 8) * 16),
+        ("k-contiguous slab, store of 8 rows x 8 pieces, 128-byte rows, permuted pieces (in use)", 0, lambda l: (l // 8) * 128 + (((l % 8) ^ ((l // 8) % 8)) * 16)),
+        ("row-contiguous slab, store of 2 k-lines x 32 pieces, chunks swapped (in use)", 0, lambda l: (l // 32) * LDR * 2 + (l % 32) * 16),
+        ("transposing reads, lane l at 8 l (no pattern)", 1, lambda l: 8 * l),
+        ("row-contiguous slab, 32x32x16 fragment (k-lines 8 (g/2) + r/4, rows 16 (g%2) + 4 (r%4))", 1,
+         lambda l: ((8 * ((l >> 4) >> 1) + ((l & 15) >> 2)) * LDR + 16 * ((l >> 4) & 1) + 4 * (l & 3)) * 2),
+        ("row-contiguous slab, 16x16x32 fragment (k-lines 8 g + r/4, rows 4 (r%4)), no swap", 1,
+         lambda l: ((8 * (l >> 4) + ((l & 15) >> 2)) * LDR + 4 * (l & 3)) * 2),
+        ("row-contiguous slab, 16x16x32 fragment, 16-row chunks swapped on odd eights of k (in use)", 1,
+         lambda l: ((8 * (l >> 4) + ((l & 15) >> 2)) * LDR + ((4 * (l & 3)) ^ (((l >> 4) & 1) << 4))) * 2),
+    ]
+    iters = 4000
+    cyc = torch.zeros(2, dtype=torch.int64, device=dev)
+    rows = []
+    for name, kind, f in pats:
+        host = (ctypes.c_int32 * 64)(*[f(l) for l in range(64)])
+        devoff = torch.tensor(list(host), dtype=torch.int32, device=dev)
+        for _ in range(2):
+            zs.ops.lds_probe(st, kind, host, devoff, iters, cyc)
+        torch.cuda.synchronize()
+        rows.append({"pattern": name, "kind": "ds_read_b64_tr_b16" if kind else "ds_read_b128",
+                     "cycles_per_wave_read": round(int(cyc[0].item()) / (iters * 8 * 8), 2)})
+    print(json.dumps({"lds_patterns": rows, "note": "one workgroup of 8 waves, 8 independent reads in flight per wave; "
+                      "4.5 (16-byte) and 3.5 (transposing) cycles per wave read are the conflict-free figures"}))
+
+
 def planner_profile(cfg):
     """What the paper's planner takes from a GPU (Section 4.3, "Profiling" and "Memory Model"): the stage timed at
     small microbatch sizes with stage_time_layers, the library's least-squares line per pass, the line's
@@ -490,6 +531,8 @@ def main():
                          "waiting in pinned host memory (include/ministages.h); interior stages only")
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="time a register-resident loop of bf16 MFMAs of both shapes: the matrix-core rate that the chip sustains")
+    ap.add_argument("--lds-patterns", action="store_true",
+                    help="time the LDS access patterns between which the GEMM's slab layouts were chosen")
     ap.add_argument("--planner-profile", action="store_true",
                     help="time one layer at small microbatch sizes, fit the runtime lines and print them with the memory terms")
     args = ap.parse_args()
@@ -531,6 +574,9 @@ def main():
     torch.cuda.set_device(torch.device("cuda:0"))
     if args.mfma_ceiling:
         mfma_ceiling()
+        return
+    if args.lds_patterns:
+        lds_patterns()
         return
     if args.planner_profile:
         planner_profile(cfg)

@@ -140,6 +140,18 @@ int stage_op_cross_entropy(void* stream, int32_t dtype, int32_t T, int32_t V, vo
  * STAGE_ERR_ARG for another shape, iters < 1 or a null pointer. */
 int stage_op_mfma_rate(void* stream, int32_t shape, int32_t iters, const void* operands, float* sink);
 
+/* Measurement aid, not a step of the path: what one LDS access pattern costs.  One workgroup of 8 waves; every wave
+ * issues `iters` x 8 wave-wide reads in which lane l reads at byte offset lane_offset[l] of the workgroup's 64 KB of LDS
+ * (plus shifts that are the same for all lanes): kind 0 = 16 bytes per lane (ds_read_b128), kind 1 = the 8-byte
+ * transposing read of gfx950 (ds_read_b64_tr_b16).  cycles[0] receives the workgroup's cycle count for all of it, so
+ * cycles[0] / (iters * 8 * 8) is the LDS time per wave read; bank conflicts raise it above the pattern-free 4.5 (kind 0) or
+ * 3.5 (kind 1).  The slab layouts of the GEMM were chosen with it (`bench.py --lds-patterns`, profiles/lds_access_patterns.txt).
+ * lane_offset_host: host, 64 offsets, each a multiple of 16 (kind 0) or 8 (kind 1) and at most 20 976 (checked here, since
+ * the kernel reads at them: STAGE_ERR_ARG otherwise); lane_offset: device, the same 64 values; cycles: device, 2 x int64
+ * (the second word is a checksum that keeps the reads alive).  Enqueues one kernel on `stream`. */
+int stage_op_lds_probe(void* stream, int32_t kind, const int32_t* lane_offset_host, const int32_t* lane_offset, int32_t iters,
+                       int64_t* cycles);
+
 /* AdamW with decoupled weight decay, step t >= 1, on n elements starting at flat index `begin`
  * (formula in stage.h).  dtype 1: master/m/v are float[n], grad float[>=begin+n], params bf16;
  * dtype 0: master NULL, params float.  grad[begin..begin+n) is zeroed. */

@@ -129,6 +129,7 @@ def lib():
         L.stage_op_cross_entropy.argtypes = [vp, i32, i32, i32, vp, i64, vp, vp, vp, vp, f32, i32]
         L.stage_op_adamw.argtypes = [vp, i32, i64, i64, vp, vp, vp, vp, vp, f32, f32, f32, f32, f32, i64, f32]
         L.stage_op_mfma_rate.argtypes = [vp, i32, i32, vp, vp]
+        L.stage_op_lds_probe.argtypes = [vp, i32, C.POINTER(i32), vp, i32, vp]
         _lib = L
     return _lib
 

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstage.so")
 SOURCES = ["stage.hip", "ministages.hip", "ops_api.hip", "elementwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "gemm_mfma_256x256.hip",
            "gemm_mfma_128x128.hip", "gemm_mfma_256x256_f16.hip", "gemm_mfma_128x128_f16.hip",
-           "attention_simple.hip", "attention_mfma.hip", "attention_mfma_f16.hip", "mfma_rate.hip"]
+           "attention_simple.hip", "attention_mfma.hip", "attention_mfma_f16.hip", "mfma_rate.hip", "lds_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

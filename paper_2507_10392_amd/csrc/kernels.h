@@ -125,6 +125,10 @@ struct AdamW { float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2, grad_scale; co
 // issues iters * 32 columns of k on a 128 x 64 tile.  operands: 64 KB of bf16 values, sink: MFMA_RATE_BLOCKS * 512 floats.
 constexpr int MFMA_RATE_BLOCKS = 256;
 hipError_t mfma_rate(hipStream_t st, int shape, int iters, const void* operands, float* sink);
+// LDS access-pattern timer (lds_probe.hip): kind 0 = 16-byte reads, 1 = 8-byte transposing reads; lane_offset: 64 byte offsets
+// on the device, each at most lds_probe_max_offset(); cycles[0] = the workgroup's cycles for iters * 8 reads per wave, 8 waves.
+int lds_probe_max_offset();
+hipError_t lds_probe(hipStream_t st, int kind, const int* lane_offset, int iters, long long* cycles);
 
 hipError_t adamw(hipStream_t st, DType dt, int64_t n, int64_t begin, void* params, float* master, float* grad,
                  float* m, float* v, const AdamW& h);

@@ -251,4 +251,14 @@ int stage_op_mfma_rate(void* stream, int32_t shape, int32_t iters, const void* o
   return rc(mfma_rate((hipStream_t)stream, shape, iters, operands, sink));
 }
 
+int stage_op_lds_probe(void* stream, int32_t kind, const int32_t* lane_offset_host, const int32_t* lane_offset, int32_t iters,
+                       int64_t* cycles) {
+  if ((kind != 0 && kind != 1) || iters < 1 || !lane_offset_host || !lane_offset || !cycles) return STAGE_ERR_ARG;
+  for (int l = 0; l < 64; ++l) {   // the host copy is what is checked: the kernel reads LDS at these offsets
+    const int o = lane_offset_host[l];
+    if (o < 0 || o > lds_probe_max_offset() || o % (kind == 0 ? 16 : 8)) return STAGE_ERR_ARG;
+  }
+  return rc(lds_probe((hipStream_t)stream, kind, lane_offset, iters, (long long*)cycles));
+}
+
 }  // extern "C"

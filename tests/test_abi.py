@@ -194,6 +194,11 @@ def test_ops_reject_bad_arguments_on_the_host():
     assert L.stage_op_mfma_rate(None, 8, 10, fake, fake) == zs.STAGE_ERR_ARG      # only the shapes 16 and 32 exist
     assert L.stage_op_mfma_rate(None, 16, 0, fake, fake) == zs.STAGE_ERR_ARG
     assert L.stage_op_mfma_rate(None, 16, 10, None, fake) == zs.STAGE_ERR_ARG
+    good, far, odd = (C.c_int32 * 64)(*[16 * l for l in range(64)]), (C.c_int32 * 64)(*[20992] * 64), (C.c_int32 * 64)(*[8] * 64)
+    assert L.stage_op_lds_probe(None, 2, good, fake, 10, fake) == zs.STAGE_ERR_ARG     # kinds 0 and 1 only
+    assert L.stage_op_lds_probe(None, 0, far, fake, 10, fake) == zs.STAGE_ERR_ARG      # offset beyond the probe's LDS
+    assert L.stage_op_lds_probe(None, 0, odd, fake, 10, fake) == zs.STAGE_ERR_ARG      # 16-byte reads at 16-byte offsets
+    assert L.stage_op_lds_probe(None, 1, good, None, 10, fake) == zs.STAGE_ERR_ARG
     assert L.stage_op_adamw(None, 0, 8, 0, fake, None, fake, fake, fake, 1e-4, 0.9, 0.999, 1e-8, 0.01, 0, 1.0) == zs.STAGE_ERR_ARG
     assert L.stage_op_norm_fwd(None, 1, 1, 4, 12, fake, fake, None, 1e-5, fake, fake, None) == zs.STAGE_ERR_ARG
     assert L.stage_op_attention_fwd(None, 1, 1, 16, 1, 12, fake, fake, fake, 12, fake, 12, fake, 0) == zs.STAGE_ERR_ARG

@@ -743,3 +743,25 @@ def test_mfma_rate_loop_matches_the_product_it_repeats(gpu_device):
                                 rows = [8 * (r // 4) + 4 * (l // 32) + r % 4 for r in range(16)]
                                 total[l] += D[rows, l % 32].sum()
             assert torch.allclose(got[0, wave], iters * total, rtol=0, atol=1e-3), (shape, wave)
+
+
+@pytest.mark.gpu
+def test_lds_probe_tells_a_conflict_from_none(gpu_device):
+    """stage_op_lds_probe: 64 lanes on 64 different 16-byte pieces of one 1 KB line cost the pattern-free minimum; 16 rows
+    that all start in the same bank (256 bytes apart) cost several times as much."""
+    import ctypes
+    import torch
+    st = torch.cuda.current_stream().cuda_stream
+    cyc = torch.zeros(2, dtype=torch.int64, device=gpu_device)
+    def cost(f, kind=0):
+        host = (ctypes.c_int32 * 64)(*[f(l) for l in range(64)])
+        devoff = torch.tensor(list(host), dtype=torch.int32, device=gpu_device)
+        for _ in range(2):
+            zs.ops.lds_probe(st, kind, host, devoff, 2000, cyc)
+        torch.cuda.synchronize()
+        return int(cyc[0].item()) / (2000 * 8 * 8)
+    free = cost(lambda l: 16 * l)
+    clash = cost(lambda l: (l % 16) * 256 + (l // 16) * 16)
+    assert 3.5 < free < 6.0, free
+    assert clash > 3 * free, (free, clash)
+    assert 2.5 < cost(lambda l: 8 * l, kind=1) < 5.0
