@@ -253,7 +253,7 @@ def lds_patterns():
         rows.append({"pattern": name, "kind": "ds_read_b64_tr_b16" if kind else "ds_read_b128",
                      "cycles_per_wave_read": round(int(cyc[0].item()) / (iters * 8 * 8), 2)})
     print(json.dumps({"lds_patterns": rows, "note": "one workgroup of 8 waves, 8 independent reads in flight per wave; "
-                      "4.5 (16-byte) and 3.5 (transposing) cycles per wave read are the conflict-free figures"}))
+                      "4.6 (16-byte) and 3.6 (transposing) cycles per wave read are the conflict-free figures"}))
 
 
 def planner_profile(cfg):

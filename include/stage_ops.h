@@ -144,8 +144,8 @@ int stage_op_mfma_rate(void* stream, int32_t shape, int32_t iters, const void* o
  * issues `iters` x 8 wave-wide reads in which lane l reads at byte offset lane_offset[l] of the workgroup's 64 KB of LDS
  * (plus shifts that are the same for all lanes): kind 0 = 16 bytes per lane (ds_read_b128), kind 1 = the 8-byte
  * transposing read of gfx950 (ds_read_b64_tr_b16).  cycles[0] receives the workgroup's cycle count for all of it, so
- * cycles[0] / (iters * 8 * 8) is the LDS time per wave read; bank conflicts raise it above the pattern-free 4.5 (kind 0) or
- * 3.5 (kind 1).  The slab layouts of the GEMM were chosen with it (`bench.py --lds-patterns`, profiles/lds_access_patterns.txt).
+ * cycles[0] / (iters * 8 * 8) is the LDS time per wave read; bank conflicts raise it above the pattern-free 4.6 (kind 0) or
+ * 3.6 (kind 1).  The slab layouts of the GEMM were chosen with it (`bench.py --lds-patterns`, profiles/lds_access_patterns.txt).
  * lane_offset_host: host, 64 offsets, each a multiple of 16 (kind 0) or 8 (kind 1) and at most 20 976 (checked here, since
  * the kernel reads at them: STAGE_ERR_ARG otherwise); lane_offset: device, the same 64 values; cycles: device, 2 x int64
  * (the second word is a checksum that keeps the reads alive).  Enqueues one kernel on `stream`. */

@@ -1,7 +1,7 @@
 // Cost of an LDS access pattern: every wave of one 512-thread workgroup issues the same wave-wide read (16 bytes per
 // lane, or the 8-byte transposing read of gfx950) at the byte offsets given per lane, `iters` x 8 times, and the
 // workgroup's cycle count is reported.  Bank conflicts show as cycles per wave read above the pattern-free minimum
-// (4.5 for 16-byte reads, 3.5 for transposing reads).  This is how the slab layouts of the GEMM were chosen: the LDS
+// (4.6 for 16-byte reads, 3.6 for transposing reads).  This is how the slab layouts of the GEMM were chosen: the LDS
 // does not serve a wave's accesses in groups of 16 consecutive lanes, so a layout has to be timed, not derived.
 #include "kernels.h"
 
