@@ -256,6 +256,76 @@ def lds_patterns():
                       "4.6 (16-byte) and 3.6 (transposing) cycles per wave read are the conflict-free figures"}))
 
 
+def gemm_scan():
+    """Three measurements of the bf16 GEMM that the tile and stream decisions rest on.  (1) Time against K at one round of
+    256 tiles (M = N = 4096): the slope is the K loop's rate, the intercept what a launch costs beyond it (launch, first
+    loads, the store pass).  (2) Time against the number of 256x256 tiles at K = 4096: a grid pays for whole rounds of 256
+    workgroups.  (3) The dX products of one layer and a grouped weight-gradient product, enqueued on one stream and on two."""
+    import numpy as np
+    import torch
+    import paper_2507_10392_amd as zs
+    dev = torch.device("cuda:0")
+    main = torch.cuda.current_stream()
+
+    def product(M, N, K, ta, tb, accum, impl=2):
+        A = torch.randn(M * K, device=dev).to(torch.bfloat16)
+        B = (torch.randn(K * N, device=dev) * 0.02).to(torch.bfloat16)
+        C = torch.zeros(M * N, device=dev, dtype=torch.float32 if accum else torch.bfloat16)
+        lda, ldb = (M if ta else K), (K if tb else N)
+        return lambda st: zs.ops.gemm(st.cuda_stream, 1, ta, tb, M, N, K, A, lda, B, ldb, C, N, int(accum), None, None, 0, 1,
+                                      M * K, K * N, M * N, 0, 0, 0, impl)
+
+    def us(f, n=30, w=5):
+        for _ in range(w):
+            f(main)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            f(main)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n * 1e3
+
+    forms = (("nt", 0, 1, 0), ("nn", 0, 0, 0), ("tn_accumulate", 1, 0, 1))
+    k_scan = []
+    for name, ta, tb, acc in forms:
+        ks = [2048, 4096, 8192, 16384]
+        ts = [us(product(4096, 4096, K, ta, tb, acc)) for K in ks]
+        slope, fixed = np.polyfit(np.array(ks, float), np.array(ts), 1)
+        k_scan.append({"form": name, "us_at_K": dict(zip(map(str, ks), [round(t, 1) for t in ts])), "fixed_us": round(float(fixed), 1),
+                       "k_loop_tflops": round(2.0 * 4096 * 4096 / slope / 1e6, 0)})
+    rounds = []
+    for N in (4096, 8192, 11008, 12288):
+        tiles = 16 * ((N + 255) // 256)
+        t = us(product(4096, N, 4096, 0, 1, 0, impl=3))
+        rounds.append({"N": N, "tiles_256x256": tiles, "rounds": round(tiles / 256.0, 3), "us": round(t, 1),
+                       "tflops": round(2.0 * 4096 * N * 4096 / t / 1e6, 0)})
+    T, H, F = 4096, 4096, 11008
+    chain = [product(T, F, H, 0, 1, 0), product(T, H, F, 0, 1, 0), product(T, H, H, 0, 1, 0), product(T, H, H, 0, 1, 0)]
+    wgrad = product(F, H, 8 * T, 1, 0, 1)
+    second = torch.cuda.Stream()                                         # default priority
+
+    def both(two_streams, layers=40, groups=10):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(layers):
+            if i < groups:
+                wgrad(second if two_streams else main)
+            for f in chain:
+                f(main)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    both(False), both(True)
+    one = sorted(both(False) for _ in range(3))[1]
+    two = sorted(both(True) for _ in range(3))[1]
+    print(json.dumps({"gemm_scan": {"time_against_K": k_scan, "time_against_tiles": rounds,
+                                    "streams": {"one_stream_ms": round(one, 2), "two_streams_ms": round(two, 2),
+                                                "work": "40 x (4 dX products of a C3 layer) + 10 x (dWd over 8 microbatches)"}},
+                      "dtype": "bf16", "note": "M = N = 4096 for the K scan (256 tiles of 256x256: one round); least-squares line over "
+                      "the four K; the tile scan forces the 256x256 tile"}))
+
+
 def planner_profile(cfg):
     """What the paper's planner takes from a GPU (Section 4.3, "Profiling" and "Memory Model"): the stage timed at
     small microbatch sizes with stage_time_layers, the library's least-squares line per pass, the line's
@@ -533,6 +603,8 @@ def main():
                     help="time a register-resident loop of bf16 MFMAs of both shapes: the matrix-core rate that the chip sustains")
     ap.add_argument("--lds-patterns", action="store_true",
                     help="time the LDS access patterns between which the GEMM's slab layouts were chosen")
+    ap.add_argument("--gemm-scan", action="store_true",
+                    help="time the bf16 GEMM against K, against the number of tiles, and on one stream against two")
     ap.add_argument("--planner-profile", action="store_true",
                     help="time one layer at small microbatch sizes, fit the runtime lines and print them with the memory terms")
     args = ap.parse_args()
@@ -577,6 +649,9 @@ def main():
         return
     if args.lds_patterns:
         lds_patterns()
+        return
+    if args.gemm_scan:
+        gemm_scan()
         return
     if args.planner_profile:
         planner_profile(cfg)

@@ -213,36 +213,66 @@ template <> __device__ __forceinline__ f32x4 mfma_16x16x32<f16>(bf16x8 a, bf16x8
 
 // Epilogue for 16-bit output (E = bf16 or IEEE half): after staging, ALL threads read rows back 8 columns at a time, add bias and
 // residual in fp32, round once to bf16 and store 16 bytes per lane, consecutive lanes covering
-// consecutive 16-byte pieces of a row of C.
+// consecutive 16-byte pieces of a row of C.  A thread keeps its 8 columns through all rows it visits, so the bias is
+// loaded once, and what depends on the row (residual, rotary angles, or the gate and up values of GLU = 2) is loaded
+// for a whole half before the staging barrier: the loads' latency runs under the staging instead of once per row.
 template <typename E, int BM, int BN, int NT, int MI, int NJ, int GLU>
 __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x4 (&acc)[MI][NJ], int m0, int n0, int wave_m,
                                                int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
   static_assert((BM / 2) * LDW * 4 <= 2 * (slab_elems(BM) + slab_elems(BN)) * 2, "staging tile must fit the K-loop buffers");
+  constexpr int VPR = BN / 8;                              // 16-byte output vectors per row
+  constexpr int NV = (BM / 2) * VPR / NT;                  // vectors per thread and half
+  constexpr int RSTEP = NT / VPR;                          // rows between a thread's consecutive vectors
+  static_assert(NT % VPR == 0 && ((BM / 2) * VPR) % NT == 0, "a thread keeps its columns");
   typedef typename Vec<E>::type E8;
   const int lane = tid & 63;
   const E* bias = g.bias ? (const E*)g.bias + (int64_t)z * g.sBias : nullptr;
   const E* R = g.resid ? (const E*)g.resid + (int64_t)z * g.sC : nullptr;
   E* Cz = (E*)g.C + (int64_t)z * g.sC;
   const bool rope = g.rope && z < g.rope_batches;
+  const int lr0 = tid / VPR, cv = (tid % VPR) * 8, col = n0 + cv;
+  const bool full = col + 8 <= g.N;                        // all 8 columns exist: the vector path
+  const bool pre_resid = GLU == 0 && R, pre_rope = GLU == 0 && rope && !R;
+  E8 bb = {};
+  if (GLU == 0 && bias && full) bb = *reinterpret_cast<const E8*>(bias + col);
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     __syncthreads();                                       // K-loop reads / previous half's reads are done
+    const int row0 = m0 + half * (BM / 2) + lr0;
+    u32x4 pre0[NV], pre1[NV];                              // one source address per slot, so each slot has one load
+    const bool want0 = full && (GLU == 2 || pre_resid || pre_rope), want1 = full && (GLU == 2 || pre_rope);
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+      const int row = row0 + RSTEP * it;
+      const E* src0 = nullptr;
+      const E* src1 = nullptr;
+      if (GLU == 2) {
+        src0 = (const E*)g.gu + (int64_t)row * g.gu_ld + col;
+        src1 = src0 + g.gu_up;
+      } else if (pre_resid) {
+        src0 = R + (int64_t)row * g.ldr + col;
+      } else if (pre_rope) {                               // (cos, sin) of pairs 0,1 and 2,3 at this row's position
+        const float2* cs = g.rope + (int64_t)(row % g.rope_S) * (g.rope_d / 2) + (col % g.rope_d) / 2;
+        src0 = reinterpret_cast<const E*>(cs);
+        src1 = reinterpret_cast<const E*>(cs + 2);
+      }
+      pre0[it] = pre1[it] = u32x4{0, 0, 0, 0};
+      if (want0 && row < g.M) pre0[it] = *reinterpret_cast<const u32x4*>(src0);
+      if (want1 && row < g.M) pre1[it] = *reinterpret_cast<const u32x4*>(src1);
+    }
     if (wave_m == half) stage_quads<BN, MI, NJ>(stage, acc, wn, lane);
     __syncthreads();
-    constexpr int VPR = BN / 8;                            // 16-byte output vectors per row
 #pragma unroll
-    for (int it = 0; it < (BM / 2) * VPR / NT; ++it) {
-      const int v = tid + NT * it;
-      const int lr = v / VPR, col = n0 + (v % VPR) * 8;
-      const int row = m0 + half * (BM / 2) + lr;
+    for (int it = 0; it < NV; ++it) {
+      const int lr = lr0 + RSTEP * it, row = row0 + RSTEP * it;
       if (row >= g.M || col >= g.N) continue;
-      const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + (v % VPR) * 8);
-      const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + (v % VPR) * 8 + 4);
+      const f32x4 x0 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + cv);
+      const f32x4 x1 = *reinterpret_cast<const f32x4*>(stage + lr * LDW + cv + 4);
       float x[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
       if (GLU == 2) {   // x is da: (gate, up) of these 8 columns become (dgate, dup) in place (N is a multiple of 8)
         E* pg = (E*)g.gu + (int64_t)row * g.gu_ld + col;
-        const E8 gg = *reinterpret_cast<const E8*>(pg), uu = *reinterpret_cast<const E8*>(pg + g.gu_up);
+        const E8 gg = __builtin_bit_cast(E8, pre0[it]), uu = __builtin_bit_cast(E8, pre1[it]);
         E8 og, ou;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -255,20 +285,26 @@ __device__ __forceinline__ void epilogue_store(const Gemm& g, int z, f32x4 (&acc
         *reinterpret_cast<E8*>(pg + g.gu_up) = ou;
         continue;
       }
-      if (col + 8 <= g.N) {
+      if (full) {
         if (bias) {
-          const E8 bb = *reinterpret_cast<const E8*>(bias + col);
 #pragma unroll
           for (int e = 0; e < 8; ++e) x[e] += (float)bb[e];
         }
         if (R) {
-          const E8 rr = *reinterpret_cast<const E8*>(R + (int64_t)row * g.ldr + col);
+          const E8 rr = __builtin_bit_cast(E8, pre0[it]);
 #pragma unroll
           for (int e = 0; e < 8; ++e) x[e] += (float)rr[e];
         }
         if (rope) {   // rotate the 4 adjacent pairs by the angles of this row's position
-          const f32x4* cs = reinterpret_cast<const f32x4*>(g.rope + (int64_t)(row % g.rope_S) * (g.rope_d / 2) + (col % g.rope_d) / 2);
-          const f32x4 t0 = cs[0], t1 = cs[1];          // (cos, sin) of pairs 0,1 and 2,3
+          f32x4 t0, t1;
+          if (pre_rope) {
+            t0 = __builtin_bit_cast(f32x4, pre0[it]);
+            t1 = __builtin_bit_cast(f32x4, pre1[it]);
+          } else {
+            const f32x4* cs = reinterpret_cast<const f32x4*>(g.rope + (int64_t)(row % g.rope_S) * (g.rope_d / 2) + (col % g.rope_d) / 2);
+            t0 = cs[0];
+            t1 = cs[1];
+          }
           const float c4[4] = {t0[0], t0[2], t1[0], t1[2]}, s4[4] = {t0[1], t0[3], t1[1], t1[3]};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
