@@ -81,7 +81,10 @@ typedef struct {
                                 keeps its operands, and grad_acc is read, added to and written once per group instead
                                 of once per microbatch.  grad_acc then holds the complete sum once no forwarded
                                 microbatch is outstanding, not after every stage_accumulate.  Costs (g-1) * layers * 5
-                                activation-sized buffers of scratch.  Ignored with recompute, with max_microbatches < 2
+                                activation-sized buffers of scratch, and with a 16-bit dtype up to 256 MiB more for the
+                                products whose tiles beyond whole rounds of workgroups are split over the microbatches
+                                of the group (partial sums, added in a fixed order: the same bits on every call).
+                                Ignored with recompute, with max_microbatches < 2
                                 and when seq*microbatch is no multiple of 128. */
   int64_t act_budget_bytes;  /* 0 = unlimited; otherwise stage_query/stage_init fail with STAGE_ERR_BUDGET
                                 when the activation term exceeds it */

@@ -53,6 +53,20 @@ int stage_op_wgrad_parts(void* stream, int32_t dtype, int32_t M, int32_t N, int3
                          const void* const* A_parts, int64_t lda, const void* const* B_parts, int64_t ldb, float* C,
                          int64_t ldc, int32_t batch, int64_t sA, int64_t sB, int64_t sC, int32_t impl);
 
+/* stage_op_wgrad_parts on the MFMA kernel with the K range of the last, partly filled round of 256x256 tiles cut into
+ * chunks of whole parts that run side by side (how the stage runs the weight gradients of a group of microbatches,
+ * Section 4.1.2's accumulation over microbatches): chunk 0 adds to C, the other chunks write partial tiles into scratch
+ * (device memory, 256-byte aligned, caller-owned, free again when the call's work on the stream has finished), and a
+ * second kernel adds them to C in the order of the chunks, so a repeat gives the same bits.  The sum differs from
+ * stage_op_wgrad_parts' in rounding order only.  stage_op_wgrad_parts_scratch_bytes (host only) returns the bytes this
+ * shape needs: 0 when the tiles fill whole rounds or a cut would not pay, and then scratch may be NULL and the call is
+ * stage_op_wgrad_parts with impl 2; a negative STAGE_ERR_ARG for invalid sizes.  STAGE_ERR_ARG when the MFMA kernel does
+ * not take the arguments, STAGE_ERR_WORKSPACE when scratch is missing, misaligned or too small. */
+int64_t stage_op_wgrad_parts_scratch_bytes(int32_t M, int32_t N, int32_t K_each, int32_t K_last, int32_t nparts, int32_t batch);
+int stage_op_wgrad_parts_cut(void* stream, int32_t dtype, int32_t M, int32_t N, int32_t K_each, int32_t K_last, int32_t nparts,
+                             const void* const* A_parts, int64_t lda, const void* const* B_parts, int64_t ldb, float* C,
+                             int64_t ldc, int32_t batch, int64_t sA, int64_t sB, int64_t sC, void* scratch, int64_t scratch_bytes);
+
 /* The gated FFN unit of the Llama-style layer fused into the store of a product (the layer the paper's Llama
  * workloads are built from, Section 6.1); gu is dense [M, 2N] = [gate | up], a dense [M, N].
  * mode 1 (forward): gate = A Wg and up = A Wu are written, rounded, to gu and silu(gate) * up of the ROUNDED values

@@ -114,6 +114,10 @@ def lib():
         L.stage_op_wgrad_pair.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, i64, vp, vp, i64, vp, i64, i32, i64, i64, i64, i32]
         L.stage_op_wgrad_parts.argtypes = [vp, i32, i32, i32, i32, i32, i32, C.POINTER(vp), i64, C.POINTER(vp), i64, vp, i64, i32,
                                            i64, i64, i64, i32]
+        L.stage_op_wgrad_parts_cut.argtypes = [vp, i32, i32, i32, i32, i32, i32, C.POINTER(vp), i64, C.POINTER(vp), i64, vp, i64, i32,
+                                               i64, i64, i64, vp, i64]
+        L.stage_op_wgrad_parts_scratch_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+        L.stage_op_wgrad_parts_scratch_bytes.restype = i64
         L.stage_op_norm_fwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, f32, vp, vp, vp]
         L.stage_op_norm_bwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32]
         L.stage_op_rope.argtypes = [vp, i32, i32, i32, i32, i32, vp, i64, f32, f32, vp]
@@ -331,6 +335,26 @@ class _Ops:
 
 
 ops = _Ops()
+
+
+def wgrad_parts_scratch_bytes(M, N, K_each, K_last, nparts, batch=1):
+    """stage_op_wgrad_parts_scratch_bytes (host only)."""
+    n = lib().stage_op_wgrad_parts_scratch_bytes(M, N, K_each, K_last, nparts, batch)
+    if n < 0:
+        raise StageError(-n, "stage_op_wgrad_parts_scratch_bytes")
+    return n
+
+
+def wgrad_parts_cut(stream, dtype, M, N, K_each, K_last, A_parts, lda, B_parts, ldb, Cbuf, ldc, batch=1, sA=0, sB=0, sC=0,
+                    scratch=None, scratch_bytes=0):
+    """stage_op_wgrad_parts_cut with lists of device tensors for the parts."""
+    n = len(A_parts)
+    pa = (C.c_void_p * n)(*[t.data_ptr() for t in A_parts])
+    pb = (C.c_void_p * n)(*[t.data_ptr() for t in B_parts])
+    code = lib().stage_op_wgrad_parts_cut(stream, dtype, M, N, K_each, K_last, n, pa, lda, pb, ldb, _ptr(Cbuf), ldc, batch, sA, sB, sC,
+                                          _ptr(scratch), scratch_bytes)
+    if code != STAGE_OK:
+        raise StageError(code, "stage_op_wgrad_parts_cut")
 
 
 def wgrad_parts(stream, dtype, M, N, K_each, K_last, A_parts, lda, B_parts, ldb, Cbuf, ldc, batch=1, sA=0, sB=0, sC=0, impl=0):

@@ -126,10 +126,115 @@ bool split_tail(DType dt, const Gemm& g, Gemm& head, Gemm& tail) {
   return gemm_mfma_supported(dt, head) && gemm_mfma_supported(dt, tail);
 }
 
+// ---- K range of the last round's tiles cut into chunks -------------------------------------------------------------
+// A multi-part product whose 256x256 tiles do not fill whole rounds of 256 workgroups is cut in two along N (whole tile
+// columns) or along M (whole tile rows): the leading tiles run as whole rounds, and the remaining `rem` tiles as one launch
+// of rem x nchunks workgroups, each multiplying chunk_parts of the parts.  Chunk 0 adds to C; the other chunks leave
+// partial tiles in scratch, which add_partials_kernel adds to C in the order of the chunks.
+struct KCut {
+  Gemm head, tail;
+  int rem = 0;              // tiles of the cut-off part (over all batches)
+  int64_t ws_need = 0;      // bytes of partial tiles
+};
+
+constexpr int64_t KCUT_MAX_WS = 256ll << 20;   // no plan wants more scratch than this
+
+// Times of the cut-off tiles are estimated in units of one part on one tile, 2*256*256*kseg flops at the 5.3 TFLOP/s a
+// CU sustains.  A round of workgroups costs its parts plus about 20 us for its first loads and its store pass; the second
+// kernel reads the partial tiles and reads and writes C at about 4 TB/s.  Measured at 11008 x 4096 with 8 parts of 4096 rows:
+// 2538 us uncut, 2458 us in 4 chunks of 2 parts (the estimate says 79 us less); with 4 parts a cut costs time, and is not made.
+double kcut_part_seconds(int kseg) { return 2.0 * 256.0 * 256.0 * (double)kseg / 5.3e12; }
+double kcut_round_fixed_parts(int kseg) { return 20e-6 / kcut_part_seconds(kseg); }
+double kcut_fixup_parts(int rem, int nch, int kseg) {
+  const double bytes = (double)(nch - 1 + 2) * rem * 256.0 * 256.0 * 4.0;
+  return bytes / 4.0e12 / kcut_part_seconds(kseg);
+}
+
+bool plan_kcut(const Gemm& g, KCut& k) {
+  if (!g.nx || !g.c_f32_accum || !g.transA || g.transB || g.kseg < 1) return false;
+  const int64_t tm = cdiv(g.M, 256), tn = cdiv(g.N, 256), tiles = tm * tn * g.batch, rem = tiles % 256;
+  if (tiles < 256 || rem == 0) return false;
+  k.head = g; k.tail = g;
+  k.head.ws = nullptr; k.head.ws_bytes = 0;
+  const double fx = kcut_round_fixed_parts(g.kseg);
+  double t_now = (double)(g.nx + 1) + fx;                             // a whole round
+  if (rem % (tm * g.batch) == 0) {                                    // whole tile columns
+    const int64_t n1 = (tn - rem / (tm * g.batch)) * 256;
+    k.head.N = (int)n1; k.tail.N = g.N - (int)n1;
+    k.tail.C = (char*)g.C + n1 * 4;
+    k.tail.B = (const char*)g.B + n1 * 2;
+    for (int p = 0; p < g.nx; ++p) k.tail.Bx[p] = (const char*)g.Bx[p] + n1 * 2;
+    if (rem <= 128) t_now = small_rounds(cdiv(g.M, 128) * cdiv(k.tail.N, 128) * g.batch) * (g.nx + 1 + fx);   // what split_tail would do
+  } else if (rem % (tn * g.batch) == 0) {                             // whole tile rows (A is stored [K, M])
+    const int64_t m1 = (tm - rem / (tn * g.batch)) * 256;
+    k.head.M = (int)m1; k.tail.M = g.M - (int)m1;
+    k.tail.C = (char*)g.C + m1 * g.ldc * 4;
+    k.tail.A = (const char*)g.A + m1 * 2;
+    for (int p = 0; p < g.nx; ++p) k.tail.Ax[p] = (const char*)g.Ax[p] + m1 * 2;
+  } else {
+    return false;
+  }
+  const int parts = g.nx + 1;
+  double best = t_now * 0.97;                                         // a cut has to win at least 3 %
+  int best_cp = 0;
+  for (int cp = 1; cp < parts; ++cp) {
+    const int nch = (int)cdiv(parts, cp);
+    if ((int64_t)(nch - 1) * rem * 256 * 256 * 4 > KCUT_MAX_WS) continue;
+    const double t = (double)cdiv(rem * nch, 256) * (cp + fx) + kcut_fixup_parts((int)rem, nch, g.kseg);
+    if (t < best) { best = t; best_cp = cp; }
+  }
+  if (!best_cp) return false;
+  k.rem = (int)rem;
+  k.tail.chunk_parts = best_cp;
+  k.tail.nchunks = (int)cdiv(parts, best_cp);
+  k.ws_need = (int64_t)(k.tail.nchunks - 1) * rem * 256 * 256 * 4;
+  return true;
+}
+
+// C tile += partial tile of chunk 1, then of chunk 2, ...: one workgroup per quarter tile (64 rows), 16 bytes per lane.
+__global__ __launch_bounds__(256) void add_partials_kernel(float* C, int64_t ldc, int64_t sC, int M, int N, int tiles_n,
+                                                           const float* __restrict__ partial, int nadd) {
+  const int t = blockIdx.x >> 2, quarter = blockIdx.x & 3, z = blockIdx.y;
+  const int64_t tiles = gridDim.x >> 2, batch = gridDim.y;
+  const int m0 = (t / tiles_n) * 256 + quarter * 64, n0 = (t % tiles_n) * 256;
+  float* Cz = C + (int64_t)z * sC;
+  const float* P0 = partial + ((int64_t)z * tiles + t) * 65536 + quarter * 64 * 256;
+  const int64_t chunk_stride = batch * tiles * 65536;
+#pragma unroll 4
+  for (int v = threadIdx.x; v < 64 * 64; v += 256) {
+    const int r = v >> 6, c = (v & 63) * 4;
+    if (m0 + r >= M || n0 + c >= N) continue;                         // N is a multiple of 4
+    float* pc = Cz + (int64_t)(m0 + r) * ldc + n0 + c;
+    f32x4 s = *reinterpret_cast<const f32x4*>(pc);
+    for (int a = 0; a < nadd; ++a) s += *reinterpret_cast<const f32x4*>(P0 + a * chunk_stride + r * 256 + c);
+    *reinterpret_cast<f32x4*>(pc) = s;
+  }
+}
+
 }  // namespace
+
+int64_t gemm_mfma_ws_bytes(const Gemm& g) {
+  KCut k;
+  return (!g_force_tile && plan_kcut(g, k)) ? k.ws_need : 0;
+}
 
 hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g) {
   const bool small = gemm_mfma_pick_tile(g) == 2;
+  if (g.ws && !g_force_tile) {
+    KCut k;
+    if (plan_kcut(g, k) && k.ws_need <= g.ws_bytes && ((uintptr_t)g.ws & 15) == 0 && gemm_mfma_supported(dt, k.head) &&
+        gemm_mfma_supported(dt, k.tail)) {
+      hipError_t e = run_tile(st, dt, k.head, false);
+      if (e != hipSuccess) return e;
+      e = run_tile(st, dt, k.tail, false);
+      if (e != hipSuccess) return e;
+      const int tiles = (int)(cdiv(k.tail.M, 256) * cdiv(k.tail.N, 256));
+      hipLaunchKernelGGL(add_partials_kernel, dim3((unsigned)(tiles * 4), (unsigned)k.tail.batch), dim3(256), 0, st,
+                         (float*)k.tail.C, k.tail.ldc, k.tail.sC, k.tail.M, k.tail.N, (int)cdiv(k.tail.N, 256),
+                         (const float*)g.ws, k.tail.nchunks - 1);
+      return hipGetLastError();
+    }
+  }
   Gemm head, tail;
   if (!g_force_tile && split_tail(dt, g, head, tail)) {
     // whole rounds of big tiles + the rest on small ones, against the better of the two uniform grids

@@ -157,24 +157,23 @@ __device__ __forceinline__ void stage_quads(float* stage, f32x4 (&acc)[MI][NJ], 
       *reinterpret_cast<f32x4*>(stage + (i * 16 + (lane & 15)) * LDW + wn + j * 16 + 4 * (lane >> 4)) = acc[i][j];
 }
 
-// Epilogue for C (fp32) += product (no bias, no residual).  After staging, ALL threads walk the half tile
-// 4 columns at a time: the old values of C are loaded 16 bytes per lane (consecutive lanes, consecutive
-// pieces of a row), all loads of a half in flight across the barrier, then sum and store.  Loads and
-// stores go through a buffer descriptor over C: rows past M fall beyond num_records and columns past N
-// are sent there, so the ragged edge needs no branches.  A tile belongs to one workgroup and launches
-// are ordered by the stream, so the sum over microbatches is formed in a fixed order.
+// Epilogue for C (fp32) += product (no bias, no residual).  Ct points at the tile's first element, of which rows x cols
+// exist.  After staging, ALL threads walk the half tile 4 columns at a time: the old values of C are loaded 16 bytes per
+// lane (consecutive lanes, consecutive pieces of a row), all loads of a half in flight across the barrier, then sum and
+// store.  Loads and stores go through a buffer descriptor over the tile: rows past the last one fall beyond num_records
+// and columns past the last one are sent there, so the ragged edge needs no branches.  A tile belongs to one workgroup and
+// launches are ordered by the stream, so the sum over microbatches is formed in a fixed order.  overwrite: the tile is
+// stored as it is (a partial sum that another kernel adds to C).
 template <int BM, int BN, int NT, int MI, int NJ>
-__device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x4 (&acc)[MI][NJ], int m0, int n0, int wave_m,
-                                               int wn, int tid, float* stage) {
+__device__ __forceinline__ void epilogue_accum(float* Ct, int ldc, int rows, int cols, bool overwrite, f32x4 (&acc)[MI][NJ],
+                                               int wave_m, int wn, int tid, float* stage) {
   constexpr int LDW = Staging<BN>::LDW;
   static_assert((BM / 2) * LDW * 4 <= 2 * (slab_elems(BM) + slab_elems(BN)) * 2, "staging tile must fit the K-loop buffers");
   constexpr int VPR = BN / 4;                              // float4 per row
   constexpr int NV = (BM / 2) * VPR / NT;                  // float4 per thread and half
-  float* Cz = (float*)g.C + (int64_t)z * g.sC;
-  const int ldc = (int)g.ldc;
-  const __amdgpu_buffer_rsrc_t rsC = make_rsrc(Cz, (uint32_t)((int64_t)(g.M - 1) * ldc + g.N) * 4u);
+  const __amdgpu_buffer_rsrc_t rsC = make_rsrc(Ct, (uint32_t)((int64_t)(rows - 1) * ldc + cols) * 4u);
   const int lr0 = tid / VPR, cv = tid % VPR;               // vector v = tid + NT*it: row lr0 + (NT/VPR)*it, same columns
-  const bool col_ok = n0 + cv * 4 < g.N;                   // N is a multiple of 4
+  const bool col_ok = cv * 4 < cols;                       // cols is a multiple of 4
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     __syncthreads();
@@ -183,9 +182,9 @@ __device__ __forceinline__ void epilogue_accum(const Gemm& g, int z, f32x4 (&acc
     uint32_t off[NV];
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
-      const int row = m0 + half * (BM / 2) + lr0 + (NT / VPR) * it;
-      off[it] = col_ok ? (uint32_t)(row * ldc + n0 + cv * 4) * 4u : 0x80000000u;
-      old[it] = __builtin_amdgcn_raw_buffer_load_b128(rsC, (int)off[it], 0, 0);
+      const int row = half * (BM / 2) + lr0 + (NT / VPR) * it;
+      off[it] = col_ok ? (uint32_t)(row * ldc + cv * 4) * 4u : 0x80000000u;
+      old[it] = overwrite ? u32x4{0u, 0u, 0u, 0u} : __builtin_amdgcn_raw_buffer_load_b128(rsC, (int)off[it], 0, 0);
     }
     __syncthreads();
 #pragma unroll
@@ -418,17 +417,23 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
                             : ((int64_t)(K1 - 1) * ldb + g.N + (GLU == 1 ? g.sB : 0))) * 2u);
   // Descriptors of part p >= 1 (the last part has the rows that remain); a part past the last one gets an empty
   // range, so a surplus slab reads zeros.
+  // A launch may cut the K range into chunks of chunk_parts parts (grid.z chunks): this workgroup then multiplies the
+  // parts p0..p1 only; chunk 0 adds its tile to C, the others store theirs as partial sums.
+  const int chunk = (PAIR && ACC) ? (int)blockIdx.z : 0;
+  const int cparts = (PAIR && ACC && g.chunk_parts > 0 && gridDim.z > 1) ? g.chunk_parts : g.nx + 1;
+  const int p0 = chunk * cparts, p1 = min(g.nx, p0 + cparts - 1);
   auto part_a = [&](int p) {
     const int rows = p < g.nx ? K1 : g.K - g.nx * K1;
-    return p <= g.nx ? make_rsrc((const bf16*)g.Ax[p - 1] + (int64_t)z * g.sA, (uint32_t)((int64_t)(rows - 1) * lda + g.M) * 2u)
-                     : make_rsrc(A, 0u);
+    return (p >= 1 && p <= p1) ? make_rsrc((const bf16*)g.Ax[p - 1] + (int64_t)z * g.sA, (uint32_t)((int64_t)(rows - 1) * lda + g.M) * 2u)
+                               : make_rsrc(A, 0u);
   };
   auto part_b = [&](int p) {
     const int rows = p < g.nx ? K1 : g.K - g.nx * K1;
-    return p <= g.nx ? make_rsrc((const bf16*)g.Bx[p - 1] + (int64_t)z * g.sB, (uint32_t)((int64_t)(rows - 1) * ldb + g.N) * 2u)
-                     : make_rsrc(B, 0u);
+    return (p >= 1 && p <= p1) ? make_rsrc((const bf16*)g.Bx[p - 1] + (int64_t)z * g.sB, (uint32_t)((int64_t)(rows - 1) * ldb + g.N) * 2u)
+                               : make_rsrc(B, 0u);
   };
-  __amdgpu_buffer_rsrc_t curA = rsA, curB = rsB;         // PAIR: descriptors of the part whose slabs are being loaded
+  // PAIR: descriptors of the part whose slabs are being loaded
+  __amdgpu_buffer_rsrc_t curA = p0 == 0 ? rsA : part_a(p0), curB = p0 == 0 ? rsB : part_b(p0);
   const int voffA = TA == 0 ? ((tid >> 3) * lda + (tid & 7) * 8) * 2 : voff_rmajor<BM>(lda, tid, m0, g.M);
   const int voffB = TB == 1     ? ((tid >> 3) * ldb + (tid & 7) * 8) * 2
                     : GLU == 1 ? voff_rmajor_two<BN>(ldb, tid, nb0, g.N, (int)g.sB)
@@ -528,9 +533,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     stash_b(0, fb0);
     fetch_part(BK, fa1, fb1);
     __syncthreads();
-    for (int p = 0; p <= g.nx + 1; ++p) {
-      const int pairs = p < g.nx ? full : p == g.nx ? tail : 1;
-      for (int j = p == 0 ? 1 : 0; j < pairs; ++j) {
+    for (int p = p0; p <= p1 + 1; ++p) {
+      const int pairs = p > p1 ? 1 : p < g.nx ? full : tail;
+      for (int j = p == p0 ? 1 : 0; j < pairs; ++j) {
         multiply(0, fa1, fb1, [&](int i0, int i1) { fetch_part(j * 2 * BK, fa0, fb0, i0, i1); });
         __syncthreads();
         multiply(1, fa0, fb0, [&](int i0, int i1) { fetch_part(j * 2 * BK + BK, fa1, fb1, i0, i1); });
@@ -553,7 +558,17 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
     }
   }
 
-  if (ACC) epilogue_accum<BM, BN, NT, MI, NJ>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
+  if (ACC) {
+    if (chunk == 0) {
+      float* Ct = (float*)g.C + (int64_t)z * g.sC + (int64_t)m0 * g.ldc + n0;
+      epilogue_accum<BM, BN, NT, MI, NJ>(Ct, (int)g.ldc, min(BM, g.M - m0), min(BN, g.N - n0), false, acc, wave / WN, wn, tid,
+                                         reinterpret_cast<float*>(smem_raw));
+    } else {   // partial tile number ((chunk-1) * batch + z) * tiles + tile, tiles counted row by row
+      const int64_t slot = ((int64_t)(chunk - 1) * gridDim.y + z) * gridDim.x + (m0 / BM) * tiles_n + n0 / BN;
+      epilogue_accum<BM, BN, NT, MI, NJ>((float*)g.ws + slot * (BM * BN), BN, BM, BN, true, acc, wave / WN, wn, tid,
+                                         reinterpret_cast<float*>(smem_raw));
+    }
+  }
   else if (GLU == 1) epilogue_glu<E, BM, BN, NT, MI, NJ>(g, acc, m0, nb0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
   else epilogue_store<E, BM, BN, NT, MI, NJ, GLU>(g, z, acc, m0, n0, wave / WN, wn, tid, reinterpret_cast<float*>(smem_raw));
 }
@@ -569,7 +584,8 @@ hipError_t launch2(hipStream_t st, const Gemm& g) {
     configured = true;
   }
   const int tiles_m = (int)cdiv(g.M, BM), tiles_n = (int)cdiv(g.N, GLU == 1 ? BN / 2 : BN);   // a gate|up tile holds BN/2 columns of each
-  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)g.batch), blk(64 * NW);
+  const bool chunks = SEG && TA == 1 && TB == 0 && ACC && g.chunk_parts > 0 && g.nchunks > 1;
+  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)g.batch, chunks ? (unsigned)g.nchunks : 1u), blk(64 * NW);
   hipLaunchKernelGGL(kern, grid, blk, SMEM_BYTES, st, g, tiles_m, tiles_n);
   return hipGetLastError();
 }

@@ -17,6 +17,11 @@ namespace zs {
 //             their own, part 0 from A, B and part p from Ax[p-1], Bx[p-1] (same leading dimensions and batch
 //             strides); parts 0..nx-1 have kseg rows each, the last one the remaining K - nx*kseg > 0 rows:
 //             C += sum_p A_p^T B_p in one K loop (weight gradients of several microbatches).
+//   ws != NULL (nx > 0 only): ws_bytes of scratch that the MFMA path may use when the 256x256 tiles of the product do
+//             not fill whole rounds of 256 workgroups: the tiles of the last, partly filled round then have their K
+//             range cut into chunks of whole parts that run side by side, chunk 0 adding to C and the others writing
+//             partial tiles into ws, which a second kernel adds to C in the order of the chunks.  The result differs
+//             from the uncut product in rounding order only and is the same on every call.
 //   rope != NULL (c_f32_accum = 0 only): for batch indices z < rope_batches the adjacent column pairs of
 //             every head (rope_d columns wide) of C are rotated, after bias and residual and before the
 //             result is rounded, by the angle table[(row % rope_S) * rope_d/2 + pair] (cos, sin).
@@ -42,6 +47,8 @@ struct Gemm {
   int batch = 1; int64_t sA = 0, sB = 0, sC = 0, sBias = 0;
   int kseg = 0; int64_t segB = 0;
   int nx = 0; const void* Ax[GEMM_MAX_PARTS - 1] = {}; const void* Bx[GEMM_MAX_PARTS - 1] = {};
+  void* ws = nullptr; int64_t ws_bytes = 0;
+  int chunk_parts = 0, nchunks = 1;   // set by gemm_mfma for the launch that runs the chunks, not by callers
   const float2* rope = nullptr; int rope_S = 0, rope_d = 0, rope_batches = 0;
   int glu = 0; void* gu = nullptr; int64_t gu_ld = 0, gu_up = 0;
 };
@@ -54,6 +61,9 @@ bool gemm_splits(DType dt, const Gemm& g);
 hipError_t gemm_simple(hipStream_t st, DType dt, const Gemm& g);
 bool gemm_mfma_supported(DType dt, const Gemm& g);
 hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g);
+// Scratch bytes (Gemm::ws) with which gemm_mfma would cut the K range of this product's last round of tiles; 0 when
+// it would not (the answer depends on the shape only, not on the pointers).
+int64_t gemm_mfma_ws_bytes(const Gemm& g);
 // Workgroup tile the MFMA kernel would use: 1 = 256x256 (8 waves), 2 = 128x128 (4 waves); force_tile(0) = automatic.
 int gemm_mfma_pick_tile(const Gemm& g);
 void gemm_mfma_force_tile(int id);

@@ -101,6 +101,41 @@ int stage_op_wgrad_parts(void* stream, int32_t dtype, int32_t M, int32_t N, int3
   return rc(e);
 }
 
+namespace {
+Gemm wgrad_parts_gemm(int32_t M, int32_t N, int32_t K_each, int32_t K_last, int32_t nparts, int64_t lda, int64_t ldb, int64_t ldc,
+                      int32_t batch, int64_t sA, int64_t sB, int64_t sC) {
+  Gemm g;
+  g.M = M; g.N = N; g.K = K_each * (nparts - 1) + K_last; g.transA = 1; g.transB = 0; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.c_f32_accum = 1; g.batch = batch; g.sA = sA; g.sB = sB; g.sC = sC;
+  g.nx = nparts - 1;
+  if (g.nx) g.kseg = K_each;
+  return g;
+}
+}  // namespace
+
+int64_t stage_op_wgrad_parts_scratch_bytes(int32_t M, int32_t N, int32_t K_each, int32_t K_last, int32_t nparts, int32_t batch) {
+  if (M < 1 || N < 1 || K_each < 1 || K_last < 1 || nparts < 1 || nparts > GEMM_MAX_PARTS || batch < 1) return -STAGE_ERR_ARG;
+  return gemm_mfma_ws_bytes(wgrad_parts_gemm(M, N, K_each, K_last, nparts, M, N, N, batch, 0, 0, 0));
+}
+
+int stage_op_wgrad_parts_cut(void* stream, int32_t dtype, int32_t M, int32_t N, int32_t K_each, int32_t K_last, int32_t nparts,
+                             const void* const* A_parts, int64_t lda, const void* const* B_parts, int64_t ldb, float* C,
+                             int64_t ldc, int32_t batch, int64_t sA, int64_t sB, int64_t sC, void* scratch, int64_t scratch_bytes) {
+  if (!dt_ok(dtype) || M < 1 || N < 1 || K_each < 1 || K_last < 1 || nparts < 1 || nparts > GEMM_MAX_PARTS || batch < 1 ||
+      !A_parts || !B_parts || !C)
+    return STAGE_ERR_ARG;
+  for (int p = 0; p < nparts; ++p)
+    if (!A_parts[p] || !B_parts[p]) return STAGE_ERR_ARG;
+  Gemm g = wgrad_parts_gemm(M, N, K_each, K_last, nparts, lda, ldb, ldc, batch, sA, sB, sC);
+  g.A = A_parts[0]; g.B = B_parts[0]; g.C = C;
+  for (int p = 1; p < nparts; ++p) { g.Ax[p - 1] = A_parts[p]; g.Bx[p - 1] = B_parts[p]; }
+  if (!gemm_mfma_supported((DType)dtype, g)) return STAGE_ERR_ARG;
+  const int64_t need = gemm_mfma_ws_bytes(g);
+  if (need > 0 && (!scratch || ((uintptr_t)scratch & 255) || scratch_bytes < need)) return STAGE_ERR_WORKSPACE;
+  g.ws = need > 0 ? scratch : nullptr; g.ws_bytes = need > 0 ? scratch_bytes : 0;
+  return rc(gemm((hipStream_t)stream, (DType)dtype, g, GEMM_MFMA));
+}
+
 int stage_op_gemm_glu(void* stream, int32_t dtype, int32_t mode, int32_t M, int32_t N, int32_t K, const void* A, int64_t lda,
                       const void* B, int64_t ldb, int64_t sB, void* a, void* gu, int32_t impl) {
   if (!dt_ok(dtype) || (mode != 1 && mode != 2) || M < 1 || N < 1 || K < 1 || !A || !B || !a || !gu) return STAGE_ERR_ARG;

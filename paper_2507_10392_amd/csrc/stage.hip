@@ -136,6 +136,7 @@ struct Plan {
   // scratch
   char *gA, *gB, *gN, *gO, *gQKV, *gF1, *ytmp;
   std::vector<char*> kdy, kdx2, kdqkv;   // pair_wgrad: per deferred microbatch and layer (index set*L + l), its dy, dx2 and dqkv
+  char* kcut = nullptr; int64_t kcut_bytes = 0;   // pair_wgrad: partial tiles of the weight-gradient products whose last round is cut along K
   float* delta; float* lossdump;
   float2* rope;
   float* partials; int64_t partial_floats;
@@ -230,6 +231,22 @@ void make_plan(const stage_config& c, char* base, Plan& p, char* scratch_base = 
     const size_t n = (size_t)(s.group - 1) * s.L;
     p.kdy.resize(n); p.kdx2.resize(n); p.kdqkv.resize(n);
     for (size_t i = 0; i < n; ++i) { p.kdy[i] = b.take(TH); p.kdx2[i] = b.take(TH); p.kdqkv[i] = b.take(3 * TH); }
+    // scratch for the four weight-gradient products of a full group (smaller groups need less)
+    auto need = [&](int M, int N, int batch) {
+      Gemm g;
+      g.M = M; g.N = N; g.K = s.group * s.T; g.transA = 1; g.c_f32_accum = 1; g.batch = batch; g.nx = s.group - 1; g.kseg = s.T;
+      int64_t most = 0;
+      for (int nd = 2; nd <= s.group; ++nd) {              // a group closed early has fewer parts
+        g.nx = nd - 1; g.K = nd * s.T;
+        most = std::max(most, gemm_mfma_ws_bytes(g));
+      }
+      return most;
+    };
+    const bool gpt = s.arch == STAGE_ARCH_GPT;
+    p.kcut_bytes = std::max(std::max(need(s.F, s.H, 1), gpt ? need(s.H, s.F, 1) : need(s.H, s.F, 2)),
+                            std::max(need(s.H, s.H, 1), gpt ? need(s.H, 3 * s.H, 1) : need(s.H, s.H, 3)));
+    if (s.bf && p.kcut_bytes) p.kcut = b.take(p.kcut_bytes);
+    else p.kcut_bytes = 0;
   }
   p.delta = b.take<float>(4ll * s.mb * s.nh * s.S);
   p.lossdump = b.take<float>(256);
@@ -508,6 +525,7 @@ bool layer_backward(stage_t* s, int l, const char* x_in, LayerActs& A, const cha
     if (wg.mode == 2) {
       w.nx = wg.nx; w.kseg = T; w.K = (wg.nx + 1) * T;
       for (int i = 0; i < wg.nx; ++i) { w.Ax[i] = wg.Ax[i]->*xsel; w.Bx[i] = dsel(i); }
+      w.ws = pl.kcut; w.ws_bytes = pl.kcut_bytes;
     }
     return do_gemm(s, w);
   };
@@ -640,7 +658,7 @@ bool flush_deferred(stage_t* s) {
     auto parts = [&](Gemm& g, char* LayerActs::*xsel, auto dsel) {   // part 0 = first deferred, the others follow
       g.A = acts(0).*xsel; g.B = dsel(0);
       g.K = nd * T;
-      if (nd > 1) { g.nx = nd - 1; g.kseg = T; }
+      if (nd > 1) { g.nx = nd - 1; g.kseg = T; g.ws = pl.kcut; g.ws_bytes = pl.kcut_bytes; }
       for (int i = 1; i < nd; ++i) { g.Ax[i - 1] = acts(i).*xsel; g.Bx[i - 1] = dsel(i); }
     };
     Gemm g;

@@ -200,6 +200,18 @@ def test_ops_reject_bad_arguments_on_the_host():
     assert L.stage_op_lds_probe(None, 0, odd, fake, 10, fake) == zs.STAGE_ERR_ARG      # 16-byte reads at 16-byte offsets
     assert L.stage_op_lds_probe(None, 1, good, None, 10, fake) == zs.STAGE_ERR_ARG
     assert L.stage_op_adamw(None, 0, 8, 0, fake, None, fake, fake, fake, 1e-4, 0.9, 0.999, 1e-8, 0.01, 0, 1.0) == zs.STAGE_ERR_ARG
+    # weight gradients with the last round cut along K: sizes, a shape that is cut but gets no scratch, a float dtype
+    assert L.stage_op_wgrad_parts_scratch_bytes(0, 8, 128, 128, 2, 1) == -zs.STAGE_ERR_ARG
+    assert L.stage_op_wgrad_parts_scratch_bytes(4096, 4096, 4096, 4096, 8, 1) == 0            # 256 tiles: whole rounds
+    assert L.stage_op_wgrad_parts_scratch_bytes(4096, 4096, 4096, 4096, 1, 1) == 0            # one part: nothing to cut
+    need = L.stage_op_wgrad_parts_scratch_bytes(11008, 4096, 4096, 4096, 8, 1)                # 688 tiles: 176 beyond two rounds
+    assert need > 0 and need % (256 * 256 * 4) == 0 and need <= 256 << 20
+    parts = (C.c_void_p * 8)(*[0x10000] * 8)
+    cut = L.stage_op_wgrad_parts_cut
+    assert cut(None, 1, 11008, 4096, 4096, 4096, 8, parts, 11008, parts, 4096, fake, 4096, 1, 0, 0, 0, None, 0) == zs.STAGE_ERR_WORKSPACE
+    assert cut(None, 1, 11008, 4096, 4096, 4096, 8, parts, 11008, parts, 4096, fake, 4096, 1, 0, 0, 0, fake, need - 1) == zs.STAGE_ERR_WORKSPACE
+    assert cut(None, 0, 11008, 4096, 4096, 4096, 8, parts, 11008, parts, 4096, fake, 4096, 1, 0, 0, 0, fake, need) == zs.STAGE_ERR_ARG
+    assert cut(None, 1, 11008, 4096, 4096, 4096, 8, None, 11008, parts, 4096, fake, 4096, 1, 0, 0, 0, fake, need) == zs.STAGE_ERR_ARG
     assert L.stage_op_norm_fwd(None, 1, 1, 4, 12, fake, fake, None, 1e-5, fake, fake, None) == zs.STAGE_ERR_ARG
     assert L.stage_op_attention_fwd(None, 1, 1, 16, 1, 12, fake, fake, fake, 12, fake, 12, fake, 0) == zs.STAGE_ERR_ARG
     # fused gated unit: unknown mode, missing buffer, and a forced MFMA kernel with float or unaligned arguments

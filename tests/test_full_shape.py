@@ -191,3 +191,52 @@ def test_full_shape_stage_properties(gpu_device):
     assert torch.equal(y2[0], y1[0]) and torch.equal(y2[1], y1[0]) and torch.equal(dx2[0], dx1[0])
     assert torch.equal(g2, 2.0 * g1)
     assert bool(torch.isfinite(g1).all()) and float(g1.abs().max()) > 0
+
+
+def test_grouped_weight_gradients_with_cut_rounds_at_full_shape(gpu_device):
+    """C3's shape, one layer, 8 microbatches with inputs of their own: with pair_wgrad = 8 the products for Wd (688 tiles)
+    and Wg (1376) have the tiles beyond whole rounds of 256 workgroups cut over the microbatches (partial tiles in scratch,
+    added in a fixed order).  The accumulated gradient equals the one of eight separate accumulations up to rounding order,
+    a repeat gives the same bits, and the stage asks for the scratch that the cut needs."""
+    base = get_config("C3").with_(layers=1, num_microbatches=8, shard_num=1, shard_den=1)
+    print("[case] full-shape grouped weight gradients with cut rounds", flush=True)
+    assert zs.wgrad_parts_scratch_bytes(base.ffn, base.hidden, base.tokens, base.tokens, 8, 1) > 0      # Wd
+    assert zs.wgrad_parts_scratch_bytes(base.hidden, base.ffn, base.tokens, base.tokens, 8, 2) > 0      # Wg: gate and up
+    g = torch.Generator(device="cuda").manual_seed(5)
+    P, T, H = base.n_params, base.tokens, base.hidden
+    params = (torch.randn(P, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    xs = [torch.randn(T, H, device="cuda", generator=g).to(torch.bfloat16) for _ in range(8)]
+    dys = [(torch.randn(T, H, device="cuda", generator=g) * 0.01).to(torch.bfloat16) for _ in range(8)]
+
+    def run(group):
+        cc = zs.make_config(base.with_(pair_wgrad=group))
+        _, mem, _ = zs.query(cc)
+        grad = torch.zeros(P, device="cuda")
+        m, v = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+        ws = torch.empty(mem["workspace"], dtype=torch.uint8, device="cuda")
+        stage = zs.Stage(cc, params.clone(), params.float(), grad, m, v, ws)
+        y = torch.empty(T, H, dtype=torch.bfloat16, device="cuda")
+        dx = torch.empty(T, H, dtype=torch.bfloat16, device="cuda")
+        for i in range(8):
+            stage.forward(i, xs[i], y)
+        for i in reversed(range(8)):
+            stage.backward(i, dys[i], dx)
+            stage.accumulate(i)
+        torch.cuda.synchronize()
+        stage.close()
+        return grad, mem
+
+    g0, mem0 = run(0)
+    g8, mem8 = run(8)
+    g8b, _ = run(8)
+    assert torch.equal(g8, g8b), "a repeat must give the same bits"
+    assert mem8["scratch"] - mem0["scratch"] >= 7 * 5 * T * H * 2 + (160 << 20)          # kept operands + partial tiles
+    worst = 0.0
+    for name, off, rows, cols in zs.layout(zs.make_config(base)):
+        n = rows * cols
+        a, b = g8[off:off + n], g0[off:off + n]
+        scale = float(b.abs().max())
+        if scale > 0:
+            worst = max(worst, float((a - b).abs().max()) / scale)
+    print(f"[info] worst segment difference grouped vs separate: {worst:.3e}", flush=True)
+    assert worst <= 2e-5 and bool(torch.isfinite(g8).all())

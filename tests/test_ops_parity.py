@@ -484,6 +484,56 @@ def test_weight_gradient_of_several_microbatches(gpu_device, dtype, impl, shape)
     assert err <= 2e-5
 
 
+# (M, N, K_each, K_last, parts, batch): grids of 272 tiles of 256x256, i.e. one round of 256 workgroups and 16 tiles more,
+# which make up one tile row (first two cases: the cut runs along M; the last tile row is ragged in the second) or one
+# three tile columns of two batches (third case: along N, ragged columns, eight chunks).
+@pytest.mark.parametrize("dtype", [1, 2])
+@pytest.mark.parametrize("shape", [(4352, 4096, 128, 128, 4, 1), (4344, 4088, 256, 72, 5, 1), (4096, 2808, 1536, 1000, 8, 2)])
+def test_weight_gradient_with_the_last_round_cut_along_k(gpu_device, dtype, shape):
+    """stage_op_wgrad_parts_cut: the tiles beyond whole rounds of workgroups have their K range cut into chunks whose partial
+    tiles a second kernel adds to C.  Against float64 on whole rows and columns that cross both regions; two calls give the
+    same bits; and the scratch buffer is checked."""
+    M, N, K_each, K_last, nparts, batch = shape
+    print(f"[case] wgrad parts cut {shape} dtype={dtype}", flush=True)
+    need = zs.wgrad_parts_scratch_bytes(M, N, K_each, K_last, nparts, batch)
+    assert need > 0 and need % (256 * 256 * 4) == 0, "these shapes are meant to be cut"
+    rng = np.random.default_rng(47)
+    td = TD[dtype]
+    rows = [K_each] * (nparts - 1) + [K_last]
+    A = [draw(rng, (k, M), dtype) for k in rows]
+    B = [draw(rng, (k, N * batch), dtype, 0.05) for k in rows]
+    C0 = rng.standard_normal((batch, M, N)).astype(np.float32)
+    Ad, Bd = [dev(a, td) for a in A], [dev(b, td) for b in B]
+    scratch = torch.full((need // 4,), float("nan"), device="cuda")           # stale content must not matter
+    outs = []
+    for rep in range(2):
+        C = dev(C0)
+        zs.wgrad_parts_cut(st(), dtype, M, N, K_each, K_last, Ad, M, Bd, N * batch, C, N, batch, 0, N, M * N, scratch, need)
+        torch.cuda.synchronize()
+        outs.append(back(C))
+    assert np.array_equal(outs[0], outs[1]), "a repeat must give the same bits"
+    A64 = np.concatenate([a.astype(np.float64) for a in A])                    # [K, M]
+    B64 = np.concatenate([b.astype(np.float64) for b in B])                    # [K, N * batch]
+    pick_m = np.unique(np.concatenate([rng.integers(0, M, 24), [0, 255, 256, M - 257, M - 256, M - 1]]))
+    pick_n = np.unique(np.concatenate([rng.integers(0, N, 24), [0, 255, 256, N - 257, N - 256, N - 1]]))
+    worst = 0.0
+    for z in range(batch):
+        Bz = B64[:, z * N:(z + 1) * N]
+        want_rows = C0[z][pick_m] + A64[:, pick_m].T @ Bz                      # whole rows
+        want_cols = C0[z][:, pick_n] + A64.T @ Bz[:, pick_n]                   # whole columns
+        scale = max(np.abs(want_rows).max(), np.abs(want_cols).max())
+        worst = max(worst, np.abs(outs[0][z][pick_m] - want_rows).max() / scale, np.abs(outs[0][z][:, pick_n] - want_cols).max() / scale)
+    log_report(f"wgrad parts cut {shape} dtype={dtype}", [("C", worst)])
+    assert worst <= 2e-5
+    # the uncut product on the same kernel: same sums up to rounding order
+    C = dev(C0)
+    zs.wgrad_parts(st(), dtype, M, N, K_each, K_last, Ad, M, Bd, N * batch, C, N, batch, 0, N, M * N, 3)
+    assert rel_err(back(C), outs[0]) <= 2e-6
+    with pytest.raises(zs.StageError) as ei:
+        zs.wgrad_parts_cut(st(), dtype, M, N, K_each, K_last, Ad, M, Bd, N * batch, C, N, batch, 0, N, M * N, scratch, need - 1)
+    assert ei.value.code == zs.STAGE_ERR_WORKSPACE
+
+
 @pytest.mark.parametrize("impl", [1, 2, 3, 4])
 @pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_gemm_with_fused_rotation(gpu_device, dtype, impl):
