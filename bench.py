@@ -319,9 +319,30 @@ def gemm_scan():
     both(False), both(True)
     one = sorted(both(False) for _ in range(3))[1]
     two = sorted(both(True) for _ in range(3))[1]
+    del chain, wgrad
+    torch.cuda.empty_cache()
+
+    # (4) the weight gradients of a group of microbatches whose tiles do not fill whole rounds: as one K loop per tile
+    # (the last round on 128x128 tiles where the dispatcher chooses so), and with the last round's K range cut into chunks
+    def grouped(M, N, batch, parts):
+        A = [torch.randn(T, M, device=dev).to(torch.bfloat16) for _ in range(parts)]
+        B = [(torch.randn(T, N * batch, device=dev) * 0.02).to(torch.bfloat16) for _ in range(parts)]
+        C = torch.zeros(batch * M * N, device=dev)
+        need = zs.wgrad_parts_scratch_bytes(M, N, T, T, parts, batch)
+        ws = torch.empty(max(need, 256) // 4, device=dev)
+        uncut = lambda st: zs.wgrad_parts(st.cuda_stream, 1, M, N, T, T, A, M, B, N * batch, C, N, batch, 0, N, M * N, 2)
+        cut = lambda st: zs.wgrad_parts_cut(st.cuda_stream, 1, M, N, T, T, A, M, B, N * batch, C, N, batch, 0, N, M * N, ws, need)
+        tu, tc = us(uncut, 10, 3), us(cut, 10, 3)
+        flops = 2.0 * M * N * batch * T * parts
+        return {"M": M, "N": N, "batch": batch, "parts": parts, "tiles": batch * ((M + 255) // 256) * ((N + 255) // 256),
+                "scratch_MiB": need >> 20, "uncut_us": round(tu, 0), "cut_us": round(tc, 0),
+                "uncut_tflops": round(flops / tu / 1e6, 0), "cut_tflops": round(flops / tc / 1e6, 0)}
+
+    cuts = [grouped(F, H, 1, 8), grouped(H, F, 2, 8), grouped(F, H, 1, 4), grouped(H, H, 3, 8)]
     print(json.dumps({"gemm_scan": {"time_against_K": k_scan, "time_against_tiles": rounds,
                                     "streams": {"one_stream_ms": round(one, 2), "two_streams_ms": round(two, 2),
-                                                "work": "40 x (4 dX products of a C3 layer) + 10 x (dWd over 8 microbatches)"}},
+                                                "work": "40 x (4 dX products of a C3 layer) + 10 x (dWd over 8 microbatches)"},
+                                    "last_round_cut_along_K": cuts},
                       "dtype": "bf16", "note": "M = N = 4096 for the K scan (256 tiles of 256x256: one round); least-squares line over "
                       "the four K; the tile scan forces the 256x256 tile"}))
 
