@@ -605,7 +605,7 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket launches with HIP events")
     ap.add_argument("--no-pair-wgrad", action="store_true",
                     help="every backward runs its own weight-gradient products (stage_config.pair_wgrad = 0)")
-    ap.add_argument("--wgrad-group", type=int, default=8, metavar="G",
+    ap.add_argument("--wgrad-group", type=int, default=16, metavar="G",
                     help="microbatches whose weight-gradient products share one K loop (stage_config.pair_wgrad = G, "
                          "at most 16 and at most the number of microbatches)")
     ap.add_argument("--graph", action="store_true",
