@@ -127,13 +127,13 @@ bool split_tail(DType dt, const Gemm& g, Gemm& head, Gemm& tail) {
 }
 
 // ---- K range of the last round's tiles cut into chunks -------------------------------------------------------------
-// A multi-part product whose 256x256 tiles do not fill whole rounds of 256 workgroups is cut in two along N (whole tile
-// columns) or along M (whole tile rows): the leading tiles run as whole rounds, and the remaining `rem` tiles as one launch
-// of rem x nchunks workgroups, each multiplying chunk_parts of the parts.  Chunk 0 adds to C; the other chunks leave
-// partial tiles in scratch, which add_partials_kernel adds to C in the order of the chunks.
+// A multi-part product whose 256x256 tiles do not fill whole rounds of 256 workgroups runs as two launches of the same
+// kernel over ranges of its tile order (counted over all batches): the leading tiles, whole rounds, as they are, and the
+// remaining `rem` tiles as rem x nchunks workgroups, each multiplying chunk_parts of the parts.  Chunk 0 adds to C; the
+// other chunks leave partial tiles in scratch, which add_partials_kernel adds to C in the order of the chunks.
 struct KCut {
   Gemm head, tail;
-  int rem = 0;              // tiles of the cut-off part (over all batches)
+  int rem = 0;              // tiles of the cut-off range
   int64_t ws_need = 0;      // bytes of partial tiles
 };
 
@@ -150,31 +150,16 @@ double kcut_fixup_parts(int rem, int nch, int kseg) {
   return bytes / 4.0e12 / kcut_part_seconds(kseg);
 }
 
-bool plan_kcut(const Gemm& g, KCut& k) {
+bool plan_kcut(DType dt, const Gemm& g, KCut& k) {
   if (!g.nx || !g.c_f32_accum || !g.transA || g.transB || g.kseg < 1) return false;
   const int64_t tm = cdiv(g.M, 256), tn = cdiv(g.N, 256), tiles = tm * tn * g.batch, rem = tiles % 256;
-  if (tiles < 256 || rem == 0) return false;
-  k.head = g; k.tail = g;
-  k.head.ws = nullptr; k.head.ws_bytes = 0;
-  const double fx = kcut_round_fixed_parts(g.kseg);
-  double t_now = (double)(g.nx + 1) + fx;                             // a whole round
-  if (rem % (tm * g.batch) == 0) {                                    // whole tile columns
-    const int64_t n1 = (tn - rem / (tm * g.batch)) * 256;
-    k.head.N = (int)n1; k.tail.N = g.N - (int)n1;
-    k.tail.C = (char*)g.C + n1 * 4;
-    k.tail.B = (const char*)g.B + n1 * 2;
-    for (int p = 0; p < g.nx; ++p) k.tail.Bx[p] = (const char*)g.Bx[p] + n1 * 2;
-    if (rem <= 128) t_now = small_rounds(cdiv(g.M, 128) * cdiv(k.tail.N, 128) * g.batch) * (g.nx + 1 + fx);   // what split_tail would do
-  } else if (rem % (tn * g.batch) == 0) {                             // whole tile rows (A is stored [K, M])
-    const int64_t m1 = (tm - rem / (tn * g.batch)) * 256;
-    k.head.M = (int)m1; k.tail.M = g.M - (int)m1;
-    k.tail.C = (char*)g.C + m1 * g.ldc * 4;
-    k.tail.A = (const char*)g.A + m1 * 2;
-    for (int p = 0; p < g.nx; ++p) k.tail.Ax[p] = (const char*)g.Ax[p] + m1 * 2;
-  } else {
-    return false;
-  }
+  if (tiles < 256 || rem == 0 || tiles >= (1ll << 30)) return false;
   const int parts = g.nx + 1;
+  const double fx = kcut_round_fixed_parts(g.kseg);
+  double t_now = (double)parts + fx;                                  // a whole round
+  Gemm h2, t2;
+  if (split_tail(dt, g, h2, t2))                                      // today's other way: the rest on 128x128 tiles
+    t_now = std::min(t_now, small_rounds(cdiv(t2.M, 128) * tile_cols(t2, 128) * t2.batch) * (parts + fx));
   double best = t_now * 0.97;                                         // a cut has to win at least 3 %
   int best_cp = 0;
   for (int cp = 1; cp < parts; ++cp) {
@@ -185,6 +170,10 @@ bool plan_kcut(const Gemm& g, KCut& k) {
   }
   if (!best_cp) return false;
   k.rem = (int)rem;
+  k.head = g; k.tail = g;
+  k.head.ws = nullptr; k.head.ws_bytes = 0; k.head.chunk_parts = 0; k.head.nchunks = 1;
+  k.head.tile_base = 0; k.head.tile_count = (int)(tiles - rem);
+  k.tail.tile_base = (int)(tiles - rem); k.tail.tile_count = (int)rem;
   k.tail.chunk_parts = best_cp;
   k.tail.nchunks = (int)cdiv(parts, best_cp);
   k.ws_need = (int64_t)(k.tail.nchunks - 1) * rem * 256 * 256 * 4;
@@ -192,14 +181,17 @@ bool plan_kcut(const Gemm& g, KCut& k) {
 }
 
 // C tile += partial tile of chunk 1, then of chunk 2, ...: one workgroup per quarter tile (64 rows), 16 bytes per lane.
-__global__ __launch_bounds__(256) void add_partials_kernel(float* C, int64_t ldc, int64_t sC, int M, int N, int tiles_n,
-                                                           const float* __restrict__ partial, int nadd) {
-  const int t = blockIdx.x >> 2, quarter = blockIdx.x & 3, z = blockIdx.y;
-  const int64_t tiles = gridDim.x >> 2, batch = gridDim.y;
-  const int m0 = (t / tiles_n) * 256 + quarter * 64, n0 = (t % tiles_n) * 256;
-  float* Cz = C + (int64_t)z * sC;
-  const float* P0 = partial + ((int64_t)z * tiles + t) * 65536 + quarter * 64 * 256;
-  const int64_t chunk_stride = batch * tiles * 65536;
+// Tile `idx` of the range is position tile_base + idx of the tile order.
+__global__ __launch_bounds__(256) void add_partials_kernel(float* C, int64_t ldc, int64_t sC, int M, int N, int tiles_m, int tiles_n,
+                                                           int tile_base, int tile_count, const float* __restrict__ partial, int nadd) {
+  const int idx = blockIdx.x >> 2, quarter = blockIdx.x & 3;
+  const int pos = tile_base + idx, ntiles = tiles_m * tiles_n;
+  int tm, tn;
+  gemm_tile_of(pos % ntiles, tiles_m, tiles_n, tm, tn);
+  const int m0 = tm * 256 + quarter * 64, n0 = tn * 256;
+  float* Cz = C + (int64_t)(pos / ntiles) * sC;
+  const float* P0 = partial + (int64_t)idx * 65536 + quarter * 64 * 256;
+  const int64_t chunk_stride = (int64_t)tile_count * 65536;
 #pragma unroll 4
   for (int v = threadIdx.x; v < 64 * 64; v += 256) {
     const int r = v >> 6, c = (v & 63) * 4;
@@ -215,23 +207,21 @@ __global__ __launch_bounds__(256) void add_partials_kernel(float* C, int64_t ldc
 
 int64_t gemm_mfma_ws_bytes(const Gemm& g) {
   KCut k;
-  return (!g_force_tile && plan_kcut(g, k)) ? k.ws_need : 0;
+  return (!g_force_tile && plan_kcut(BF16, g, k)) ? k.ws_need : 0;
 }
 
 hipError_t gemm_mfma(hipStream_t st, DType dt, const Gemm& g) {
   const bool small = gemm_mfma_pick_tile(g) == 2;
   if (g.ws && !g_force_tile) {
     KCut k;
-    if (plan_kcut(g, k) && k.ws_need <= g.ws_bytes && ((uintptr_t)g.ws & 15) == 0 && gemm_mfma_supported(dt, k.head) &&
-        gemm_mfma_supported(dt, k.tail)) {
+    if (plan_kcut(dt, g, k) && k.ws_need <= g.ws_bytes && ((uintptr_t)g.ws & 15) == 0 && gemm_mfma_supported(dt, g)) {
       hipError_t e = run_tile(st, dt, k.head, false);
       if (e != hipSuccess) return e;
       e = run_tile(st, dt, k.tail, false);
       if (e != hipSuccess) return e;
-      const int tiles = (int)(cdiv(k.tail.M, 256) * cdiv(k.tail.N, 256));
-      hipLaunchKernelGGL(add_partials_kernel, dim3((unsigned)(tiles * 4), (unsigned)k.tail.batch), dim3(256), 0, st,
-                         (float*)k.tail.C, k.tail.ldc, k.tail.sC, k.tail.M, k.tail.N, (int)cdiv(k.tail.N, 256),
-                         (const float*)g.ws, k.tail.nchunks - 1);
+      hipLaunchKernelGGL(add_partials_kernel, dim3((unsigned)(k.rem * 4)), dim3(256), 0, st, (float*)g.C, g.ldc, g.sC, g.M, g.N,
+                         (int)cdiv(g.M, 256), (int)cdiv(g.N, 256), k.tail.tile_base, k.tail.tile_count, (const float*)g.ws,
+                         k.tail.nchunks - 1);
       return hipGetLastError();
     }
   }

@@ -132,13 +132,10 @@ __device__ __forceinline__ void tile_origin(int pid, int tiles_m, int tiles_n, i
   const int ntiles = tiles_m * tiles_n;
   const int per = ntiles / 8;                             // ids [0, 8*per) are remapped, the rest stay
   if (pid < per * 8) pid = (pid % 8) * per + pid / 8;
-  constexpr int GROUP = 8;
-  const int width = GROUP * tiles_n;
-  const int group_id = pid / width;
-  const int first_m = group_id * GROUP;
-  const int gsz = min(tiles_m - first_m, GROUP);
-  m0 = (first_m + (pid % width) % gsz) * BM;
-  n0 = ((pid % width) / gsz) * BN;
+  int tm, tn;
+  gemm_tile_of(pid, tiles_m, tiles_n, tm, tn);
+  m0 = tm * BM;
+  n0 = tn * BN;
 }
 
 // Both epilogues pass the tile through LDS (free after the K loop) as fp32, in two halves of BM/2 rows.
@@ -378,10 +375,22 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
   extern __shared__ __align__(16) char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);        // [2 buffers][A slab | B slab]
 
-  int m0, n0;
-  tile_origin<BM, BN>(blockIdx.x, tiles_m, tiles_n, m0, n0);
-
-  const int z = blockIdx.y;
+  // A launch of a cut product (multi-part K, fp32 accumulation) covers tile_count positions of the tile order from tile_base
+  // on, counted over all batches; its ids are dealt to the XCDs like those of a whole grid.
+  int m0, n0, z = blockIdx.y, sub = 0;                    // sub: position inside the launch's range
+  if (SEG && TA == 1 && TB == 0 && ACC && g.tile_count > 0) {
+    const int per = g.tile_count / 8;
+    sub = blockIdx.x;
+    if (sub < per * 8) sub = (sub % 8) * per + sub / 8;
+    const int pos = g.tile_base + sub, ntiles = tiles_m * tiles_n;
+    int tm, tn;
+    gemm_tile_of(pos % ntiles, tiles_m, tiles_n, tm, tn);
+    z = pos / ntiles;
+    m0 = tm * BM;
+    n0 = tn * BN;
+  } else {
+    tile_origin<BM, BN>(blockIdx.x, tiles_m, tiles_n, m0, n0);
+  }
   const bf16* A = (const bf16*)g.A + (int64_t)z * g.sA;
   const bf16* B = (const bf16*)g.B + (int64_t)z * g.sB;
 
@@ -563,8 +572,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BM * BN <= 128 * 128) ? 2 : 1)
       float* Ct = (float*)g.C + (int64_t)z * g.sC + (int64_t)m0 * g.ldc + n0;
       epilogue_accum<BM, BN, NT, MI, NJ>(Ct, (int)g.ldc, min(BM, g.M - m0), min(BN, g.N - n0), false, acc, wave / WN, wn, tid,
                                          reinterpret_cast<float*>(smem_raw));
-    } else {   // partial tile number ((chunk-1) * batch + z) * tiles + tile, tiles counted row by row
-      const int64_t slot = ((int64_t)(chunk - 1) * gridDim.y + z) * gridDim.x + (m0 / BM) * tiles_n + n0 / BN;
+    } else {   // partial tile number (chunk-1) * tile_count + position inside the launch's range
+      const int64_t slot = (int64_t)(chunk - 1) * g.tile_count + sub;
       epilogue_accum<BM, BN, NT, MI, NJ>((float*)g.ws + slot * (BM * BN), BN, BM, BN, true, acc, wave / WN, wn, tid,
                                          reinterpret_cast<float*>(smem_raw));
     }
@@ -584,8 +593,10 @@ hipError_t launch2(hipStream_t st, const Gemm& g) {
     configured = true;
   }
   const int tiles_m = (int)cdiv(g.M, BM), tiles_n = (int)cdiv(g.N, GLU == 1 ? BN / 2 : BN);   // a gate|up tile holds BN/2 columns of each
-  const bool chunks = SEG && TA == 1 && TB == 0 && ACC && g.chunk_parts > 0 && g.nchunks > 1;
-  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)g.batch, chunks ? (unsigned)g.nchunks : 1u), blk(64 * NW);
+  const bool range = SEG && TA == 1 && TB == 0 && ACC && g.tile_count > 0;   // part of a cut product
+  const bool chunks = range && g.chunk_parts > 0 && g.nchunks > 1;
+  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)g.batch), blk(64 * NW);
+  if (range) grid = dim3((unsigned)g.tile_count, 1u, chunks ? (unsigned)g.nchunks : 1u);
   hipLaunchKernelGGL(kern, grid, blk, SMEM_BYTES, st, g, tiles_m, tiles_n);
   return hipGetLastError();
 }

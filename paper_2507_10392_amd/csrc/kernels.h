@@ -18,7 +18,8 @@ namespace zs {
 //             strides); parts 0..nx-1 have kseg rows each, the last one the remaining K - nx*kseg > 0 rows:
 //             C += sum_p A_p^T B_p in one K loop (weight gradients of several microbatches).
 //   ws != NULL (nx > 0 only): ws_bytes of scratch that the MFMA path may use when the 256x256 tiles of the product do
-//             not fill whole rounds of 256 workgroups: the tiles of the last, partly filled round then have their K
+//             not fill whole rounds of 256 workgroups: the tiles beyond the whole rounds (the last ones of the kernel's
+//             tile order, over all batches) then have their K
 //             range cut into chunks of whole parts that run side by side, chunk 0 adding to C and the others writing
 //             partial tiles into ws, which a second kernel adds to C in the order of the chunks.  The result differs
 //             from the uncut product in rounding order only and is the same on every call.
@@ -48,10 +49,20 @@ struct Gemm {
   int kseg = 0; int64_t segB = 0;
   int nx = 0; const void* Ax[GEMM_MAX_PARTS - 1] = {}; const void* Bx[GEMM_MAX_PARTS - 1] = {};
   void* ws = nullptr; int64_t ws_bytes = 0;
-  int chunk_parts = 0, nchunks = 1;   // set by gemm_mfma for the launch that runs the chunks, not by callers
+  // set by gemm_mfma for the launches of a product that is cut, not by callers: the launch covers tiles
+  // tile_base .. tile_base + tile_count - 1 of the order gemm_tile_of (over all batches), each in nchunks chunks of chunk_parts parts
+  int chunk_parts = 0, nchunks = 1, tile_base = 0, tile_count = 0;
   const float2* rope = nullptr; int rope_S = 0, rope_d = 0, rope_batches = 0;
   int glu = 0; void* gu = nullptr; int64_t gu_ld = 0, gu_up = 0;
 };
+// Position `pos` of the MFMA kernels' tile order -> tile row and column: the order walks groups of 8 tile rows column by
+// column, so that tiles which run at the same time share A rows and B columns.
+__host__ __device__ inline void gemm_tile_of(int pos, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int width = 8 * tiles_n, first = (pos / width) * 8;
+  const int gsz = tiles_m - first < 8 ? tiles_m - first : 8;
+  tm = first + (pos % width) % gsz;
+  tn = (pos % width) / gsz;
+}
 enum GemmImpl { GEMM_AUTO = 0, GEMM_SIMPLE = 1, GEMM_MFMA = 2 };
 // Returns which implementation a call with these arguments runs (GEMM_SIMPLE or GEMM_MFMA).
 int gemm_select(DType dt, const Gemm& g, int force);

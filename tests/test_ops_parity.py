@@ -484,11 +484,12 @@ def test_weight_gradient_of_several_microbatches(gpu_device, dtype, impl, shape)
     assert err <= 2e-5
 
 
-# (M, N, K_each, K_last, parts, batch): grids of 272 tiles of 256x256, i.e. one round of 256 workgroups and 16 tiles more,
-# which make up one tile row (first two cases: the cut runs along M; the last tile row is ragged in the second) or one
-# three tile columns of two batches (third case: along N, ragged columns, eight chunks).
+# (M, N, K_each, K_last, parts, batch): grids of 256x256 tiles that fill one round of 256 workgroups and leave 16 tiles (one
+# tile row: first two cases, ragged in the second), 96 (three tile columns of two batches: third case) or 14 (no whole row
+# or column, ragged both ways; in the last case the 14 tiles lie in the second batch).
 @pytest.mark.parametrize("dtype", [1, 2])
-@pytest.mark.parametrize("shape", [(4352, 4096, 128, 128, 4, 1), (4344, 4088, 256, 72, 5, 1), (4096, 2808, 1536, 1000, 8, 2)])
+@pytest.mark.parametrize("shape", [(4352, 4096, 128, 128, 4, 1), (4344, 4088, 256, 72, 5, 1), (4096, 2808, 1536, 1000, 8, 2),
+                                   (4600, 3832, 128, 128, 4, 1), (2304, 3832, 256, 200, 5, 2)])
 def test_weight_gradient_with_the_last_round_cut_along_k(gpu_device, dtype, shape):
     """stage_op_wgrad_parts_cut: the tiles beyond whole rounds of workgroups have their K range cut into chunks whose partial
     tiles a second kernel adds to C.  Against float64 on whole rows and columns that cross both regions; two calls give the
