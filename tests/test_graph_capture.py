@@ -18,9 +18,18 @@ from workloads.configs import DTYPE_BF16
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["C1", "C3t"])
+def wide_cut_config():
+    """A one-layer stage wide enough for its grouped weight gradients to leave partly filled rounds of 256x256 tiles
+    (Wd: 33 x 8 = 264 tiles), so that the launches of the cut K range and the kernel that adds the partial tiles are
+    captured as well."""
+    cfg = get_config("C3t").with_(layers=1, hidden=2048, heads=16, ffn=8448, seq=256, num_microbatches=4, pair_wgrad=4)
+    assert zs.wgrad_parts_scratch_bytes(cfg.ffn, cfg.hidden, cfg.tokens, cfg.tokens, 4, 1) > 0
+    return cfg
+
+
+@pytest.mark.parametrize("name", ["C1", "C3t", "wide-cut"])
 def test_microbatch_loop_replays_from_a_graph(gpu_device, name):
-    cfg = get_config(name)
+    cfg = wide_cut_config() if name == "wide-cut" else get_config(name)
     print(f"[case] graph capture {name}", flush=True)
     inp = make_inputs(cfg, perturbed=True)
     M, T, H = cfg.num_microbatches, cfg.tokens, cfg.hidden
