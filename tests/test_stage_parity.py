@@ -3,6 +3,8 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2507_10392_amd as zs
+
 from harness import TOL, GpuStage, compare_optimizer, compare_step, log_report, oracle_step
 from workloads import get_config, make_inputs
 
@@ -68,6 +70,25 @@ def test_paired_weight_gradients_match_oracle(gpu_device, name, M, group):
     log_report(f"paired wgrad {name} M={M} group={group}", sorted(rep, key=lambda r: -r[1])[:6])
     res = g.step(1)
     compare_optimizer(cfg, inp, g.shard, gpu["grad"], res, ora["grad"], TOL[cfg.dtype])
+    g.stage.close()
+
+
+@pytest.mark.parametrize("dtype", [1, 2])
+def test_grouped_weight_gradients_with_cut_rounds_match_oracle(gpu_device, dtype):
+    """A one-layer stage wide enough (hidden 2048, FFN 8448: 264 and 528 tiles of 256x256) for the grouped weight gradients of
+    Wd and Wg to leave partly filled rounds: those tiles' K range is cut over the 4 microbatches, partial tiles go through
+    scratch and are added in a fixed order.  Everything against the oracle, as for the uncut products."""
+    cfg = get_config("C3t").with_(layers=1, hidden=2048, heads=16, ffn=8448, seq=256, num_microbatches=4, pair_wgrad=4, dtype=dtype)
+    print(f"[case] grouped wgrad with cut rounds, dtype={dtype}", flush=True)
+    assert zs.wgrad_parts_scratch_bytes(cfg.ffn, cfg.hidden, cfg.tokens, cfg.tokens, 4, 1) > 0
+    assert zs.wgrad_parts_scratch_bytes(cfg.hidden, cfg.ffn, cfg.tokens, cfg.tokens, 4, 2) > 0
+    inp = make_inputs(cfg, perturbed=True)
+    g = GpuStage(cfg, inp)
+    gpu = g.run_microbatches(inp)
+    ora = oracle_step(cfg, inp)
+    rep = []
+    compare_step(cfg, gpu, ora, TOL[cfg.dtype], rep)
+    log_report(f"grouped wgrad with cut rounds dtype={dtype}", sorted(rep, key=lambda r: -r[1])[:6])
     g.stage.close()
 
 
